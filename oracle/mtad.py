@@ -1,0 +1,277 @@
+"""Oracle of one MTAD / MMTAD iteration and of the decoding loop.
+
+TEST INFRASTRUCTURE (see the package header).  Steps follow Algorithm 1 of the paper
+(appendix "Pseudocode of MTAD") and Section 3.3 for the multi-candidate variant, with
+these readings of what the paper leaves open or misprints:
+
+  * Algorithm 1 initialises eta to -1 and later sets it to the token id; read as: eta = 0
+    when nothing passes (the bonus token then comes from the first row of P, so at least
+    one token is produced, Section 3.2 item (3)) and eta = i for the longest passing prefix.
+  * MTAD passes a prefix when min(1, p/q) > tau (strict, Section 3.2 and Algorithm 1);
+    MMTAD passes a node when p/q** >= tau (Eq. 9).  tau = 0 is legal and passes everything.
+  * All prefixes are examined: a failing prefix does not stop longer ones from passing.
+  * q is the raw (unwarped) joint likelihood the beam search stored (Section 2.1).
+  * Deterministic beam search keeps the b best candidates (last sentence of Section 2.1);
+    ties go to the lowest flat index beam*V + token; survivors are listed best first.
+    Stochastic beam sampling draws b distinct candidates in proportion to p_beam (Eq. 2)
+    by adding Gumbel noise to the joint log-likelihoods (the normaliser of Eq. 2 is common
+    to all candidates of a step and cannot change the order).
+  * x** is the final-step beam with the largest stored likelihood (Section 3.3); the
+    denominator for a depth-i node is the likelihood stored at x**'s depth-i ancestor.
+  * MMTAD judges every node on its own ratio; the longest passing node wins, ties go to the
+    highest target likelihood (Section 3.3), then to the lowest row.
+  * The bonus token is drawn from the target row of the accepted node (the root row when
+    eta = 0), as argmax(logit + Gumbel noise) keyed by the token's absolute position, or as
+    plain argmax in deterministic mode.
+
+Decisions (top-b, thresholds, argmax) are taken in `dt`, float64 by default; tests that
+compare integer decisions with the float32 kernels pass dt=np.float32 so that both sides
+decide in the same precision.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import rng
+
+
+def log_softmax_rows(logits):
+    """Row-wise log-softmax; returns (log-probabilities, logsumexp per row)."""
+    m = logits.max(axis=-1, keepdims=True)
+    lse = m[..., 0] + np.log(np.exp(logits - m).sum(axis=-1))
+    return logits - lse[..., None], lse
+
+
+def perplexity(logp_tokens):
+    """Eq. 1: exp of the mean negative log-likelihood of the generated tokens."""
+    return float(np.exp(-np.mean(np.asarray(logp_tokens, dtype=np.float64))))
+
+
+def top_b(keys, b):
+    """Indices of the b largest keys, best first; equal keys: lowest index first."""
+    keys = np.asarray(keys)
+    order = np.lexsort((np.arange(keys.size), -keys))
+    return order[:b]
+
+
+# ---- draft: beam sampling on the auxiliary model (Section 2.1, Eq. 2) --------------------
+
+def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=np.float64):
+    """gamma beam steps from the session's context.  Returns a history dict with, per step
+    i and survivor j: tok[i][j], parent[i][j] (index of the beam it extends in step i-1; 0 at
+    step 0 where the only beam is the context), score[i][j] = log q(branch | context), and
+    node[i][j] = the session node id (only for steps whose survivors were run, i < gamma-1)."""
+    V = None
+    rows, _ = session.tree_logits([], [])
+    live_rows = rows[:1]
+    live_score = np.zeros(1, dtype=dt)
+    live_node = [-1]
+    n0 = len(session.context)
+    hist = {"tok": [], "parent": [], "score": [], "node": [], "margin": []}
+    for i in range(gamma):
+        logits = live_rows.astype(dt)
+        V = logits.shape[1]
+        _, lse = log_softmax_rows(live_rows)
+        cand = live_score[:, None] + (logits - lse.astype(dt)[:, None])      # joint log q of every extension
+        flat = cand.ravel()
+        if stochastic:
+            g = rng.gumbel(seed, rng.stream_id(seq_index, rng.STREAM_BEAM), n0 + i, np.arange(flat.size))
+            key = flat + g.astype(dt)
+        else:
+            key = flat
+        k = min(b, flat.size)                    # a step has fewer than b candidates only if b > |V| (tests)
+        sel = top_b(key, k + 1)
+        margin = float(key[sel[k - 1]] - key[sel[k]]) if len(sel) > k else np.inf
+        sel = sel[:k]
+        parent, tok = sel // V, sel % V
+        score = flat[sel]
+        pad = b - k
+        hist["tok"].append(np.concatenate([tok, -np.ones(pad)]).astype(np.int32))
+        hist["parent"].append(np.concatenate([parent, -np.ones(pad)]).astype(np.int32))
+        hist["score"].append(np.concatenate([score, np.full(pad, -np.inf)]).astype(dt))
+        hist["margin"].append(margin)
+        if i < gamma - 1:
+            rows, ids = session.tree_logits([live_node[p] for p in parent], tok)
+            live_rows, live_node, live_score = rows[1:], ids, score
+            hist["node"].append(list(ids) + [-1] * pad)
+        else:
+            hist["node"].append([-1] * b)
+    for k in ("tok", "parent", "score"):
+        hist[k] = np.stack(hist[k])
+    return hist
+
+
+def output_beam(hist):
+    """x**: the final-step beam with the highest stored likelihood; returns the beam index
+    at every depth (back-traced through the parents), its tokens and q_i = q(x**_{1:i})."""
+    gamma = hist["tok"].shape[0]
+    j = int(np.argmax(hist["score"][gamma - 1]))
+    beams = [0] * gamma
+    for i in range(gamma - 1, -1, -1):
+        beams[i] = j
+        j = int(hist["parent"][i][j])
+    toks = [int(hist["tok"][i][beams[i]]) for i in range(gamma)]
+    q = np.array([hist["score"][i][beams[i]] for i in range(gamma)])
+    return beams, toks, q
+
+
+def build_tree(hist, mode):
+    """Rows of the target pass.  Row 0 is the root (the last context token).  MTAD: the chain
+    of x**.  MMTAD: every survivor of every step, row 1 + i*b + j for step i, beam j."""
+    gamma, b = hist["tok"].shape
+    beams, toks, q = output_beam(hist)
+    tok, parent, depth, src = [-1], [-1], [0], [-1]
+    if mode == "mtad":
+        for i in range(gamma):
+            tok.append(toks[i]); parent.append(i); depth.append(i + 1); src.append(beams[i])
+    elif mode == "mmtad":
+        for i in range(gamma):
+            for j in range(b):
+                tok.append(int(hist["tok"][i][j]))
+                parent.append(0 if i == 0 else 1 + (i - 1) * b + int(hist["parent"][i][j]))
+                depth.append(i + 1); src.append(j)
+    else:
+        raise ValueError(mode)
+    return {"tok": np.array(tok, np.int32), "parent": np.array(parent, np.int32),
+            "depth": np.array(depth, np.int32), "src_beam": np.array(src, np.int32),
+            "qref": q, "out_beams": beams}
+
+
+def ancestor_masks(parent):
+    """Bit j of mask[r] is set iff row j is r itself or an ancestor of r (the tree attention mask)."""
+    masks = []
+    for r in range(len(parent)):
+        m, j = 0, r
+        while j >= 0:
+            m |= 1 << j
+            j = int(parent[j])
+        masks.append(m)
+    return np.array(masks, dtype=np.uint64)
+
+
+# ---- verification by the target model (Algorithm 1, P = M_p(input, X); Section 3.3) -------
+
+def verify(session, tree):
+    """Target logits after the root and after every tree node, the conditional log-likelihood
+    of every node's token given its branch, and the joint log p of every branch."""
+    M = len(tree["tok"])
+    base = len(session.node_tok)                 # row r >= 1 becomes session node base + r - 1
+    rows, ids = session.tree_logits([-1 if p == 0 else base + int(p) - 1 for p in tree["parent"][1:]],
+                                    tree["tok"][1:])
+    logp, lse = log_softmax_rows(rows)
+    cond = np.zeros(M)
+    joint = np.zeros(M)
+    for c in range(1, M):
+        p = int(tree["parent"][c])
+        cond[c] = logp[p, tree["tok"][c]]
+        joint[c] = joint[p] + cond[c]
+    return {"logits": rows, "lse": lse, "logp_cond": cond, "logp_joint": joint, "node_ids": [-1] + list(ids)}
+
+
+def joint_from_cond(tree, cond, dt=np.float64):
+    """Joint log-likelihood of every branch: conditionals summed from the root down."""
+    M = len(tree["tok"])
+    joint = np.zeros(M, dtype=dt)
+    cond = np.asarray(cond, dtype=dt)
+    for c in range(1, M):
+        joint[c] = joint[int(tree["parent"][c])] + cond[c]
+    return joint
+
+
+def _log_tau(tau, dt):
+    with np.errstate(divide="ignore"):
+        return np.log(dt(tau)).astype(dt) if tau > 0 else dt(-np.inf)
+
+
+def accept_mtad(tree, joint, tau, dt=np.float64):
+    """Longest prefix i of the chain with min(1, p_i/q_i) > tau; eta = 0 if none."""
+    log_tau = _log_tau(tau, dt)
+    qref = np.asarray(tree["qref"], dtype=dt)
+    joint = np.asarray(joint, dtype=dt)
+    eta, node, margins = 0, 0, []
+    for c in range(1, len(tree["tok"])):
+        i = int(tree["depth"][c])
+        ratio = min(dt(0), joint[c] - qref[i - 1])          # log min(1, p/q)
+        margins.append(abs(float(joint[c] - qref[i - 1]) - float(log_tau)))
+        if ratio > log_tau:
+            eta, node = i, c                                  # all prefixes are examined; the longest wins
+    return eta, node, margins
+
+
+def accept_mmtad(tree, joint, tau, dt=np.float64):
+    """Node (i, j) passes iff p(x^(j)_{1:i}) / q(x**_{1:i}) >= tau; longest, then highest p, then lowest row."""
+    log_tau = _log_tau(tau, dt)
+    qref = np.asarray(tree["qref"], dtype=dt)
+    joint = np.asarray(joint, dtype=dt)
+    best, margins = (0, -np.inf, 0), []
+    for c in range(1, len(tree["tok"])):
+        i = int(tree["depth"][c])
+        margins.append(abs(float(joint[c] - qref[i - 1]) - float(log_tau)))
+        if joint[c] - qref[i - 1] >= log_tau:
+            if i > best[0] or (i == best[0] and joint[c] > best[1]):
+                best = (i, joint[c], c)
+    return best[0], best[2], margins
+
+
+def branch_rows(tree, node):
+    """Rows on the branch from the first level down to `node` (empty for the root)."""
+    out = []
+    while node > 0:
+        out.append(int(node))
+        node = int(tree["parent"][node])
+    return out[::-1]
+
+
+def bonus_token(logits_row, *, sample, seed=0, seq_index=0, position=0, dt=np.float64):
+    """t ~ P_{eta+1}: argmax(logit + Gumbel) (a draw from softmax(logits)); plain argmax if not sampling.
+    Returns (token, gap between the best and second-best key)."""
+    key = np.asarray(logits_row).astype(dt)
+    if sample:
+        g = rng.gumbel(seed, rng.stream_id(seq_index, rng.STREAM_BONUS), position, np.arange(key.size))
+        key = key + g.astype(dt)
+    t = int(np.argmax(key))
+    rest = np.delete(key, t)
+    return t, float(key[t] - rest.max()) if rest.size else np.inf
+
+
+# ---- one iteration and the loop -------------------------------------------------------------
+
+def iteration(sq, sp, *, gamma, beam, mode, tau, stochastic_beam=False, sample_bonus=True, seed=0,
+              seq_index=0, dt=np.float64):
+    """One iteration on draft session sq and target session sp (both hold the same context).
+    Returns a trace; both sessions end with the context extended by [x_1..x_eta, t]."""
+    assert sq.context == sp.context
+    n = len(sp.context)
+    hist = beam_search(sq, gamma, beam, stochastic=stochastic_beam, seed=seed, seq_index=seq_index, dt=dt)
+    tree = build_tree(hist, mode)
+    ver = verify(sp, tree)
+    joint = joint_from_cond(tree, ver["logp_cond"].astype(dt), dt)
+    eta, node, margins = (accept_mtad if mode == "mtad" else accept_mmtad)(tree, joint, tau, dt)
+    rows = branch_rows(tree, node)
+    t, gap = bonus_token(ver["logits"][node], sample=sample_bonus, seed=seed, seq_index=seq_index,
+                         position=n + eta, dt=dt)
+    accepted = [int(tree["tok"][r]) for r in rows]
+    sp.commit(ver["node_ids"][node] if node > 0 else None, [t])
+    # the draft never ran its final-step tokens: commit what it has, hand over the rest as context
+    keep = min(eta, gamma - 1)
+    dnode = None
+    if keep > 0:
+        r = rows[keep - 1]
+        dnode = hist["node"][keep - 1][int(tree["src_beam"][r])]
+    sq.commit(dnode, accepted[keep:] + [t])
+    return {"hist": hist, "tree": tree, "verify": ver, "joint": joint, "eta": eta, "node": node,
+            "path_rows": rows, "bonus": t, "bonus_gap": gap, "accept_margins": margins,
+            "emitted": accepted + [t], "n_before": n}
+
+
+def generate(make_sq, make_sp, prompt, new_tokens, **kw):
+    """Decoding loop (Section 2.2 step 4 applied to MTAD): iterate until new_tokens tokens
+    exist; the surplus of the last iteration is cut.  make_sq / make_sp build a session from
+    a context.  Returns (tokens, traces)."""
+    sq, sp = make_sq(list(prompt)), make_sp(list(prompt))
+    out, traces = [], []
+    while len(out) < new_tokens:
+        tr = iteration(sq, sp, **kw)
+        out += tr["emitted"]
+        traces.append(tr)
+    return out[:new_tokens], traces

@@ -1,0 +1,333 @@
+"""Pins for oracle.mtad: beam sampling, verification, acceptance, bonus token, loop.
+
+Toy models are explicit conditional tables over tiny vocabularies, so that every
+gamma-token sequence can be enumerated (the joint distribution has |V|^gamma entries,
+Section 3.2) and each rule can be re-evaluated in the probability domain, the form the
+paper states it in."""
+import itertools
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import synth_inputs as si
+from oracle import mtad
+from oracle.lm import CachedSession, DecoderLM, RecomputeSession, TableSession
+
+
+def table_lm(V, seed, temp=1.0):
+    """Next-token log-probabilities that depend on the whole history (hash of the sequence)."""
+    def fn(seq):
+        g = np.random.default_rng([seed, len(seq)] + [int(t) for t in seq])
+        logits = g.normal(size=V) * temp
+        return logits - np.log(np.exp(logits).sum())
+    return fn
+
+
+def joint_logprob(fn, ctx, seq):
+    lp, cur = 0.0, tuple(ctx)
+    for t in seq:
+        lp += fn(cur)[t]
+        cur += (t,)
+    return lp
+
+
+# ---- beam sampling (Section 2.1) -----------------------------------------------------------
+
+def test_wide_beam_finds_the_most_likely_sequence_by_enumeration():
+    V, gamma = 6, 3
+    fn = table_lm(V, 1, temp=2.0)
+    ctx = (2, 4)
+    hist = mtad.beam_search(TableSession(fn, ctx), gamma, V ** (gamma - 1))
+    _, toks, q = mtad.output_beam(hist)
+    allseq = list(itertools.product(range(V), repeat=gamma))
+    scores = np.array([joint_logprob(fn, ctx, s) for s in allseq])
+    best = allseq[int(np.argmax(scores))]
+    assert tuple(toks) == best
+    assert np.isclose(q[-1], scores.max())
+    # the b final survivors are exactly the b best sequences, best first
+    b = V ** (gamma - 1)
+    want = np.sort(scores)[::-1][:b]
+    assert np.allclose(hist["score"][-1], want)
+    # stored prefix likelihoods are the joint likelihoods of the prefixes (Eq. 2 numerator)
+    for i in range(gamma):
+        assert np.isclose(q[i], joint_logprob(fn, ctx, toks[:i + 1]))
+
+
+def test_width_one_beam_is_greedy_decoding():
+    V, gamma = 7, 5
+    fn = table_lm(V, 2)
+    hist = mtad.beam_search(TableSession(fn, (1,)), gamma, 1)
+    cur, want = (1,), []
+    for _ in range(gamma):
+        t = int(np.argmax(fn(cur)))
+        want.append(t); cur += (t,)
+    assert list(hist["tok"][:, 0]) == want
+
+
+def test_beam_scores_and_parents_are_consistent_joint_likelihoods():
+    V, gamma, b = 5, 4, 3
+    fn = table_lm(V, 3)
+    hist = mtad.beam_search(TableSession(fn, (0, 1)), gamma, b)
+    for i in range(gamma):
+        assert np.all(np.diff(hist["score"][i]) <= 0)            # listed best first
+        for j in range(b):
+            seq, jj = [], j
+            for k in range(i, -1, -1):
+                seq.append(int(hist["tok"][k][jj])); jj = int(hist["parent"][k][jj])
+            assert np.isclose(hist["score"][i][j], joint_logprob(fn, (0, 1), seq[::-1]))
+
+
+def test_topb_ties_go_to_lowest_flat_index():
+    assert list(mtad.top_b(np.array([1.0, 3.0, 3.0, 0.0, 3.0]), 2)) == [1, 2]
+
+
+def test_stochastic_width_one_is_ancestral_sampling():
+    V, gamma = 3, 2
+    fn = table_lm(V, 4)
+    ctx = (1,)
+    allseq = list(itertools.product(range(V), repeat=gamma))
+    p = np.exp([joint_logprob(fn, ctx, s) for s in allseq])
+    n = 6000
+    counts = np.zeros(len(allseq))
+    for seed in range(n):
+        hist = mtad.beam_search(TableSession(fn, ctx), gamma, 1, stochastic=True, seed=seed)
+        counts[allseq.index(tuple(int(t) for t in hist["tok"][:, 0]))] += 1
+    assert stats.chisquare(counts, p / p.sum() * n).pvalue > 1e-4
+
+
+def test_stochastic_beam_first_draw_follows_p_beam_and_draws_are_distinct():
+    V, b = 4, 3
+    fn = table_lm(V, 5)
+    p = np.exp(fn((0,)))
+    n = 6000
+    counts = np.zeros(V)
+    for seed in range(n):
+        hist = mtad.beam_search(TableSession(fn, (0,)), 1, b, stochastic=True, seed=seed)
+        toks = list(hist["tok"][0])
+        assert len(set(toks)) == b
+        counts[toks[0]] += 1
+    assert stats.chisquare(counts, p * n).pvalue > 1e-4
+
+
+# ---- verification (Section 3.3: one pass gives every node's conditional likelihood) -------------
+
+def test_tree_verification_equals_branchwise_enumeration():
+    V, gamma, b = 5, 3, 3
+    fq, fp = table_lm(V, 6), table_lm(V, 7)
+    ctx = (3, 1)
+    hist = mtad.beam_search(TableSession(fq, ctx), gamma, b)
+    for mode in ("mtad", "mmtad"):
+        tree = mtad.build_tree(hist, mode)
+        ver = mtad.verify(TableSession(fp, ctx), tree)
+        assert np.allclose(np.exp(ver["logits"] - ver["lse"][:, None]).sum(axis=1), 1.0)
+        for c in range(1, len(tree["tok"])):
+            branch = [int(tree["tok"][r]) for r in mtad.branch_rows(tree, c)]
+            assert len(branch) == tree["depth"][c]
+            assert np.isclose(ver["logp_joint"][c], joint_logprob(fp, ctx, branch))
+        assert len(tree["tok"]) == 1 + (gamma if mode == "mtad" else gamma * b)
+
+
+def test_tree_rows_and_masks():
+    hist = {"tok": np.array([[5, 6], [7, 8]]), "parent": np.array([[0, 0], [1, 1]]),
+            "score": np.array([[-1.0, -2.0], [-3.0, -2.5]])}
+    tree = mtad.build_tree(hist, "mmtad")
+    assert list(tree["parent"]) == [-1, 0, 0, 2, 2] and list(tree["depth"]) == [0, 1, 1, 2, 2]
+    assert list(mtad.ancestor_masks(tree["parent"])) == [0b1, 0b11, 0b101, 0b1101, 0b10101]
+    # x** = final beam 1 (score -2.5), which extends step-0 beam 1
+    assert tree["out_beams"] == [1, 1] and list(tree["qref"]) == [-2.0, -2.5]
+    chain = mtad.build_tree(hist, "mtad")
+    assert list(chain["tok"]) == [-1, 6, 8] and list(chain["parent"]) == [-1, 0, 1]
+
+
+# ---- acceptance (Section 3.2, Algorithm 1; Section 3.3 Eq. 9) -----------------------------------
+
+def _prob_domain_mtad(p, q, tau):
+    eta = 0
+    for i in range(len(p)):
+        if min(1.0, np.prod(p[:i + 1]) / q[i]) > tau:
+            eta = i + 1
+    return eta
+
+
+@pytest.mark.parametrize("tau", [0.0, 0.1, 0.3, 0.5, 0.9])
+def test_mtad_accept_matches_probability_domain_rule_exhaustively(tau):
+    # conditional target probabilities and joint draft probabilities on a grid: every outcome pattern occurs
+    grid = [0.053, 0.21, 0.49, 0.87]          # generic values: no ratio lands exactly on a threshold
+    gamma = 3
+    tree = {"tok": np.arange(gamma + 1), "parent": np.arange(-1, gamma), "depth": np.arange(gamma + 1)}
+    seen = set()
+    for pc in itertools.product(grid, repeat=gamma):
+        for qc in itertools.product(grid, repeat=gamma):
+            q = np.cumprod(qc)
+            tree["qref"] = np.log(q)
+            joint = mtad.joint_from_cond(tree, np.log([1.0] + list(pc)))
+            eta, node, _ = mtad.accept_mtad(tree, joint, tau)
+            assert eta == _prob_domain_mtad(np.array(pc), q, tau) and node == eta
+            seen.add(eta)
+    assert seen == ({gamma} if tau == 0 else set(range(gamma + 1)))
+
+
+def test_a_failing_prefix_does_not_block_a_longer_one():
+    tree = {"tok": np.arange(4), "parent": np.arange(-1, 3), "depth": np.arange(4),
+            "qref": np.log([0.5, 0.25, 0.1])}
+    joint = np.log([1.0, 0.4, 0.01, 0.09])       # ratios 0.8, 0.04, 0.9
+    assert mtad.accept_mtad(tree, joint, 0.3)[0] == 3
+    assert mtad.accept_mtad(tree, np.log([1.0, 0.4, 0.01, 0.001]), 0.3)[0] == 1
+
+
+def test_exact_tie_is_strict_for_the_chain_rule_and_inclusive_for_the_tree_rule():
+    # Algorithm 1 tests tau < min(1, p/q); Eq. 9 tests p/q** >= tau
+    tree = {"tok": np.arange(2), "parent": np.array([-1, 0]), "depth": np.array([0, 1]), "qref": np.log([0.5])}
+    joint = np.array([0.0, np.log(0.25)])
+    assert joint[1] - tree["qref"][0] == np.log(0.5)
+    assert mtad.accept_mtad(tree, joint, 0.5)[0] == 0
+    assert mtad.accept_mmtad(tree, joint, 0.5)[0] == 1
+
+
+def test_identical_models_accept_everything_for_every_tau():
+    V, gamma, b = 6, 4, 3
+    fn = table_lm(V, 8)
+    for tau in (0.0, 0.3, 0.9, 0.999999):
+        for mode in ("mtad", "mmtad"):
+            sq, sp = TableSession(fn, (1, 2)), TableSession(fn, (1, 2))
+            tr = mtad.iteration(sq, sp, gamma=gamma, beam=b, mode=mode, tau=tau, sample_bonus=False)
+            assert tr["eta"] == gamma and len(tr["emitted"]) == gamma + 1
+            assert sq.context == sp.context == [1, 2] + tr["emitted"]
+
+
+def test_tau_zero_accepts_all_and_overconfident_draft_accepts_none():
+    V, gamma = 5, 3
+    fq, fp = table_lm(V, 9, temp=4.0), table_lm(V, 10, temp=0.01)     # target ~ uniform, draft peaked
+    tr = mtad.iteration(TableSession(fq, (0,)), TableSession(fp, (0,)), gamma=gamma, beam=2, mode="mtad",
+                        tau=0.0, sample_bonus=False)
+    assert tr["eta"] == gamma
+    tr = mtad.iteration(TableSession(fq, (0,)), TableSession(fp, (0,)), gamma=gamma, beam=2, mode="mtad",
+                        tau=0.999, sample_bonus=False)
+    assert tr["eta"] == 0 and len(tr["emitted"]) == 1
+    assert tr["emitted"][0] == int(np.argmax(fp((0,))))               # bonus token from the first row of P
+
+
+def test_accepted_length_bound_of_theorem_3_6():
+    # |log p - log q| <= U for every conditional  =>  every prefix of length <= |log tau| / U passes
+    V, gamma, U = 6, 6, 0.2
+    fp = table_lm(V, 11)
+
+    def fq(seq):
+        g = np.random.default_rng([77, len(seq)] + [int(t) for t in seq])
+        shifted = fp(seq) + g.uniform(-U / 2, U / 2, V)                # renormalising moves each entry by <= U/2 more
+        return shifted - np.log(np.exp(shifted).sum())
+    for tau in (0.3, 0.5, 0.7):
+        for ctx in ((0,), (1, 2), (3, 3, 3)):
+            tr = mtad.iteration(TableSession(fq, ctx), TableSession(fp, ctx), gamma=gamma, beam=2, mode="mtad",
+                                tau=tau, sample_bonus=False)
+            assert tr["eta"] >= min(gamma, int(np.floor(abs(np.log(tau)) / U)))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_tree_accepts_at_least_as_long_as_chain_theorem_3_7(seed):
+    V, gamma, b = 5, 4, 3
+    fq, fp = table_lm(V, 20 + seed, temp=1.5), table_lm(V, 40 + seed, temp=0.7)
+    ctx = (seed % V,)
+    hist = mtad.beam_search(TableSession(fq, ctx), gamma, b)
+    for tau in (0.05, 0.1, 0.3, 0.5):
+        res = {}
+        for mode in ("mtad", "mmtad"):
+            tree = mtad.build_tree(hist, mode)
+            ver = mtad.verify(TableSession(fp, ctx), tree)
+            acc = mtad.accept_mtad if mode == "mtad" else mtad.accept_mmtad
+            res[mode] = acc(tree, ver["logp_joint"], tau) + (tree, ver)
+        assert res["mmtad"][0] >= res["mtad"][0]
+        # on x** itself both rules see the same ratio (same numerator and denominator)
+        tree, ver = res["mmtad"][3], res["mmtad"][4]
+        chain, cver = res["mtad"][3], res["mtad"][4]
+        for i in range(gamma):
+            row = 1 + i * b + tree["out_beams"][i]
+            assert tree["tok"][row] == chain["tok"][i + 1]
+            assert np.isclose(ver["logp_joint"][row], cver["logp_joint"][i + 1])
+
+
+def test_mmtad_selection_longest_then_most_likely_by_enumeration():
+    g = np.random.default_rng(0)
+    gamma, b = 3, 3
+    parent = [-1, 0, 0, 0] + [1 + int(g.integers(b)) for _ in range(b)] + [4 + int(g.integers(b)) for _ in range(b)]
+    tree = {"tok": np.arange(10), "parent": np.array(parent), "depth": np.array([0] + [1] * 3 + [2] * 3 + [3] * 3)}
+    for trial in range(300):
+        cond = np.log(g.uniform(0.02, 1.0, 10)); cond[0] = 0.0
+        tree["qref"] = np.log(np.sort(g.uniform(0.01, 1.0, gamma))[::-1])
+        tau = float(g.choice([0.1, 0.3, 0.5, 0.9]))
+        joint = mtad.joint_from_cond(tree, cond)
+        eta, node, _ = mtad.accept_mmtad(tree, joint, tau)
+        # definition in the probability domain
+        P = np.exp(joint)
+        ok = [c for c in range(1, 10) if P[c] / np.exp(tree["qref"][tree["depth"][c] - 1]) >= tau]
+        if not ok:
+            assert (eta, node) == (0, 0)
+            continue
+        deepest = max(tree["depth"][c] for c in ok)
+        want = max((c for c in ok if tree["depth"][c] == deepest), key=lambda c: (P[c], -c))
+        assert (eta, node) == (deepest, want)
+
+
+# ---- bonus token and loop -------------------------------------------------------------------
+
+def test_bonus_token_follows_target_row():
+    logits = np.array([1.0, 0.0, -0.5, 2.2])
+    p = np.exp(logits) / np.exp(logits).sum()
+    n = 20000
+    counts = np.zeros(4)
+    for pos in range(n):
+        counts[mtad.bonus_token(logits, sample=True, seed=3, position=pos)[0]] += 1
+    assert stats.chisquare(counts, p * n).pvalue > 1e-4
+    assert mtad.bonus_token(logits, sample=False)[0] == 3
+
+
+def test_loop_lengths_and_accept_invariant():
+    V, gamma, b, N = 8, 4, 3, 40
+    fq, fp = table_lm(V, 60, temp=1.2), table_lm(V, 61, temp=1.0)
+    for mode, tau in (("mtad", 0.3), ("mmtad", 0.3), ("mtad", 0.05)):
+        toks, traces = mtad.generate(lambda c: TableSession(fq, c), lambda c: TableSession(fp, c), [1, 2, 3], N,
+                                     gamma=gamma, beam=b, mode=mode, tau=tau, seed=5)
+        assert len(toks) == N
+        flat = [t for tr in traces for t in tr["emitted"]]
+        assert flat[:N] == toks
+        for tr in traces:
+            assert 1 <= len(tr["emitted"]) <= gamma + 1 and len(tr["emitted"]) == tr["eta"] + 1
+            if tr["eta"]:                                       # premise of Lemma A.1: accepted prefix has p/q >= tau
+                i = tr["eta"]
+                assert tr["joint"][tr["node"]] - tr["tree"]["qref"][i - 1] >= np.log(tau) - 1e-12
+        assert any(tr["eta"] > 0 for tr in traces)
+
+
+def test_identical_transformers_greedy_draft_reproduce_greedy_decoding():
+    """draft == target, width-1 deterministic beam, argmax bonus: every iteration emits the
+    gamma+1 greedy tokens, so the loop must reproduce plain greedy decoding (cache commit included)."""
+    shape = si.ModelShape(2, 32, 4, 2, 8, 48, 40, "fp32")
+    w = si.make_weights(shape, 3, "target", threads=1)
+    lm = DecoderLM(shape, w)
+    prompt, N = [5, 9, 1], 11
+    want, cur = [], list(prompt)
+    for _ in range(N):
+        t = int(np.argmax(lm.logits_full(cur)[-1]))
+        want.append(t); cur.append(t)
+    for mode in ("mtad", "mmtad"):
+        got, traces = mtad.generate(lambda c: CachedSession(lm, c), lambda c: CachedSession(lm, c), prompt, N,
+                                    gamma=3, beam=1, mode=mode, tau=0.5, sample_bonus=False)
+        assert got == want and all(tr["eta"] == 3 for tr in traces)
+
+
+def test_cached_and_recompute_sessions_give_the_same_run():
+    st, sd = si.ModelShape(2, 32, 4, 2, 8, 48, 40, "bf16"), si.ModelShape(1, 16, 2, 2, 8, 24, 40, "bf16")
+    lp = DecoderLM(st, si.make_weights(st, 1, "target", threads=1))
+    lq = DecoderLM(sd, si.make_weights(sd, 1, "draft", threads=1))
+    kw = dict(gamma=3, beam=2, mode="mmtad", tau=0.0, seed=2)
+    a, ta = mtad.generate(lambda c: CachedSession(lq, c), lambda c: CachedSession(lp, c), [1, 2, 3, 4], 9, **kw)
+    b, tb = mtad.generate(lambda c: RecomputeSession(lq, c), lambda c: RecomputeSession(lp, c), [1, 2, 3, 4], 9, **kw)
+    assert a == b
+    for x, y in zip(ta, tb):
+        assert np.allclose(x["verify"]["logits"], y["verify"]["logits"], atol=1e-9)
+        assert np.allclose(x["hist"]["score"], y["hist"]["score"], atol=1e-9)
+
+
+def test_perplexity_eq1():
+    assert np.isclose(mtad.perplexity(np.log([0.5, 0.25, 0.5])), (0.5 * 0.25 * 0.5) ** (-1 / 3))
