@@ -1,0 +1,41 @@
+/*
+ * mtad_kernels.h - component entry points of libmtad: single kernels of the hot path, exported so that each
+ * can be checked and timed on its own at the real shapes.  Same conventions as mtad.h (device pointers are
+ * borrowed, work is only enqueued on `stream`, status codes of mtad_status).
+ */
+#ifndef MTAD_KERNELS_H
+#define MTAD_KERNELS_H
+
+#include "mtad.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* The few-row matrix product of every projection, FFN matrix and the lm_head of a pass (the weight stream the
+ * paper's cost argument is about, Section 4: time and energy are dominated by reading the weights once per run).
+ * Y[r][n] (+)= sum_k X[r][k] * W[n][k], r < R.  dtype 1: W, X bfloat16, float32 accumulation (N % 16 == 0,
+ * K % 32 == 0, R <= 256); dtype 0: all float32 (K % 4 == 0).  Y float32 [R][ldy], ldy >= N, ldy % 4 == 0.
+ * accumulate != 0 adds to Y (the residual connection). */
+int mtad_k_gemm(int32_t dtype, const void *W, const void *X, float *Y, int32_t R, int32_t N, int32_t K, int32_t ldy,
+                int32_t accumulate, void *stream);
+
+/* out[row][i] = h[row][i] / sqrt(mean_i h[row][i]^2 + eps) * g[i]; out is bfloat16 (dtype 1) or float32 (dtype 0). */
+int mtad_k_rmsnorm(int32_t dtype, const float *h, const float *g, void *out, int32_t rows, int32_t d, float eps,
+                   void *stream);
+
+/* lse[row] = log sum_v exp(logits[row][v]) (the normaliser that turns a logits row into a row of P, Algorithm 1). */
+int mtad_k_row_lse(const float *logits, float *lse, int32_t rows, int32_t vocab, void *stream);
+
+/* The selection part of one beam step (Section 2.1, Eq. 2) on given draft logits [batch][rows_per_seq][vocab] and
+ * their row logsumexps: candidate (r, v) scores hist.cum_logq[step-1][r] + (logits[r][v] - lse[r]) (at step 0 the
+ * only live beam is row catchup_cnt-1 with score 0); writes hist[.][step][.].  `len` = committed draft tokens per
+ * sequence (only keys the sampling noise).  Needs a context with a bound workspace. */
+int mtad_k_beam_topb(mtad_ctx *ctx, const float *logits, const float *lse, mtad_beam *hist, int32_t step,
+                     const int32_t *catchup_cnt, const int32_t *len, int32_t rows_per_seq, int32_t vocab,
+                     int32_t sample_beam, uint64_t seed, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTAD_KERNELS_H */

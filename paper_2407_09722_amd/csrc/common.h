@@ -1,0 +1,67 @@
+// Internal declarations shared by the kernel files and the C-ABI layer of libmtad.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mtad {
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// float32 -> bfloat16, round to nearest even (NaN not expected on this path)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float round_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
+
+// Device status bits (sticky, OR-ed by kernels that refuse an out-of-range access)
+enum : uint32_t { ST_KV_CAP = 1u, ST_SPEC_WINDOW = 2u, ST_BAD_CATCHUP = 4u };
+
+// Paged KV addressing: element offset of (layer, logical position pos, kv head 0, dim 0)
+struct KvView {
+  void* k;
+  void* v;
+  const int32_t* page_table;  // [B][max_pages]
+  int32_t* len;               // [B]
+  int32_t page_size, max_pages, n_pages;
+  int32_t n_kv_heads, head_dim;
+  int64_t layer_stride;  // elements per layer = n_pages*page_size*n_kv_heads*head_dim
+};
+
+__device__ __forceinline__ int64_t kv_token_offset(const KvView& kv, int seq, int pos) {
+  int page = kv.page_table[(int64_t)seq * kv.max_pages + pos / kv.page_size];
+  return ((int64_t)page * kv.page_size + pos % kv.page_size) * kv.n_kv_heads * kv.head_dim;
+}
+__device__ __forceinline__ int kv_capacity(const KvView& kv) { return kv.page_size * kv.max_pages; }
+
+// Row descriptors of one pass (R rows per sequence, B sequences), device arrays in the workspace
+struct RowDesc {
+  int32_t* tok;    // [B*R] token id of the row
+  int32_t* pos;    // [B*R] rotary position
+  int32_t* slot;   // [B*R] logical KV position the row's K/V are written to, -1 = inactive row
+  uint64_t* mask;  // [B*R] visible speculative slots: bit j <=> logical position len+j
+  int32_t* nspec;  // [B]   speculative slots in use after this pass (keys len .. len+nspec-1 exist)
+};
+
+// ---- launchers (kernels_*.hip) ----------------------------------------------------------------
+// Y[r][n] (+)= sum_k X[r][k] * W[n][k];  X: bf16 [R][K] (dtype 1) or f32 (dtype 0); W likewise [N][K]; Y f32 [R][ldy]
+hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate,
+                       hipStream_t s);
+hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, hipStream_t s);
+// out = rmsnorm(h) * g, written as bf16 (dtype 1) or f32 (dtype 0)
+hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s);
+hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s);
+// rotate q (in place in qkv, rounded to storage precision), rotate k and write k, v to the cache
+hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
+                          int n_heads, uint32_t* status, hipStream_t s);
+hipError_t launch_attention(int dtype, const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
+                            float* partial, int n_splits, void* out, hipStream_t s);
+hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int rows, int f, hipStream_t s);
+hipError_t launch_row_lse(const float* logits, float* lse, int rows, int vocab, hipStream_t s);
+
+size_t attention_partial_floats(int B, int R, int n_heads, int head_dim, int n_splits);
+
+}  // namespace mtad

@@ -1,0 +1,241 @@
+// Tree-masked paged attention for the rows of one pass (Section 3.3: tree attention gives every tree
+// token its conditional likelihood in one pass).  Every row sees the whole committed cache of its
+// sequence plus the speculative rows named in its ancestor mask.
+//
+// Split-KV "flash decoding": grid = (key split, head x row chunk, sequence).  A workgroup stages 64-key
+// K and V tiles in LDS once and reuses them for its (up to 16) query rows, keeps running max / sum /
+// output per row, and writes one partial per split; a second kernel merges the partials in a fixed
+// order.  Everything is float32 arithmetic; K/V are read in their storage type.
+#include "common.h"
+
+namespace mtad {
+
+constexpr int RB = 16;  // query rows per workgroup
+
+template <typename T, int HD>
+struct AttnCfg {
+  static constexpr int TK = (sizeof(T) == 4 && HD == 128) ? 32 : 64;  // keys per tile (LDS budget)
+  static constexpr int KSTRIDE = (sizeof(T) == 2) ? HD + 2 : HD + 1;  // odd dword stride: no bank conflicts
+};
+
+__device__ __forceinline__ float wsum(float v) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wmax(float v) {
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict__ qkv, RowDesc rd, KvView kv, int layer, int R,
+                                                        int n_heads, int n_chunks, float scale, float* __restrict__ partial,
+                                                        int n_splits) {
+  using C = AttnCfg<T, HD>;
+  constexpr int TK = C::TK, KS = C::KSTRIDE;
+  constexpr int NRG = 256 / TK, RPT = RB / NRG;    // score phase: row groups, rows per thread
+  constexpr int NRG2 = 256 / HD, RPT2 = RB / NRG2;  // PV phase
+
+  __shared__ float q_s[RB][HD];
+  __shared__ T k_s[TK * KS];
+  __shared__ __attribute__((aligned(16))) T v_s[TK * HD];
+  __shared__ float s_s[RB][TK];
+  __shared__ float m_s[RB], l_s[RB], a_s[RB];
+  __shared__ unsigned long long mask_s[RB];
+
+  const int split = blockIdx.x;
+  const int head = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
+  const int seq = blockIdx.z;
+  const int t = threadIdx.x;
+  const int row0 = chunk * RB;                     // first row (within the sequence) of this chunk
+  const int nrows = min(RB, R - row0);
+  const int KVH = kv.n_kv_heads;
+  const int g = head * KVH / n_heads;
+  const int width = (n_heads + 2 * KVH) * HD;
+  const int len = kv.len[seq];
+  int nspec = rd.nspec[seq];
+  nspec = max(0, min(nspec, 64));
+  const int cap = kv_capacity(kv);
+  const int ktot = min(len + nspec, cap);
+
+  // queries of this chunk and head
+  for (int i = t; i < RB * HD; i += 256) {
+    const int r = i / HD, d = i % HD;
+    q_s[r][d] = (r < nrows) ? qkv[(int64_t)(seq * R + row0 + r) * width + (int64_t)head * HD + d] : 0.f;
+  }
+  if (t < RB) {
+    m_s[t] = -INFINITY;
+    l_s[t] = 0.f;
+    a_s[t] = 0.f;
+    mask_s[t] = (t < nrows) ? rd.mask[seq * R + row0 + t] : 0ull;
+  }
+  float acc[RPT2];
+#pragma unroll
+  for (int i = 0; i < RPT2; ++i) acc[i] = 0.f;
+
+  int per = (ktot + n_splits - 1) / n_splits;
+  per = ((per + TK - 1) / TK) * TK;
+  const int kbeg = split * per, kend = min(ktot, kbeg + per);
+
+  const T* kbase = (const T*)kv.k + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
+  const T* vbase = (const T*)kv.v + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
+  constexpr int EPC = 16 / sizeof(T);  // elements per 16-byte chunk
+  constexpr int CPK = HD / EPC;        // chunks per key
+
+  for (int tile = kbeg; tile < kend; tile += TK) {
+    __syncthreads();  // previous tile fully consumed (and q_s / stats initialised on the first pass)
+    for (int c = t; c < TK * CPK; c += 256) {
+      const int j = c / CPK, e = (c % CPK) * EPC;
+      const int kj = tile + j;
+      uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (kj < kend) {
+        const int64_t off = kv_token_offset(kv, seq, kj) + e;
+        kk = *(const uint4*)(kbase + off);
+        vv = *(const uint4*)(vbase + off);
+      }
+      uint32_t* kd = (uint32_t*)(k_s + j * KS + e);  // padded stride: 4-byte aligned only
+      kd[0] = kk.x; kd[1] = kk.y; kd[2] = kk.z; kd[3] = kk.w;
+      *(uint4*)(v_s + j * HD + e) = vv;
+    }
+    __syncthreads();
+
+    // scores: thread (key j, row group rg)
+    {
+      const int j = t % TK, rg = t / TK;
+      float sacc[RPT];
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) sacc[i] = 0.f;
+      const T* krow = k_s + j * KS;
+#pragma unroll 8
+      for (int d = 0; d < HD; d += 2) {
+        float k0, k1;
+        if constexpr (sizeof(T) == 2) {
+          const uint32_t w = *(const uint32_t*)(krow + d);
+          k0 = __uint_as_float(w << 16);
+          k1 = __uint_as_float(w & 0xFFFF0000u);
+        } else {
+          k0 = krow[d];
+          k1 = krow[d + 1];
+        }
+#pragma unroll
+        for (int i = 0; i < RPT; ++i) {
+          const float2 qq = *(const float2*)&q_s[rg + NRG * i][d];
+          sacc[i] = fmaf(qq.x, k0, sacc[i]);
+          sacc[i] = fmaf(qq.y, k1, sacc[i]);
+        }
+      }
+      const int kj = tile + j;
+#pragma unroll
+      for (int i = 0; i < RPT; ++i) {
+        const int r = rg + NRG * i;
+        bool vis = kj < kend;
+        if (vis && kj >= len) vis = (mask_s[r] >> (kj - len)) & 1ull;
+        s_s[r][j] = vis ? sacc[i] * scale : -INFINITY;
+      }
+    }
+    __syncthreads();
+
+    // running softmax statistics: wave w owns rows w, w+4, ...
+    {
+      const int lane = t & 63, w = t >> 6;
+      for (int r = w; r < RB; r += 4) {
+        const float s = (lane < TK) ? s_s[r][lane] : -INFINITY;
+        const float m_old = m_s[r];
+        const float m_new = fmaxf(m_old, wmax(s));
+        const float p = (s == -INFINITY) ? 0.f : expf(s - m_new);
+        const float alpha = (m_old == -INFINITY) ? 0.f : expf(m_old - m_new);
+        const float l_new = l_s[r] * alpha + wsum(p);
+        if (lane < TK) s_s[r][lane] = p;
+        if (lane == 0) {
+          m_s[r] = m_new;
+          l_s[r] = l_new;
+          a_s[r] = alpha;
+        }
+      }
+    }
+    __syncthreads();
+
+    // output accumulation: thread (dim d, row group rg2)
+    {
+      const int d = t % HD, rg2 = t / HD;
+#pragma unroll
+      for (int i = 0; i < RPT2; ++i) acc[i] *= a_s[rg2 + NRG2 * i];
+      for (int j = 0; j < TK; ++j) {
+        float v;
+        if constexpr (sizeof(T) == 2) v = bf16_to_f32(v_s[j * HD + d]);
+        else v = v_s[j * HD + d];
+#pragma unroll
+        for (int i = 0; i < RPT2; ++i) acc[i] = fmaf(s_s[rg2 + NRG2 * i][j], v, acc[i]);
+      }
+    }
+  }
+  __syncthreads();
+
+  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD])
+  {
+    const int d = t % HD, rg2 = t / HD;
+#pragma unroll
+    for (int i = 0; i < RPT2; ++i) {
+      const int r = rg2 + NRG2 * i;
+      if (r < nrows) {
+        float* p = partial + ((((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits + split) * (HD + 2);
+        p[2 + d] = acc[i];
+        if (d == 0) {
+          p[0] = m_s[r];
+          p[1] = l_s[r];
+        }
+      }
+    }
+  }
+}
+
+// grid (B*R, n_heads), block HD: merge the splits of one (row, head)
+template <typename T, int HD>
+__global__ void attn_combine_kernel(const float* __restrict__ partial, T* __restrict__ out, int R, int n_heads, int n_splits) {
+  const int row = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
+  const int seq = row / R, r = row % R;
+  const float* p = partial + (((int64_t)seq * n_heads + head) * R + r) * n_splits * (HD + 2);
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, p[(int64_t)s * (HD + 2)]);
+  float L = 0.f, o = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float m = p[(int64_t)s * (HD + 2)];
+    const float w = (m == -INFINITY) ? 0.f : expf(m - M);
+    L = fmaf(p[(int64_t)s * (HD + 2) + 1], w, L);
+    o = fmaf(p[(int64_t)s * (HD + 2) + 2 + d], w, o);
+  }
+  const float y = (L > 0.f) ? o / L : 0.f;
+  const int64_t idx = (int64_t)row * n_heads * HD + (int64_t)head * HD + d;
+  if constexpr (sizeof(T) == 2) out[idx] = f32_to_bf16(y);
+  else out[idx] = y;
+}
+
+size_t attention_partial_floats(int B, int R, int n_heads, int head_dim, int n_splits) {
+  return (size_t)B * R * n_heads * n_splits * (head_dim + 2);
+}
+
+template <typename T, int HD>
+static hipError_t run_attn(const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads, float* partial,
+                           int n_splits, void* out, hipStream_t s) {
+  const int n_chunks = (R + RB - 1) / RB;
+  const float scale = 1.0f / sqrtf((float)HD);
+  hipLaunchKernelGGL((tree_attn_kernel<T, HD>), dim3(n_splits, n_heads * n_chunks, B), dim3(256), 0, s, qkv, rd, kv, layer, R,
+                     n_heads, n_chunks, scale, partial, n_splits);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(B * R, n_heads), dim3(HD), 0, s, partial, (T*)out, R, n_heads, n_splits);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention(int dtype, const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
+                            float* partial, int n_splits, void* out, hipStream_t s) {
+  if (B * R <= 0) return hipSuccess;
+  const int hd = kv.head_dim;
+  if (dtype == 1 && hd == 128) return run_attn<bf16_t, 128>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
+  if (dtype == 1 && hd == 64) return run_attn<bf16_t, 64>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
+  if (dtype == 0 && hd == 128) return run_attn<float, 128>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
+  if (dtype == 0 && hd == 64) return run_attn<float, 64>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace mtad

@@ -1,0 +1,163 @@
+// Skinny matrix products Y[R][N] (+)= X[R][K] * W[N][K]^T for the few-row projections, FFN and
+// lm_head of the draft and target passes (the weight stream that dominates one target pass).
+//
+// bf16: the weight matrix is the A operand of v_mfma_f32_16x16x32_bf16 (16 output features x 32 k),
+// the activations are the B operand (32 k x 16 rows, rows beyond R are zero).  One workgroup owns 16
+// output features; its waves interleave over the 32-wide k blocks (wave w takes blocks w, w+WPB, ...),
+// so one iteration of the whole group reads WPB*64 contiguous bytes of each weight row, and every
+// lane keeps several 16-byte loads in flight.  Partial sums are reduced through LDS in a fixed order
+// (deterministic).  Memory bound: weights are read exactly once, activations come from L2.
+//
+// fp32 (the tiny all-float32 workload): one wave per output feature, plain FMA, shuffle reduction.
+#include "common.h"
+
+namespace mtad {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float floatx4;
+
+union Frag {
+  uint4 u;
+  bf16x8 v;
+};
+
+template <int MT, int WPB>
+__global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ X,
+                                                             float* __restrict__ Y, int R, int N, int K, int ldy,
+                                                             int accumulate) {
+  extern __shared__ float red[];  // [WPB][MT][64] float4
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n0 = blockIdx.x * 16;
+  const int r16 = lane & 15, kg = lane >> 4;
+  const int nkb = K >> 5;
+
+  floatx4 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const bf16_t* wp = W + (int64_t)(n0 + r16) * K + kg * 8;
+  const bf16_t* xp = X + (int64_t)r16 * K + kg * 8;
+  constexpr int U = (MT <= 2) ? 4 : 2;
+
+  int kb = wave;
+  for (; kb + (U - 1) * WPB < nkb; kb += U * WPB) {
+    Frag a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u].u = *(const uint4*)(wp + (int64_t)(kb + u * WPB) * 32);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        Frag b;
+        b.u = make_uint4(0, 0, 0, 0);
+        if (mt * 16 + r16 < R) b.u = *(const uint4*)(xp + (int64_t)mt * 16 * K + (int64_t)(kb + u * WPB) * 32);
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u].v, b.v, acc[mt], 0, 0, 0);
+      }
+    }
+  }
+  for (; kb < nkb; kb += WPB) {
+    Frag a;
+    a.u = *(const uint4*)(wp + (int64_t)kb * 32);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      Frag b;
+      b.u = make_uint4(0, 0, 0, 0);
+      if (mt * 16 + r16 < R) b.u = *(const uint4*)(xp + (int64_t)mt * 16 * K + (int64_t)kb * 32);
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[mt], 0, 0, 0);
+    }
+  }
+
+  floatx4* red4 = (floatx4*)red;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) red4[(wave * MT + mt) * 64 + lane] = acc[mt];
+  __syncthreads();
+  // D[i][j]: lane l, register i holds output feature n0 + (l/16)*4 + i of row (l%16)
+  for (int idx = threadIdx.x; idx < MT * 64; idx += WPB * 64) {
+    const int mt = idx >> 6, l = idx & 63;
+    floatx4 s = red4[mt * 64 + l];
+    for (int w = 1; w < WPB; ++w) {
+      floatx4 t = red4[(w * MT + mt) * 64 + l];
+      s[0] += t[0]; s[1] += t[1]; s[2] += t[2]; s[3] += t[3];
+    }
+    const int m = mt * 16 + (l & 15);
+    if (m < R) {
+      float4* y = (float4*)(Y + (int64_t)m * ldy + n0 + (l >> 4) * 4);
+      float4 o = make_float4(s[0], s[1], s[2], s[3]);
+      if (accumulate) {
+        float4 p = *y;
+        o.x += p.x; o.y += p.y; o.z += p.z; o.w += p.w;
+      }
+      *y = o;
+    }
+  }
+}
+
+template <int RB>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ W, const float* __restrict__ X,
+                                                       float* __restrict__ Y, int R, int N, int K, int ldy,
+                                                       int accumulate) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 4 + wave;
+  const int r0 = blockIdx.y * RB;
+  if (n >= N) return;
+  float acc[RB];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+  const float* wrow = W + (int64_t)n * K;
+  for (int k = lane * 4; k < K; k += 256) {
+    const float4 w = *(const float4*)(wrow + k);
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+      if (r0 + r < R) {
+        const float4 x = *(const float4*)(X + (int64_t)(r0 + r) * K + k);
+        acc[r] = fmaf(w.x, x.x, acc[r]);
+        acc[r] = fmaf(w.y, x.y, acc[r]);
+        acc[r] = fmaf(w.z, x.z, acc[r]);
+        acc[r] = fmaf(w.w, x.w, acc[r]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < RB; ++r) {
+    float v = acc[r];
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0 && r0 + r < R) {
+      float* y = Y + (int64_t)(r0 + r) * ldy + n;
+      *y = accumulate ? (*y + v) : v;
+    }
+  }
+}
+
+template <int MT, int WPB>
+static hipError_t run_bf16(const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool acc, hipStream_t s) {
+  const size_t lds = (size_t)WPB * MT * 64 * sizeof(float) * 4;
+  hipLaunchKernelGGL((gemm_bf16_kernel<MT, WPB>), dim3(N / 16), dim3(WPB * 64), lds, s, (const bf16_t*)W, (const bf16_t*)X, Y, R,
+                     N, K, ldy, acc ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate,
+                       hipStream_t s) {
+  if (R <= 0) return hipSuccess;
+  if (dtype == 0) {
+    if (K % 4) return hipErrorInvalidValue;
+    constexpr int RB = 8;
+    hipLaunchKernelGGL((gemm_f32_kernel<RB>), dim3((N + 3) / 4, (R + RB - 1) / RB), dim3(256), 0, s, (const float*)W,
+                       (const float*)X, Y, R, N, K, ldy, accumulate ? 1 : 0);
+    return hipGetLastError();
+  }
+  if ((N % 16) || (K % 32) || (ldy % 4) || R > 256) return hipErrorInvalidValue;
+  const int mt = (R + 15) / 16;
+  // few output tiles: more waves per tile so that every CU still has many loads in flight
+  const bool wide = (N / 16) >= 1024;
+  if (mt <= 1) return wide ? run_bf16<1, 8>(W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<1, 16>(W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 2) return wide ? run_bf16<2, 8>(W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<2, 16>(W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 3) return run_bf16<3, 8>(W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 4) return run_bf16<4, 8>(W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 6) return run_bf16<6, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 8) return run_bf16<8, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 12) return run_bf16<12, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
+  return run_bf16<16, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
+}
+
+}  // namespace mtad

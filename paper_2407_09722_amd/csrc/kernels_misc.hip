@@ -1,0 +1,196 @@
+// Row-wise pieces of the decoder pass: embedding gather, RMSNorm (wavefront reductions), the rotary
+// table, rotary + KV-cache write, SwiGLU gating and the row-wise logsumexp of the logits.
+// All of them move a few KB..MB per launch; they are latency bound, not bandwidth bound.
+#include "common.h"
+
+namespace mtad {
+
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// block-wide reductions for 256-thread blocks; every thread gets the result
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = sh[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) t += sh[w];
+  return t;
+}
+__device__ __forceinline__ float block_max(float v, float* sh) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = sh[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) t = fmaxf(t, sh[w]);
+  return t;
+}
+
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ h, int d, int vocab) {
+  const int row = blockIdx.x;
+  int t = tok[row];
+  if (t < 0 || t >= vocab) t = 0;  // inactive rows carry no meaningful token
+  const T* e = E + (int64_t)t * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    if constexpr (sizeof(T) == 2) h[(int64_t)row * d + i] = bf16_to_f32(e[i]);
+    else h[(int64_t)row * d + i] = e[i];
+  }
+}
+
+hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (dtype == 1) hipLaunchKernelGGL((embed_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t*)E, tok, h, d, vocab);
+  else hipLaunchKernelGGL((embed_kernel<float>), dim3(rows), dim3(256), 0, s, (const float*)E, tok, h, d, vocab);
+  return hipGetLastError();
+}
+
+// out[row][i] = h[row][i] / sqrt(mean(h[row]^2) + eps) * g[i]
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ h, const float* __restrict__ g, T* __restrict__ out,
+                                                      int d, float eps) {
+  __shared__ float sh[4];
+  const int row = blockIdx.x;
+  const float* x = h + (int64_t)row * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {
+    const float4 v = *(const float4*)(x + i);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = block_sum(ss, sh);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {
+    const float4 v = *(const float4*)(x + i);
+    const float4 gg = *(const float4*)(g + i);
+    const float o0 = v.x * inv * gg.x, o1 = v.y * inv * gg.y, o2 = v.z * inv * gg.z, o3 = v.w * inv * gg.w;
+    if constexpr (sizeof(T) == 2) {
+      ushort4 o = make_ushort4(f32_to_bf16(o0), f32_to_bf16(o1), f32_to_bf16(o2), f32_to_bf16(o3));
+      *(ushort4*)(out + (int64_t)row * d + i) = o;
+    } else {
+      *(float4*)(out + (int64_t)row * d + i) = make_float4(o0, o1, o2, o3);
+    }
+  }
+}
+
+hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (d % 4) return hipErrorInvalidValue;
+  if (dtype == 1) hipLaunchKernelGGL((rmsnorm_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, h, g, (bf16_t*)out, d, eps);
+  else hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(rows), dim3(256), 0, s, h, g, (float*)out, d, eps);
+  return hipGetLastError();
+}
+
+// table[row][i] = (cos, sin)(pos[row] * theta^(-2i/head_dim)), evaluated in double so that positions in
+// the thousands keep float32-exact angles
+__global__ void rope_table_kernel(const int32_t* __restrict__ pos, float2* __restrict__ table, int rows, int half, float theta) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows * half) return;
+  const int row = idx / half, i = idx % half;
+  const double inv_freq = pow((double)theta, -(double)i / (double)half);
+  const double ang = (double)pos[row] * inv_freq;
+  double sn, cs;
+  sincos(ang, &sn, &cs);
+  table[idx] = make_float2((float)cs, (float)sn);
+}
+
+hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  const int half = head_dim / 2, n = rows * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, pos, table, rows, half, theta);
+  return hipGetLastError();
+}
+
+// grid (rows, n_heads + 2*n_kv_heads), block head_dim/2.  q heads: rotated in place (rounded to the storage
+// precision, kept as float).  k heads: rotated and stored to the cache; v heads: stored to the cache.
+template <typename T>
+__global__ void rope_kv_kernel(float* __restrict__ qkv, const float2* __restrict__ table, RowDesc rd, KvView kv, int layer, int R,
+                               int n_heads, uint32_t* __restrict__ status) {
+  const int row = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
+  const int hd = kv.head_dim, half = hd >> 1, KVH = kv.n_kv_heads;
+  const int width = (n_heads + 2 * KVH) * hd;
+  float* p = qkv + (int64_t)row * width + (int64_t)head * hd;
+  const float x1 = p[i], x2 = p[i + half];
+  const float2 cs = table[(int64_t)row * half + i];
+  if (head < n_heads) {
+    float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
+    if constexpr (sizeof(T) == 2) { y1 = round_bf16(y1); y2 = round_bf16(y2); }
+    p[i] = y1;
+    p[i + half] = y2;
+    return;
+  }
+  const int slot = rd.slot[row];
+  if (slot < 0) return;
+  if (slot >= kv_capacity(kv)) {
+    if (i == 0) atomicOr(status, (uint32_t)ST_KV_CAP);
+    return;
+  }
+  const int seq = row / R;
+  const bool is_k = head < n_heads + KVH;
+  const int g = is_k ? head - n_heads : head - n_heads - KVH;
+  const int64_t off = (int64_t)layer * kv.layer_stride + kv_token_offset(kv, seq, slot) + (int64_t)g * hd;
+  T* dst = (T*)(is_k ? kv.k : kv.v) + off;
+  float y1 = x1, y2 = x2;
+  if (is_k) { y1 = x1 * cs.x - x2 * cs.y; y2 = x2 * cs.x + x1 * cs.y; }
+  if constexpr (sizeof(T) == 2) { dst[i] = f32_to_bf16(y1); dst[i + half] = f32_to_bf16(y2); }
+  else { dst[i] = y1; dst[i + half] = y2; }
+}
+
+hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
+                          int n_heads, uint32_t* status, hipStream_t s) {
+  const int rows = B * R;
+  if (rows <= 0) return hipSuccess;
+  dim3 grid(rows, n_heads + 2 * kv.n_kv_heads), block(kv.head_dim / 2);
+  if (dtype == 1) hipLaunchKernelGGL((rope_kv_kernel<bf16_t>), grid, block, 0, s, qkv, table, rd, kv, layer, R, n_heads, status);
+  else hipLaunchKernelGGL((rope_kv_kernel<float>), grid, block, 0, s, qkv, table, rd, kv, layer, R, n_heads, status);
+  return hipGetLastError();
+}
+
+// act[row][j] = silu(gu[row][j]) * gu[row][f + j]
+template <typename T>
+__global__ void silu_mul_kernel(const float* __restrict__ gu, T* __restrict__ act, int rows, int f) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)rows * f) return;
+  const int row = (int)(idx / f), j = (int)(idx % f);
+  const float g = gu[(int64_t)row * 2 * f + j], u = gu[(int64_t)row * 2 * f + f + j];
+  const float a = g / (1.0f + expf(-g)) * u;
+  if constexpr (sizeof(T) == 2) act[idx] = f32_to_bf16(a);
+  else act[idx] = a;
+}
+
+hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int rows, int f, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  const int64_t n = (int64_t)rows * f;
+  const int blocks = (int)((n + 255) / 256);
+  if (dtype == 1) hipLaunchKernelGGL((silu_mul_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, gu, (bf16_t*)act, rows, f);
+  else hipLaunchKernelGGL((silu_mul_kernel<float>), dim3(blocks), dim3(256), 0, s, gu, (float*)act, rows, f);
+  return hipGetLastError();
+}
+
+// lse[row] = log(sum_v exp(logits[row][v])), max-shifted; one block per row
+__global__ __launch_bounds__(256) void row_lse_kernel(const float* __restrict__ logits, float* __restrict__ lse, int vocab) {
+  __shared__ float sh[4];
+  const float* x = logits + (int64_t)blockIdx.x * vocab;
+  float m = -INFINITY;
+  for (int i = threadIdx.x; i < vocab; i += 256) m = fmaxf(m, x[i]);
+  m = block_max(m, sh);
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < vocab; i += 256) sum += expf(x[i] - m);
+  sum = block_sum(sum, sh);
+  if (threadIdx.x == 0) lse[blockIdx.x] = m + logf(sum);
+}
+
+hipError_t launch_row_lse(const float* logits, float* lse, int rows, int vocab, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(row_lse_kernel, dim3(rows), dim3(256), 0, s, logits, lse, vocab);
+  return hipGetLastError();
+}
+
+}  // namespace mtad

@@ -1,0 +1,394 @@
+// C-ABI layer of libmtad: context, workspace carving, host-side validation and the sequencing of the
+// kernels for the draft beam step, the target pass, accept and commit (see include/mtad.h).
+#include "../../include/mtad.h"
+#include "../../include/mtad_kernels.h"
+#include "beam.h"
+#include "common.h"
+
+#include <math.h>
+#include <new>
+#include <string.h>
+
+using namespace mtad;
+
+struct mtad_ctx {
+  mtad_config cfg;
+  mtad_model tshape, dshape;  // shapes only (weights pointer cleared)
+  int M;                      // rows per sequence of the target pass
+  int Rmax;                   // most rows per sequence of any pass
+  int draft_rows;             // rows per sequence of a draft step (max over steps)
+  size_t ws_need;
+  char* ws;
+  // workspace carve-up
+  float *h, *qkv, *gu, *dlogits, *lse, *partial, *part_key;
+  void* xn;
+  float2* rope;
+  int* part_idx;
+  RowDesc rd;
+  uint32_t* status;
+  int last_hip;
+};
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int imax(int a, int b) { return a > b ? a : b; }
+inline int imin(int a, int b) { return a < b ? a : b; }
+
+int shape_ok(const mtad_model* m) {
+  if (m->n_layers < 1 || m->d_model < 1 || m->n_heads < 1 || m->n_kv_heads < 1 || m->d_ffn < 1 || m->vocab < 1) return 0;
+  if (m->head_dim != 64 && m->head_dim != 128) return 0;
+  if (m->n_heads % m->n_kv_heads) return 0;
+  if (m->dtype != 0 && m->dtype != 1) return 0;
+  const int hhd = m->n_heads * m->head_dim, qkv = (m->n_heads + 2 * m->n_kv_heads) * m->head_dim;
+  if (m->d_model % 4 || m->d_ffn % 4) return 0;
+  if (m->dtype == 1) {
+    if (m->d_model % 32 || m->d_ffn % 32 || hhd % 32) return 0;           // reduction widths
+    if (m->d_model % 16 || qkv % 16 || (2 * m->d_ffn) % 16 || m->vocab % 16) return 0;  // output widths
+  }
+  return 1;
+}
+
+int splits_for(const mtad_ctx* c, const mtad_model* m, int R) {
+  const int chunks = (R + 15) / 16;
+  const int blocks = c->cfg.batch * m->n_heads * chunks;
+  int s = (1024 + blocks - 1) / blocks;
+  s = imin(s, (c->cfg.max_context + 127) / 128);
+  return imax(1, imin(32, s));
+}
+
+struct Carver {
+  size_t off = 0;
+  char* base;
+  explicit Carver(char* b) : base(b) {}
+  template <typename T>
+  T* take(size_t n) {
+    T* p = base ? (T*)(base + off) : nullptr;
+    off += align256(n * sizeof(T));
+    return p;
+  }
+};
+
+void carve(mtad_ctx* c, char* base) {
+  const mtad_model &t = c->tshape, &d = c->dshape;
+  const size_t rows = (size_t)c->cfg.batch * c->Rmax;
+  const int dmax = imax(t.d_model, d.d_model), fmax = imax(t.d_ffn, d.d_ffn);
+  const int hhd = imax(t.n_heads * t.head_dim, d.n_heads * d.head_dim);
+  const int qkv = imax((t.n_heads + 2 * t.n_kv_heads) * t.head_dim, (d.n_heads + 2 * d.n_kv_heads) * d.head_dim);
+  const int hdmax = imax(t.head_dim, d.head_dim);
+  Carver k(base);
+  c->status = k.take<uint32_t>(64);
+  c->h = k.take<float>(rows * dmax);
+  c->xn = k.take<float>(rows * imax(imax(dmax, hhd), fmax));
+  c->qkv = k.take<float>(rows * qkv);
+  c->gu = k.take<float>(rows * 2 * fmax);
+  c->dlogits = k.take<float>((size_t)c->cfg.batch * c->draft_rows * d.vocab);
+  c->lse = k.take<float>(rows);
+  const size_t pt = attention_partial_floats(c->cfg.batch, c->Rmax, t.n_heads, t.head_dim, 32);
+  const size_t pd = attention_partial_floats(c->cfg.batch, c->Rmax, d.n_heads, d.head_dim, 32);
+  c->partial = k.take<float>(pt > pd ? pt : pd);
+  c->rope = k.take<float2>(rows * (hdmax / 2));
+  c->rd.tok = k.take<int32_t>(rows);
+  c->rd.pos = k.take<int32_t>(rows);
+  c->rd.slot = k.take<int32_t>(rows);
+  c->rd.mask = k.take<uint64_t>(rows);
+  c->rd.nspec = k.take<int32_t>(c->cfg.batch);
+  c->part_key = k.take<float>((size_t)c->cfg.batch * TOPB_BLOCKS * 8);
+  c->part_idx = k.take<int>((size_t)c->cfg.batch * TOPB_BLOCKS * 8);
+  c->ws_need = k.off;
+}
+
+int kv_ok(const mtad_kv* kv) {
+  return kv && kv->k && kv->v && kv->page_table && kv->len && kv->page_size > 0 && kv->max_pages > 0 && kv->n_pages > 0;
+}
+
+KvView view_of(const mtad_kv* kv, const mtad_model* m) {
+  KvView v;
+  v.k = kv->k;
+  v.v = kv->v;
+  v.page_table = kv->page_table;
+  v.len = kv->len;
+  v.page_size = kv->page_size;
+  v.max_pages = kv->max_pages;
+  v.n_pages = kv->n_pages;
+  v.n_kv_heads = m->n_kv_heads;
+  v.head_dim = m->head_dim;
+  v.layer_stride = (int64_t)kv->n_pages * kv->page_size * m->n_kv_heads * m->head_dim;
+  return v;
+}
+
+int same_shape(const mtad_model* a, const mtad_model* b) {
+  return a->n_layers == b->n_layers && a->d_model == b->d_model && a->n_heads == b->n_heads && a->n_kv_heads == b->n_kv_heads &&
+         a->head_dim == b->head_dim && a->d_ffn == b->d_ffn && a->vocab == b->vocab && a->dtype == b->dtype;
+}
+
+#define HIP_TRY(ctx, expr)              \
+  do {                                  \
+    hipError_t e__ = (expr);            \
+    if (e__ != hipSuccess) {            \
+      (ctx)->last_hip = (int)e__;       \
+      return MTAD_EHIP;                 \
+    }                                   \
+  } while (0)
+
+// The decoder pass over B*R rows described by ctx->rd; hidden states end in ctx->h.
+int decoder_pass(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s) {
+  const int B = c->cfg.batch, rows = B * R, dt = m->dtype;
+  const int d = m->d_model, f = m->d_ffn, H = m->n_heads, hd = m->head_dim;
+  const int qkvw = (H + 2 * m->n_kv_heads) * hd;
+  const KvView kvv = view_of(kv, m);
+  const int n_splits = splits_for(c, m, R);
+  const void* const* W = m->weights;
+  HIP_TRY(c, launch_embed(dt, W[0], c->rd.tok, c->h, rows, d, m->vocab, s));
+  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s));
+  for (int l = 0; l < m->n_layers; ++l) {
+    const void* const* L = W + 1 + 6 * l;
+    HIP_TRY(c, launch_rmsnorm(dt, c->h, (const float*)L[0], c->xn, rows, d, m->rms_eps, s));
+    HIP_TRY(c, launch_gemm(dt, L[1], c->xn, c->qkv, rows, qkvw, d, qkvw, false, s));
+    HIP_TRY(c, launch_rope_kv(dt, c->qkv, c->rope, c->rd, kvv, l, B, R, H, c->status, s));
+    HIP_TRY(c, launch_attention(dt, c->qkv, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->xn, s));
+    HIP_TRY(c, launch_gemm(dt, L[2], c->xn, c->h, rows, d, H * hd, d, true, s));
+    HIP_TRY(c, launch_rmsnorm(dt, c->h, (const float*)L[3], c->xn, rows, d, m->rms_eps, s));
+    HIP_TRY(c, launch_gemm(dt, L[4], c->xn, c->gu, rows, 2 * f, d, 2 * f, false, s));
+    HIP_TRY(c, launch_silu_mul(dt, c->gu, c->xn, rows, f, s));
+    HIP_TRY(c, launch_gemm(dt, L[5], c->xn, c->h, rows, d, f, d, true, s));
+  }
+  return MTAD_OK;
+}
+
+int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* lse, hipStream_t s) {
+  const void* const* W = m->weights;
+  const int tail = 1 + 6 * m->n_layers;
+  HIP_TRY(c, launch_rmsnorm(m->dtype, c->h, (const float*)W[tail], c->xn, rows, m->d_model, m->rms_eps, s));
+  HIP_TRY(c, launch_gemm(m->dtype, W[tail + 1], c->xn, logits, rows, m->vocab, m->d_model, m->vocab, false, s));
+  HIP_TRY(c, launch_row_lse(logits, lse, rows, m->vocab, s));
+  return MTAD_OK;
+}
+
+int weights_ok(const mtad_model* m) {
+  if (!m || !m->weights) return 0;
+  for (int i = 0; i < 3 + 6 * m->n_layers; ++i)
+    if (!m->weights[i]) return 0;
+  return 1;
+}
+
+TreeView tview(const mtad_tree* t) {
+  TreeView v;
+  v.M = t->M;
+  v.tok = t->tok;
+  v.parent = t->parent;
+  v.depth = t->depth;
+  v.src_beam = t->src_beam;
+  v.anc_mask = t->anc_mask;
+  v.qref = t->qref;
+  return v;
+}
+int tree_ok(const mtad_tree* t) { return t && t->tok && t->parent && t->depth && t->src_beam && t->anc_mask && t->qref; }
+
+}  // namespace
+
+extern "C" {
+
+int mtad_create(mtad_ctx** out, const mtad_config* cfg, const mtad_model* target, const mtad_model* draft) {
+  if (!out || !cfg || !target || !draft) return MTAD_EINVAL;
+  if (cfg->batch < 1 || cfg->gamma < 1 || cfg->beam < 1 || cfg->max_context < 1) return MTAD_EINVAL;
+  if (cfg->mode != MTAD_MODE_MTAD && cfg->mode != MTAD_MODE_MMTAD) return MTAD_EINVAL;
+  if (!shape_ok(target) || !shape_ok(draft)) return MTAD_ESHAPE;
+  if (target->vocab != draft->vocab) return MTAD_ESHAPE;
+  if (cfg->beam > MTAD_MAX_BEAM || cfg->beam > draft->vocab) return MTAD_ESHAPE;
+  if (cfg->prefill_rows < 1 || cfg->prefill_rows > MTAD_MAX_ROWS) return MTAD_ESHAPE;
+  const int M = 1 + (cfg->mode == MTAD_MODE_MTAD ? cfg->gamma : cfg->gamma * cfg->beam);
+  if (M > MTAD_MAX_ROWS) return MTAD_ESHAPE;
+  if ((cfg->gamma + 1) + (cfg->gamma - 1) * cfg->beam > MTAD_MAX_ROWS) return MTAD_ESHAPE;  // draft rows of one iteration
+  mtad_ctx* c = new (std::nothrow) mtad_ctx();
+  if (!c) return MTAD_ECAP;
+  memset(c, 0, sizeof(*c));
+  c->cfg = *cfg;
+  c->tshape = *target;
+  c->dshape = *draft;
+  c->tshape.weights = nullptr;
+  c->dshape.weights = nullptr;
+  c->M = M;
+  c->draft_rows = imax(cfg->gamma + 1, cfg->beam);
+  c->Rmax = imax(imax(cfg->prefill_rows, M), c->draft_rows);
+  if ((int64_t)cfg->batch * c->Rmax > 256) {  // the skinny product kernels hold at most 256 rows
+    delete c;
+    return MTAD_ESHAPE;
+  }
+  carve(c, nullptr);
+  *out = c;
+  return MTAD_OK;
+}
+
+void mtad_destroy(mtad_ctx* c) { delete c; }
+
+size_t mtad_workspace_bytes(const mtad_ctx* c) { return c ? c->ws_need : 0; }
+
+int mtad_bind_workspace(mtad_ctx* c, void* buf, size_t bytes) {
+  if (!c || !buf) return MTAD_EINVAL;
+  if (((uintptr_t)buf) & 255) return MTAD_EINVAL;
+  if (bytes < c->ws_need) return MTAD_ECAP;
+  c->ws = (char*)buf;
+  carve(c, c->ws);
+  hipError_t e = hipMemset(c->status, 0, 256);
+  if (e != hipSuccess) {
+    c->last_hip = (int)e;
+    return MTAD_EHIP;
+  }
+  return MTAD_OK;
+}
+
+const char* mtad_strerror(int st) {
+  switch (st) {
+    case MTAD_OK: return "ok";
+    case MTAD_EINVAL: return "invalid argument";
+    case MTAD_ESHAPE: return "unsupported shape";
+    case MTAD_ECAP: return "capacity exceeded";
+    case MTAD_EHIP: return "HIP error";
+    case MTAD_ENOSYS: return "not implemented";
+    default: return "unknown status";
+  }
+}
+
+int mtad_last_hip_error(const mtad_ctx* c) { return c ? c->last_hip : 0; }
+
+int mtad_device_status(mtad_ctx* c, uint32_t* bits, void* stream) {
+  if (!c || !bits || !c->ws) return MTAD_EINVAL;
+  HIP_TRY(c, hipMemcpyAsync(bits, c->status, sizeof(uint32_t), hipMemcpyDeviceToHost, (hipStream_t)stream));
+  HIP_TRY(c, hipStreamSynchronize((hipStream_t)stream));
+  return MTAD_OK;
+}
+
+int mtad_prefill(mtad_ctx* c, const mtad_model* model, mtad_kv* kv, const int32_t* tokens, int32_t n_tokens, void* stream) {
+  if (!c || !c->ws || !weights_ok(model) || !kv_ok(kv) || !tokens || n_tokens < 0) return MTAD_EINVAL;
+  if (!same_shape(model, &c->tshape) && !same_shape(model, &c->dshape)) return MTAD_ESHAPE;
+  if (n_tokens > kv->page_size * kv->max_pages) return MTAD_ECAP;
+  hipStream_t s = (hipStream_t)stream;
+  const int R = c->cfg.prefill_rows, B = c->cfg.batch, cap = kv->page_size * kv->max_pages;
+  for (int c0 = 0; c0 < n_tokens; c0 += R) {
+    const int r = imin(R, n_tokens - c0);
+    HIP_TRY(c, launch_prefill_rows(c->rd, kv->len, tokens, n_tokens, c0, B, r, cap, c->status, s));
+    int st = decoder_pass(c, model, kv, r, s);
+    if (st) return st;
+    HIP_TRY(c, launch_advance_len(kv->len, c->rd.nspec, B, cap, s));
+  }
+  return MTAD_OK;
+}
+
+int mtad_draft_beam_step(mtad_ctx* c, const mtad_model* draft, mtad_kv* dkv, mtad_beam* hist, int32_t step, const mtad_state* st,
+                         int32_t sample_beam, uint64_t seed, void* stream) {
+  if (!c || !c->ws || !weights_ok(draft) || !kv_ok(dkv) || !hist || !hist->tok || !hist->parent || !hist->cum_logq || !st ||
+      !st->catchup_tok || !st->catchup_cnt)
+    return MTAD_EINVAL;
+  if (step < 0 || step >= c->cfg.gamma) return MTAD_EINVAL;
+  if (!same_shape(draft, &c->dshape)) return MTAD_ESHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  const int B = c->cfg.batch, gamma = c->cfg.gamma, beam = c->cfg.beam;
+  const int R = (step == 0) ? gamma + 1 : beam;
+  const BeamView hv{hist->tok, hist->parent, hist->cum_logq};
+  HIP_TRY(c, launch_draft_rows(c->rd, dkv->len, hv, st->catchup_tok, st->catchup_cnt, step, B, R, gamma, beam,
+                               dkv->page_size * dkv->max_pages, c->status, s));
+  int rc = decoder_pass(c, draft, dkv, R, s);
+  if (rc) return rc;
+  rc = lm_head(c, draft, B * R, c->dlogits, c->lse, s);
+  if (rc) return rc;
+  HIP_TRY(c, launch_topb(c->dlogits, c->lse, hv, st->catchup_cnt, dkv->len, step, B, R, gamma, beam, draft->vocab, sample_beam ? 1 : 0,
+                         seed, c->part_key, c->part_idx, TOPB_BLOCKS, s));
+  return MTAD_OK;
+}
+
+int mtad_build_tree(mtad_ctx* c, const mtad_beam* hist, int32_t mode, mtad_tree* tree, void* stream) {
+  if (!c || !hist || !hist->tok || !hist->parent || !hist->cum_logq || !tree_ok(tree)) return MTAD_EINVAL;
+  if (mode != MTAD_MODE_MTAD && mode != MTAD_MODE_MMTAD) return MTAD_EINVAL;
+  const int M = 1 + (mode == MTAD_MODE_MTAD ? c->cfg.gamma : c->cfg.gamma * c->cfg.beam);
+  if (M > MTAD_MAX_ROWS) return MTAD_ESHAPE;
+  tree->M = M;
+  const BeamView hv{hist->tok, hist->parent, hist->cum_logq};
+  HIP_TRY(c, launch_build_tree(hv, tview(tree), c->cfg.batch, c->cfg.gamma, c->cfg.beam, mode, (hipStream_t)stream));
+  return MTAD_OK;
+}
+
+int mtad_verify_tree(mtad_ctx* c, const mtad_model* target, mtad_kv* tkv, const int32_t* root_tok, const mtad_tree* tree,
+                     float* logp_cond, float* row_lse, float* logits, void* stream) {
+  if (!c || !c->ws || !weights_ok(target) || !kv_ok(tkv) || !root_tok || !tree_ok(tree) || !logp_cond || !row_lse || !logits)
+    return MTAD_EINVAL;
+  if (!same_shape(target, &c->tshape)) return MTAD_ESHAPE;
+  if (tree->M < 1 || tree->M > c->Rmax) return MTAD_ESHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  const int B = c->cfg.batch, M = tree->M;
+  HIP_TRY(c, launch_verify_rows(c->rd, tkv->len, root_tok, tview(tree), B, tkv->page_size * tkv->max_pages, c->status, s));
+  int rc = decoder_pass(c, target, tkv, M, s);
+  if (rc) return rc;
+  rc = lm_head(c, target, B * M, logits, row_lse, s);
+  if (rc) return rc;
+  HIP_TRY(c, launch_gather_logp(logits, row_lse, tview(tree), B, target->vocab, logp_cond, s));
+  return MTAD_OK;
+}
+
+int mtad_accept(mtad_ctx* c, const mtad_tree* tree, const float* logp_cond, const float* logits, int32_t vocab, const mtad_kv* tkv,
+                float tau, int32_t mode, int32_t sample_bonus, uint64_t seed, mtad_accept_out* out, void* stream) {
+  if (!c || !tree_ok(tree) || !logp_cond || !logits || !tkv || !tkv->len || !out || !out->eta || !out->path || !out->bonus_row ||
+      !out->bonus_tok || !out->out_tok || !out->out_cnt)
+    return MTAD_EINVAL;
+  if (!(tau >= 0.f && tau < 1.f) || vocab < 1) return MTAD_EINVAL;
+  if (mode != MTAD_MODE_MTAD && mode != MTAD_MODE_MMTAD) return MTAD_EINVAL;
+  if (tree->M < 1 || tree->M > MTAD_MAX_ROWS) return MTAD_ESHAPE;
+  const float log_tau = (tau > 0.f) ? (float)log((double)tau) : -INFINITY;
+  const AcceptView av{out->eta, out->path, out->bonus_row, out->bonus_tok, out->out_tok, out->out_cnt};
+  HIP_TRY(c, launch_accept(tview(tree), logp_cond, logits, vocab, tkv->len, log_tau, mode, c->cfg.batch, c->cfg.gamma,
+                           sample_bonus ? 1 : 0, seed, av, (hipStream_t)stream));
+  return MTAD_OK;
+}
+
+int mtad_kv_commit(mtad_ctx* c, mtad_kv* tkv, mtad_kv* dkv, const mtad_tree* tree, const mtad_accept_out* acc, mtad_state* st,
+                   void* stream) {
+  if (!c || !kv_ok(tkv) || (dkv && !kv_ok(dkv)) || !tree_ok(tree) || !acc || !acc->eta || !acc->path || !acc->bonus_tok || !st ||
+      !st->root_tok || !st->catchup_tok || !st->catchup_cnt)
+    return MTAD_EINVAL;
+  if (tree->M < 1 || tree->M > MTAD_MAX_ROWS) return MTAD_ESHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  const int B = c->cfg.batch, gamma = c->cfg.gamma, beam = c->cfg.beam;
+  HIP_TRY(c, launch_kv_gather(c->tshape.dtype, view_of(tkv, &c->tshape), c->tshape.n_layers, B, acc->eta, acc->path, tree->src_beam,
+                              st->catchup_cnt, tree->M, gamma, beam, 0, s));
+  if (dkv)
+    HIP_TRY(c, launch_kv_gather(c->dshape.dtype, view_of(dkv, &c->dshape), c->dshape.n_layers, B, acc->eta, acc->path, tree->src_beam,
+                                st->catchup_cnt, tree->M, gamma, beam, 1, s));
+  const AcceptView av{acc->eta, acc->path, acc->bonus_row, acc->bonus_tok, acc->out_tok, acc->out_cnt};
+  HIP_TRY(c, launch_commit_state(tkv->len, dkv ? dkv->len : nullptr, tview(tree), av, st->root_tok, st->catchup_tok, st->catchup_cnt, B,
+                                 gamma, tkv->page_size * tkv->max_pages, dkv ? dkv->page_size * dkv->max_pages : 0, s));
+  return MTAD_OK;
+}
+
+// ---- component entry points (include/mtad_kernels.h) ------------------------------------------------------------
+
+int mtad_k_gemm(int32_t dtype, const void* W, const void* X, float* Y, int32_t R, int32_t N, int32_t K, int32_t ldy, int32_t accumulate,
+                void* stream) {
+  if (!W || !X || !Y || R < 1 || N < 1 || K < 1 || ldy < N) return MTAD_EINVAL;
+  if (dtype != 0 && dtype != 1) return MTAD_EINVAL;
+  if (dtype == 1 && ((N % 16) || (K % 32) || (ldy % 4) || R > 256)) return MTAD_ESHAPE;
+  if (dtype == 0 && (K % 4)) return MTAD_ESHAPE;
+  return launch_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate != 0, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+}
+
+int mtad_k_rmsnorm(int32_t dtype, const float* h, const float* g, void* out, int32_t rows, int32_t d, float eps, void* stream) {
+  if (!h || !g || !out || rows < 1 || d < 4 || (d % 4)) return MTAD_EINVAL;
+  return launch_rmsnorm(dtype, h, g, out, rows, d, eps, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+}
+
+int mtad_k_row_lse(const float* logits, float* lse, int32_t rows, int32_t vocab, void* stream) {
+  if (!logits || !lse || rows < 1 || vocab < 1) return MTAD_EINVAL;
+  return launch_row_lse(logits, lse, rows, vocab, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+}
+
+int mtad_k_beam_topb(mtad_ctx* c, const float* logits, const float* lse, mtad_beam* hist, int32_t step, const int32_t* catchup_cnt,
+                     const int32_t* len, int32_t rows_per_seq, int32_t vocab, int32_t sample_beam, uint64_t seed, void* stream) {
+  if (!c || !c->ws || !logits || !lse || !hist || !hist->tok || !hist->parent || !hist->cum_logq || !catchup_cnt || !len)
+    return MTAD_EINVAL;
+  if (step < 0 || step >= c->cfg.gamma || vocab < c->cfg.beam || rows_per_seq < 1) return MTAD_EINVAL;
+  const BeamView hv{hist->tok, hist->parent, hist->cum_logq};
+  HIP_TRY(c, launch_topb(logits, lse, hv, catchup_cnt, len, step, c->cfg.batch, rows_per_seq, c->cfg.gamma, c->cfg.beam, vocab,
+                         sample_beam ? 1 : 0, seed, c->part_key, c->part_idx, TOPB_BLOCKS, (hipStream_t)stream));
+  return MTAD_OK;
+}
+
+}  // extern "C"

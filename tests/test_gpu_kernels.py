@@ -1,0 +1,104 @@
+"""GPU parity of single kernels against the oracle's arithmetic (float64 numpy) on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _mb():
+    from paper_2407_09722_amd import binding as mb
+    mb.lib()
+    return mb
+
+
+def _bits(x):
+    return torch.from_numpy(si.f32_to_bf16_bits(x).view(np.int16)).to(DEV)
+
+
+def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None):
+    g = np.random.default_rng(seed)
+    W = (g.standard_normal((N, K)) * 0.05).astype(np.float32)
+    X = g.standard_normal((R, K)).astype(np.float32)
+    ldy = ldy or N
+    Y0 = g.standard_normal((R, ldy)).astype(np.float32)
+    if dtype == 1:
+        Wd, Xd = _bits(W), _bits(X)
+        W, X = si.bf16_bits_to_f32(si.f32_to_bf16_bits(W)), si.bf16_bits_to_f32(si.f32_to_bf16_bits(X))
+    else:
+        Wd, Xd = torch.from_numpy(W).to(DEV), torch.from_numpy(X).to(DEV)
+    Yd = torch.from_numpy(Y0).to(DEV)
+    mb.mtad_k_gemm(dtype, Wd, Xd, Yd, R, N, K, ldy, accumulate)
+    torch.cuda.synchronize()
+    got = Yd.cpu().numpy().astype(np.float64)
+    want = Y0.astype(np.float64)
+    prod = X.astype(np.float64) @ W.astype(np.float64).T
+    want[:, :N] = (want[:, :N] + prod) if accumulate else prod
+    scale = np.abs(X).astype(np.float64) @ np.abs(W).astype(np.float64).T      # bound on the sum of |terms|
+    err = np.abs(got[:, :N] - want[:, :N])
+    assert np.all(err <= 2e-6 * scale + 1e-6), f"R{R} N{N} K{K}: max err {err.max()}"
+    assert np.array_equal(got[:, N:], want[:, N:])                            # padding columns untouched
+
+
+@pytest.mark.parametrize("R,N,K", [(1, 16, 32), (5, 48, 1376), (5, 2304, 768), (16, 64, 4096), (17, 4096, 4096),
+                                   (5, 12288, 4096), (5, 4096, 11008), (33, 80, 96), (41, 512, 2048), (100, 96, 160),
+                                   (164, 640, 5120), (200, 32, 64), (256, 1024, 1376)])
+def test_gemm_bf16_matches_float64(R, N, K):
+    mb = _mb()
+    print(f"gemm bf16 R={R} N={N} K={K}", flush=True)
+    _gemm_case(mb, R, N, K, 1, seed=R * 7 + N)
+
+
+def test_gemm_accumulate_and_padded_rows():
+    mb = _mb()
+    _gemm_case(mb, 5, 64, 96, 1, seed=1, accumulate=True)
+    _gemm_case(mb, 20, 48, 64, 1, seed=2, accumulate=True, ldy=52)
+    _gemm_case(mb, 7, 30, 44, 0, seed=3, accumulate=True, ldy=32)
+
+
+@pytest.mark.parametrize("R,N,K", [(1, 4, 4), (5, 1024, 256), (9, 688 * 2, 256), (5, 256, 688), (32, 37, 344), (64, 1024, 128)])
+def test_gemm_fp32_matches_float64(R, N, K):
+    mb = _mb()
+    _gemm_case(mb, R, N, K, 0, seed=R + N + K)
+
+
+def test_lm_head_shape_full_vocab():
+    """The 7B-shaped lm_head at its real size, checked on every output."""
+    mb = _mb()
+    _gemm_case(mb, 5, 32000, 4096, 1, seed=11)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_rmsnorm(dtype):
+    mb = _mb()
+    g = np.random.default_rng(3)
+    for rows, d in ((1, 128), (5, 4096), (17, 768), (41, 5120)):
+        h = (g.standard_normal((rows, d)) * 3).astype(np.float32)
+        gain = (1 + 0.1 * g.standard_normal(d)).astype(np.float32)
+        out = torch.zeros((rows, d), dtype=torch.int16 if dtype else torch.float32, device=DEV)
+        mb.mtad_k_rmsnorm(dtype, torch.from_numpy(h).to(DEV), torch.from_numpy(gain).to(DEV), out, rows, d, 1e-5)
+        torch.cuda.synchronize()
+        x = h.astype(np.float64)
+        want = x / np.sqrt((x * x).mean(axis=1, keepdims=True) + 1e-5) * gain
+        if dtype:
+            got = si.bf16_bits_to_f32(out.cpu().numpy().view(np.uint16)).astype(np.float64)
+            assert np.all(np.abs(got - want) <= np.abs(want) * 2 ** -8 + 1e-30)      # half a bf16 ulp, rounded once
+        else:
+            got = out.cpu().numpy().astype(np.float64)
+            assert np.allclose(got, want, rtol=2e-6, atol=1e-7)
+
+
+def test_row_lse():
+    mb = _mb()
+    g = np.random.default_rng(4)
+    for rows, V in ((1, 7), (5, 1024), (17, 32000)):
+        x = (g.standard_normal((rows, V)) * 3).astype(np.float32)
+        lse = torch.zeros(rows, dtype=torch.float32, device=DEV)
+        mb.mtad_k_row_lse(torch.from_numpy(x).to(DEV), lse, rows, V)
+        torch.cuda.synchronize()
+        xx = x.astype(np.float64)
+        want = xx.max(1) + np.log(np.exp(xx - xx.max(1, keepdims=True)).sum(1))
+        assert np.allclose(lse.cpu().numpy(), want, rtol=1e-6, atol=1e-6)
