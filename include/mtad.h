@@ -25,9 +25,11 @@
  *     A kernel that would step outside a KV cache or outside the 64-row speculative window
  *     writes nothing there and sets a sticky bit readable with mtad_device_status().
  *   - A context is not thread safe; use one context per stream.
- *   - Matrices are row-major [out_features, in_features].  dtype 0 = float32, 1 = bfloat16
- *     (weights, KV cache and matrix-product inputs rounded to nearest even; accumulation,
- *     residual stream, softmax, logits and all scores in float32).
+ *   - Matrices are row-major [out_features, in_features].  dtype 0 = float32 everywhere.
+ *     dtype 1 = bfloat16 weights; KV cache in IEEE half (16 bits per value, round to nearest
+ *     even); an activation entering a weight matrix product is carried as the sum of two
+ *     bfloat16 terms hi = bf16(x), lo = bf16(x - hi); accumulation, queries, residual stream,
+ *     softmax, logits and all scores are float32.
  */
 #ifndef MTAD_H
 #define MTAD_H
@@ -72,7 +74,7 @@ typedef struct {
 } mtad_model;
 
 /* Paged KV cache of one model, device memory owned by the caller.
- * k, v: [n_layers][n_pages][page_size][n_kv_heads][head_dim] in the model's dtype.
+ * k, v: [n_layers][n_pages][page_size][n_kv_heads][head_dim], float32 (dtype 0) or IEEE half (dtype 1).
  * page_table: int32 [batch][max_pages], logical page -> physical page (each < n_pages).
  * len: int32 [batch], tokens whose K/V are committed.  Token position t of sequence s lives in
  * page page_table[s][t / page_size], slot t % page_size.  Rows of a pass that are not committed yet

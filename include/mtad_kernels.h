@@ -14,13 +14,15 @@ extern "C" {
 
 /* The few-row matrix product of every projection, FFN matrix and the lm_head of a pass (the weight stream the
  * paper's cost argument is about, Section 4: time and energy are dominated by reading the weights once per run).
- * Y[r][n] (+)= sum_k X[r][k] * W[n][k], r < R.  dtype 1: W, X bfloat16, float32 accumulation (N % 16 == 0,
- * K % 32 == 0, R <= 256); dtype 0: all float32 (K % 4 == 0).  Y float32 [R][ldy], ldy >= N, ldy % 4 == 0.
+ * Y[r][n] (+)= sum_k X[r][k] * W[n][k], r < R.  dtype 1: W bfloat16 [N][K]; X two bfloat16 planes [2][R][K]
+ * (hi, lo) whose sum is the activation; float32 accumulation (N % 16 == 0, K % 32 == 0, R <= 256);
+ * dtype 0: W, X float32 (K % 4 == 0).  Y float32 [R][ldy], ldy >= N, ldy % 4 == 0.
  * accumulate != 0 adds to Y (the residual connection). */
 int mtad_k_gemm(int32_t dtype, const void *W, const void *X, float *Y, int32_t R, int32_t N, int32_t K, int32_t ldy,
                 int32_t accumulate, void *stream);
 
-/* out[row][i] = h[row][i] / sqrt(mean_i h[row][i]^2 + eps) * g[i]; out is bfloat16 (dtype 1) or float32 (dtype 0). */
+/* out[row][i] = h[row][i] / sqrt(mean_i h[row][i]^2 + eps) * g[i]; out is two
+ * bfloat16 planes [2][rows][d] (hi, lo; dtype 1) or float32 [rows][d] (dtype 0). */
 int mtad_k_rmsnorm(int32_t dtype, const float *h, const float *g, void *out, int32_t rows, int32_t d, float eps,
                    void *stream);
 

@@ -6,6 +6,7 @@
 namespace mtad {
 
 typedef uint16_t bf16_t;  // bfloat16 bit pattern
+typedef _Float16 kv16_t;  // storage type of the KV cache of a bfloat16 model: IEEE half (3 more mantissa bits at the same size)
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
@@ -16,6 +17,12 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 __device__ __forceinline__ float round_bf16(float f) { return bf16_to_f32(f32_to_bf16(f)); }
+// Two-term bfloat16 split of a float32 activation: x ~= hi + lo with a relative error of about 2^-17.
+// Matrix-product inputs are carried this way so that their rounding stays far below the weights' own.
+__device__ __forceinline__ void split_bf16(float x, bf16_t& hi, bf16_t& lo) {
+  hi = f32_to_bf16(x);
+  lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
 
 // Device status bits (sticky, OR-ed by kernels that refuse an out-of-range access)
 enum : uint32_t { ST_KV_CAP = 1u, ST_SPEC_WINDOW = 2u, ST_BAD_CATCHUP = 4u };
@@ -47,14 +54,15 @@ struct RowDesc {
 };
 
 // ---- launchers (kernels_*.hip) ----------------------------------------------------------------
-// Y[r][n] (+)= sum_k X[r][k] * W[n][k];  X: bf16 [R][K] (dtype 1) or f32 (dtype 0); W likewise [N][K]; Y f32 [R][ldy]
+// Y[r][n] (+)= sum_k X[r][k] * W[n][k];  W [N][K] bf16 (dtype 1) or f32 (dtype 0); X f32 [R][K] (dtype 0) or two
+// bf16 planes [2][R][K] (hi, lo) whose sum is the activation (dtype 1); Y f32 [R][ldy]
 hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate,
                        hipStream_t s);
 hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, hipStream_t s);
-// out = rmsnorm(h) * g, written as bf16 (dtype 1) or f32 (dtype 0)
+// out = rmsnorm(h) * g, written as hi/lo bf16 planes [2][rows][d] (dtype 1) or f32 [rows][d] (dtype 0)
 hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s);
 hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s);
-// rotate q (in place in qkv, rounded to storage precision), rotate k and write k, v to the cache
+// rotate q (in place in qkv, float32), rotate k and write k, v to the cache in its storage type
 hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
                           int n_heads, uint32_t* status, hipStream_t s);
 hipError_t launch_attention(int dtype, const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,

@@ -5,8 +5,10 @@
 // Split-KV "flash decoding": grid = (key split, head x row chunk, sequence).  A workgroup stages 64-key
 // K and V tiles in LDS once and reuses them for its (up to 16) query rows, keeps running max / sum /
 // output per row, and writes one partial per split; a second kernel merges the partials in a fixed
-// order.  Everything is float32 arithmetic; K/V are read in their storage type.
+// order.  Everything is float32 arithmetic; K/V are read in their storage type (half or float32).
 #include "common.h"
+
+#include <type_traits>
 
 namespace mtad {
 
@@ -37,7 +39,7 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
   constexpr int NRG2 = 256 / HD, RPT2 = RB / NRG2;  // PV phase
 
   __shared__ float q_s[RB][HD];
-  __shared__ T k_s[TK * KS];
+  __shared__ __attribute__((aligned(16))) T k_s[TK * KS];
   __shared__ __attribute__((aligned(16))) T v_s[TK * HD];
   __shared__ float s_s[RB][TK];
   __shared__ float m_s[RB], l_s[RB], a_s[RB];
@@ -110,9 +112,10 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
       for (int d = 0; d < HD; d += 2) {
         float k0, k1;
         if constexpr (sizeof(T) == 2) {
-          const uint32_t w = *(const uint32_t*)(krow + d);
-          k0 = __uint_as_float(w << 16);
-          k1 = __uint_as_float(w & 0xFFFF0000u);
+          typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+          const half2_t w = *(const half2_t*)(krow + d);
+          k0 = (float)w[0];
+          k1 = (float)w[1];
         } else {
           k0 = krow[d];
           k1 = krow[d + 1];
@@ -161,9 +164,7 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
 #pragma unroll
       for (int i = 0; i < RPT2; ++i) acc[i] *= a_s[rg2 + NRG2 * i];
       for (int j = 0; j < TK; ++j) {
-        float v;
-        if constexpr (sizeof(T) == 2) v = bf16_to_f32(v_s[j * HD + d]);
-        else v = v_s[j * HD + d];
+        const float v = (float)v_s[j * HD + d];
 #pragma unroll
         for (int i = 0; i < RPT2; ++i) acc[i] = fmaf(s_s[rg2 + NRG2 * i][j], v, acc[i]);
       }
@@ -206,7 +207,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ partial, T* __rest
   }
   const float y = (L > 0.f) ? o / L : 0.f;
   const int64_t idx = (int64_t)row * n_heads * HD + (int64_t)head * HD + d;
-  if constexpr (sizeof(T) == 2) out[idx] = f32_to_bf16(y);
+  if constexpr (sizeof(T) == 2) split_bf16(y, out[idx], out[(int64_t)gridDim.x * n_heads * HD + idx]);  // hi / lo planes
   else out[idx] = y;
 }
 
@@ -217,13 +218,14 @@ size_t attention_partial_floats(int B, int R, int n_heads, int head_dim, int n_s
 template <typename T, int HD>
 static hipError_t run_attn(const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads, float* partial,
                            int n_splits, void* out, hipStream_t s) {
+  using OutT = typename std::conditional<sizeof(T) == 2, bf16_t, float>::type;  // bf16 hi/lo planes or float32
   const int n_chunks = (R + RB - 1) / RB;
   const float scale = 1.0f / sqrtf((float)HD);
   hipLaunchKernelGGL((tree_attn_kernel<T, HD>), dim3(n_splits, n_heads * n_chunks, B), dim3(256), 0, s, qkv, rd, kv, layer, R,
                      n_heads, n_chunks, scale, partial, n_splits);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_combine_kernel<T, HD>), dim3(B * R, n_heads), dim3(HD), 0, s, partial, (T*)out, R, n_heads, n_splits);
+  hipLaunchKernelGGL((attn_combine_kernel<OutT, HD>), dim3(B * R, n_heads), dim3(HD), 0, s, partial, (OutT*)out, R, n_heads, n_splits);
   return hipGetLastError();
 }
 
@@ -231,8 +233,8 @@ hipError_t launch_attention(int dtype, const float* qkv, const RowDesc& rd, KvVi
                             float* partial, int n_splits, void* out, hipStream_t s) {
   if (B * R <= 0) return hipSuccess;
   const int hd = kv.head_dim;
-  if (dtype == 1 && hd == 128) return run_attn<bf16_t, 128>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
-  if (dtype == 1 && hd == 64) return run_attn<bf16_t, 64>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
+  if (dtype == 1 && hd == 128) return run_attn<kv16_t, 128>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
+  if (dtype == 1 && hd == 64) return run_attn<kv16_t, 64>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
   if (dtype == 0 && hd == 128) return run_attn<float, 128>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
   if (dtype == 0 && hd == 64) return run_attn<float, 64>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
   return hipErrorInvalidValue;

@@ -2,8 +2,10 @@
 // lm_head of the draft and target passes (the weight stream that dominates one target pass).
 //
 // bf16: the weight matrix is the A operand of v_mfma_f32_16x16x32_bf16 (16 output features x 32 k),
-// the activations are the B operand (32 k x 16 rows, rows beyond R are zero).  One workgroup owns 16
-// output features; its waves interleave over the 32-wide k blocks (wave w takes blocks w, w+WPB, ...),
+// the activations are the B operand (32 k x 16 rows, rows beyond R are zero).  An activation is the
+// sum of two bf16 terms (hi + lo planes), so every weight tile feeds two MFMAs per 16 rows; the matrix
+// cores idle anyway.  One workgroup owns 16 output features; its waves interleave over the 32-wide k
+// blocks (wave w takes blocks w, w+WPB, ...),
 // so one iteration of the whole group reads WPB*64 contiguous bytes of each weight row, and every
 // lane keeps several 16-byte loads in flight.  Partial sums are reduced through LDS in a fixed order
 // (deterministic).  Memory bound: weights are read exactly once, activations come from L2.
@@ -37,6 +39,7 @@ __global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(const bf16_t* __res
 
   const bf16_t* wp = W + (int64_t)(n0 + r16) * K + kg * 8;
   const bf16_t* xp = X + (int64_t)r16 * K + kg * 8;
+  const int64_t lo_plane = (int64_t)R * K;  // the lo plane follows the hi plane
   constexpr int U = (MT <= 2) ? 4 : 2;
 
   int kb = wave;
@@ -48,10 +51,16 @@ __global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(const bf16_t* __res
     for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        Frag b;
+        Frag b, bl;
         b.u = make_uint4(0, 0, 0, 0);
-        if (mt * 16 + r16 < R) b.u = *(const uint4*)(xp + (int64_t)mt * 16 * K + (int64_t)(kb + u * WPB) * 32);
+        bl.u = make_uint4(0, 0, 0, 0);
+        if (mt * 16 + r16 < R) {
+          const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)(kb + u * WPB) * 32;
+          b.u = *(const uint4*)x;
+          bl.u = *(const uint4*)(x + lo_plane);
+        }
         acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u].v, b.v, acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u].v, bl.v, acc[mt], 0, 0, 0);
       }
     }
   }
@@ -60,10 +69,16 @@ __global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(const bf16_t* __res
     a.u = *(const uint4*)(wp + (int64_t)kb * 32);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      Frag b;
+      Frag b, bl;
       b.u = make_uint4(0, 0, 0, 0);
-      if (mt * 16 + r16 < R) b.u = *(const uint4*)(xp + (int64_t)mt * 16 * K + (int64_t)kb * 32);
+      bl.u = make_uint4(0, 0, 0, 0);
+      if (mt * 16 + r16 < R) {
+        const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)kb * 32;
+        b.u = *(const uint4*)x;
+        bl.u = *(const uint4*)(x + lo_plane);
+      }
       acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, bl.v, acc[mt], 0, 0, 0);
     }
   }
 

@@ -59,6 +59,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
                                                       int d, float eps) {
   __shared__ float sh[4];
   const int row = blockIdx.x;
+  const int64_t lo_plane = (int64_t)gridDim.x * d;
   const float* x = h + (int64_t)row * d;
   float ss = 0.f;
   for (int i = threadIdx.x * 4; i < d; i += 1024) {
@@ -72,8 +73,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     const float4 gg = *(const float4*)(g + i);
     const float o0 = v.x * inv * gg.x, o1 = v.y * inv * gg.y, o2 = v.z * inv * gg.z, o3 = v.w * inv * gg.w;
     if constexpr (sizeof(T) == 2) {
-      ushort4 o = make_ushort4(f32_to_bf16(o0), f32_to_bf16(o1), f32_to_bf16(o2), f32_to_bf16(o3));
-      *(ushort4*)(out + (int64_t)row * d + i) = o;
+      ushort4 hi, lo;
+      split_bf16(o0, hi.x, lo.x);
+      split_bf16(o1, hi.y, lo.y);
+      split_bf16(o2, hi.z, lo.z);
+      split_bf16(o3, hi.w, lo.w);
+      *(ushort4*)(out + (int64_t)row * d + i) = hi;
+      *(ushort4*)(out + lo_plane + (int64_t)row * d + i) = lo;
     } else {
       *(float4*)(out + (int64_t)row * d + i) = make_float4(o0, o1, o2, o3);
     }
@@ -108,8 +114,8 @@ hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int he
   return hipGetLastError();
 }
 
-// grid (rows, n_heads + 2*n_kv_heads), block head_dim/2.  q heads: rotated in place (rounded to the storage
-// precision, kept as float).  k heads: rotated and stored to the cache; v heads: stored to the cache.
+// grid (rows, n_heads + 2*n_kv_heads), block head_dim/2.  q heads: rotated in place (float32).
+// k heads: rotated and stored to the cache in its storage type; v heads: stored to the cache.
 template <typename T>
 __global__ void rope_kv_kernel(float* __restrict__ qkv, const float2* __restrict__ table, RowDesc rd, KvView kv, int layer, int R,
                                int n_heads, uint32_t* __restrict__ status) {
@@ -120,10 +126,8 @@ __global__ void rope_kv_kernel(float* __restrict__ qkv, const float2* __restrict
   const float x1 = p[i], x2 = p[i + half];
   const float2 cs = table[(int64_t)row * half + i];
   if (head < n_heads) {
-    float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
-    if constexpr (sizeof(T) == 2) { y1 = round_bf16(y1); y2 = round_bf16(y2); }
-    p[i] = y1;
-    p[i + half] = y2;
+    p[i] = x1 * cs.x - x2 * cs.y;
+    p[i + half] = x2 * cs.x + x1 * cs.y;
     return;
   }
   const int slot = rd.slot[row];
@@ -139,8 +143,8 @@ __global__ void rope_kv_kernel(float* __restrict__ qkv, const float2* __restrict
   T* dst = (T*)(is_k ? kv.k : kv.v) + off;
   float y1 = x1, y2 = x2;
   if (is_k) { y1 = x1 * cs.x - x2 * cs.y; y2 = x2 * cs.x + x1 * cs.y; }
-  if constexpr (sizeof(T) == 2) { dst[i] = f32_to_bf16(y1); dst[i + half] = f32_to_bf16(y2); }
-  else { dst[i] = y1; dst[i + half] = y2; }
+  dst[i] = (T)y1;  // round to nearest even for the half type
+  dst[i + half] = (T)y2;
 }
 
 hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
@@ -148,7 +152,7 @@ hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowD
   const int rows = B * R;
   if (rows <= 0) return hipSuccess;
   dim3 grid(rows, n_heads + 2 * kv.n_kv_heads), block(kv.head_dim / 2);
-  if (dtype == 1) hipLaunchKernelGGL((rope_kv_kernel<bf16_t>), grid, block, 0, s, qkv, table, rd, kv, layer, R, n_heads, status);
+  if (dtype == 1) hipLaunchKernelGGL((rope_kv_kernel<kv16_t>), grid, block, 0, s, qkv, table, rd, kv, layer, R, n_heads, status);
   else hipLaunchKernelGGL((rope_kv_kernel<float>), grid, block, 0, s, qkv, table, rd, kv, layer, R, n_heads, status);
   return hipGetLastError();
 }
@@ -161,7 +165,7 @@ __global__ void silu_mul_kernel(const float* __restrict__ gu, T* __restrict__ ac
   const int row = (int)(idx / f), j = (int)(idx % f);
   const float g = gu[(int64_t)row * 2 * f + j], u = gu[(int64_t)row * 2 * f + f + j];
   const float a = g / (1.0f + expf(-g)) * u;
-  if constexpr (sizeof(T) == 2) act[idx] = f32_to_bf16(a);
+  if constexpr (sizeof(T) == 2) split_bf16(a, act[idx], act[(int64_t)rows * f + idx]);
   else act[idx] = a;
 }
 

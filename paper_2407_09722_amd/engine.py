@@ -48,7 +48,7 @@ class DeviceKV:
         self.shape, self.batch, self.page_size = shape, batch, page_size
         self.max_pages = (max_tokens + page_size - 1) // page_size
         self.n_pages = self.max_pages * batch
-        dt = torch.int16 if shape.dtype == "bf16" else torch.float32
+        dt = torch.float16 if shape.dtype == "bf16" else torch.float32
         dims = (shape.n_layers, self.n_pages, page_size, shape.n_kv_heads, shape.head_dim)
         self.k = torch.zeros(dims, dtype=dt, device=device)
         self.v = torch.zeros(dims, dtype=dt, device=device)
@@ -66,8 +66,6 @@ class DeviceKV:
         out = []
         for x in (self.k, self.v):
             flat = x.reshape(x.shape[0], -1, x.shape[3], x.shape[4])[:, idx]
-            if x.dtype == torch.int16:
-                flat = (flat.to(torch.int32) << 16).view(torch.float32)
             out.append(flat.double().cpu().numpy())
         return out
 

@@ -1,0 +1,146 @@
+"""Free-running parity of the HIP path against the oracle, iteration by iteration.
+
+Both sides start from the same seeded weights and prompt and run on their own.  Every iteration the
+beam history, tree, target logits, log-likelihoods, accept decision, bonus token and cache lengths
+are compared.  Integer decisions must be identical; a difference is only excused when the oracle
+reports that the decision's margin is below the logit tolerance (then the runs legitimately part
+and the comparison stops).  Returns statistics of what was compared."""
+import numpy as np
+import torch
+
+import synth_inputs as si
+from oracle import mtad
+from oracle.lm import CachedSession, DecoderLM
+
+
+def logit_tolerance(dtype):
+    # fp32: 1e-4 relative to max(1, |value|); bf16: 2e-2 absolute
+    return (1e-4, 1e-4) if dtype == "fp32" else (0.0, 2e-2)
+
+
+def close(got, want, dtype, what=""):
+    rtol, atol = logit_tolerance(dtype)
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want)
+    lim = atol + rtol * np.abs(want)
+    assert np.all(err <= lim), f"{what}: max err {err.max():.3e} (limit {lim.flat[int(np.argmax(err - lim))]:.3e})"
+    return float(err.max())
+
+
+def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, tau, sample_bonus=True,
+             sample_beam=False, seed=0, max_context=None, page_size=16, prefill_rows=64, check_kv=False,
+             max_iters=None, device="cuda:0"):
+    from paper_2407_09722_amd.engine import DeviceModel, Engine
+    prompt = np.asarray(prompt, np.int32)
+    B, n0 = prompt.shape
+    dtype = tshape.dtype
+    M = 1 + (gamma if mode == "mtad" else gamma * beam)
+    max_context = max_context or (n0 + new_tokens + 2 * (gamma + 1) + M + 8)
+    eng = Engine(DeviceModel(tshape, wt, device), DeviceModel(dshape, wd, device), batch=B, gamma=gamma, beam=beam,
+                 mode=mode, max_context=max_context, prefill_rows=prefill_rows, page_size=page_size, device=device)
+    lm_p, lm_q = DecoderLM(tshape, wt), DecoderLM(dshape, wd)
+    sp = [CachedSession(lm_p, list(prompt[s])) for s in range(B)]
+    sq = [CachedSession(lm_q, list(prompt[s])) for s in range(B)]
+    eng.prefill(prompt)
+    stats = {"iters": 0, "excused": 0, "max_logit_err": 0.0, "eta": [], "tokens": [[] for _ in range(B)]}
+    _, atol = logit_tolerance(dtype)
+    margin_tol = max(atol, 1e-4) * 2
+    alive = [True] * B
+    while min(len(t) for t in stats["tokens"]) < new_tokens and (max_iters is None or stats["iters"] < max_iters):
+        eng.draft_phase(sample_beam, seed)
+        eng.verify_phase()
+        eng.accept_phase(tau, sample_bonus, seed)
+        torch.cuda.synchronize()
+        g = {k: getattr(eng, k).cpu().numpy() for k in ("h_tok", "h_parent", "h_cum", "t_tok", "t_parent", "t_depth", "t_src",
+                                                         "t_mask", "t_qref", "logp_cond", "row_lse", "logits", "eta", "path",
+                                                         "bonus_row", "bonus_tok", "out_tok", "out_cnt")}
+        eng.commit_phase()
+        torch.cuda.synchronize()
+        post = {k: getattr(eng, k).cpu().numpy() for k in ("root_tok", "catchup_tok", "catchup_cnt")}
+        tlen, dlen = eng.tkv.len.cpu().numpy(), eng.dkv.len.cpu().numpy()
+        for s in range(B):
+            if not alive[s]:
+                continue
+            tr = mtad.iteration(sq[s], sp[s], gamma=gamma, beam=beam, mode=mode, tau=tau, stochastic_beam=sample_beam,
+                                sample_bonus=sample_bonus, seed=seed, seq_index=s, dt=np.float32)
+            h = tr["hist"]
+            # --- draft: beam history
+            for i in range(gamma):
+                same = np.array_equal(g["h_tok"][s, i], h["tok"][i]) and np.array_equal(g["h_parent"][s, i], h["parent"][i])
+                if not same:
+                    assert h["margin"][i] < margin_tol or _near_tie(h["score"][i], margin_tol), \
+                        f"seq {s} iter {stats['iters']} beam step {i}: survivors differ, margin {h['margin'][i]}"
+                    alive[s] = False
+                    break
+                close(g["h_cum"][s, i], h["score"][i], dtype, f"cum_logq step {i}")
+            if not alive[s]:
+                stats["excused"] += 1
+                continue
+            # --- tree
+            t = tr["tree"]
+            assert np.array_equal(g["t_tok"][s, 1:], t["tok"][1:]) and np.array_equal(g["t_parent"][s], t["parent"])
+            assert np.array_equal(g["t_depth"][s], t["depth"]) and np.array_equal(g["t_src"][s, 1:], t["src_beam"][1:])
+            assert np.array_equal(g["t_mask"][s].view(np.uint64), mtad.ancestor_masks(t["parent"]))
+            close(g["t_qref"][s], t["qref"], dtype, "qref")
+            # --- verify
+            v = tr["verify"]
+            stats["max_logit_err"] = max(stats["max_logit_err"], close(g["logits"][s], v["logits"], dtype, "target logits"))
+            close(g["row_lse"][s], v["lse"], dtype, "row lse")
+            close(g["logp_cond"][s], v["logp_cond"], dtype, "logp_cond")
+            # --- accept + bonus
+            if g["eta"][s] != tr["eta"] or g["bonus_row"][s] != tr["node"]:
+                assert min(tr["accept_margins"]) < margin_tol * gamma, f"accept differs: {g['eta'][s]} vs {tr['eta']}"
+                alive[s] = False
+                stats["excused"] += 1
+                continue
+            assert list(g["path"][s, :tr["eta"]]) == tr["path_rows"] and np.all(g["path"][s, tr["eta"]:] == -1)
+            if g["bonus_tok"][s] != tr["bonus"]:
+                assert tr["bonus_gap"] < margin_tol, f"bonus token differs with gap {tr['bonus_gap']}"
+                alive[s] = False
+                stats["excused"] += 1
+                continue
+            assert g["out_cnt"][s] == tr["eta"] + 1 and list(g["out_tok"][s, :tr["eta"] + 1]) == tr["emitted"]
+            # --- commit: lengths and next-iteration state
+            assert tlen[s] == len(sp[s].context) - 1
+            pend = sq[s].context[sq[s].n_cached:]
+            assert dlen[s] == sq[s].n_cached and post["catchup_cnt"][s] == len(pend)
+            assert list(post["catchup_tok"][s, :len(pend)]) == pend and post["root_tok"][s] == sp[s].context[-1]
+            if check_kv:
+                _check_kv(eng.tkv, s, sp[s], dtype)
+                _check_kv(eng.dkv, s, sq[s], dtype)
+            stats["eta"].append(tr["eta"])
+            stats["tokens"][s] += tr["emitted"]
+        stats["iters"] += 1
+        if not any(alive):
+            break
+    status = _status(eng)
+    eng.close()
+    assert status == 0, f"device status {status:#x}"
+    return stats
+
+
+def _near_tie(scores, tol):
+    s = np.sort(np.asarray(scores, np.float64))
+    return len(s) > 1 and np.min(np.diff(s)) < tol
+
+
+def _status(eng):
+    from paper_2407_09722_amd import binding as mb
+    return mb.mtad_device_status(eng.ctx)
+
+
+def _check_kv(kv, s, sess, dtype):
+    n = sess.n_cached
+    if n == 0:
+        return
+    K, V = kv.gather(s, n)
+    wantK = np.stack([k[:n] for k in sess.ck])
+    wantV = np.stack([v[:n] for v in sess.cv])
+    # A structural check (right slot, right row after the commit gather): a wrong row is off by O(1).  float32
+    # caches agree to 1e-4; half-precision caches to a few grid steps (a rounding that lands on the other side of
+    # a midpoint in an earlier layer moves every later value of that token a little)
+    if dtype == "fp32":
+        assert np.allclose(K, wantK, rtol=1e-4, atol=1e-5) and np.allclose(V, wantV, rtol=1e-4, atol=1e-5)
+    else:
+        for got, want in ((K, wantK), (V, wantV)):
+            assert np.all(np.abs(got - want) <= np.abs(want) * 2 ** -8 + 4e-3), float(np.abs(got - want).max())

@@ -26,8 +26,10 @@ def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None):
     ldy = ldy or N
     Y0 = g.standard_normal((R, ldy)).astype(np.float32)
     if dtype == 1:
-        Wd, Xd = _bits(W), _bits(X)
-        W, X = si.bf16_bits_to_f32(si.f32_to_bf16_bits(W)), si.bf16_bits_to_f32(si.f32_to_bf16_bits(X))
+        hi = si.bf16_bits_to_f32(si.f32_to_bf16_bits(X))
+        lo = si.bf16_bits_to_f32(si.f32_to_bf16_bits(X - hi))
+        Wd, Xd = _bits(W), _bits(np.stack([hi, lo]))                     # activation = hi + lo planes
+        W, X = si.bf16_bits_to_f32(si.f32_to_bf16_bits(W)), hi.astype(np.float64) + lo
     else:
         Wd, Xd = torch.from_numpy(W).to(DEV), torch.from_numpy(X).to(DEV)
     Yd = torch.from_numpy(Y0).to(DEV)
@@ -78,14 +80,16 @@ def test_rmsnorm(dtype):
     for rows, d in ((1, 128), (5, 4096), (17, 768), (41, 5120)):
         h = (g.standard_normal((rows, d)) * 3).astype(np.float32)
         gain = (1 + 0.1 * g.standard_normal(d)).astype(np.float32)
-        out = torch.zeros((rows, d), dtype=torch.int16 if dtype else torch.float32, device=DEV)
+        out = torch.zeros((2, rows, d) if dtype else (rows, d), dtype=torch.int16 if dtype else torch.float32, device=DEV)
         mb.mtad_k_rmsnorm(dtype, torch.from_numpy(h).to(DEV), torch.from_numpy(gain).to(DEV), out, rows, d, 1e-5)
         torch.cuda.synchronize()
         x = h.astype(np.float64)
         want = x / np.sqrt((x * x).mean(axis=1, keepdims=True) + 1e-5) * gain
         if dtype:
-            got = si.bf16_bits_to_f32(out.cpu().numpy().view(np.uint16)).astype(np.float64)
-            assert np.all(np.abs(got - want) <= np.abs(want) * 2 ** -8 + 1e-30)      # half a bf16 ulp, rounded once
+            planes = si.bf16_bits_to_f32(out.cpu().numpy().view(np.uint16)).astype(np.float64)
+            got = planes[0] + planes[1]
+            assert np.all(np.abs(planes[0] - want) <= np.abs(want) * 2 ** -8)        # hi = nearest bfloat16
+            assert np.all(np.abs(got - want) <= np.abs(want) * 2 ** -15)             # hi + lo: ~16 significant bits
         else:
             got = out.cpu().numpy().astype(np.float64)
             assert np.allclose(got, want, rtol=2e-6, atol=1e-7)

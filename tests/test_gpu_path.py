@@ -1,0 +1,87 @@
+"""GPU parity of the whole hot path (draft beam steps, tree, target pass, accept, commit) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from tests._parity import run_pair
+
+pytestmark = pytest.mark.gpu
+
+
+def _weights(shape, seed, role, boost=None):
+    w = si.make_weights(shape, seed, role, threads=8)
+    if boost:        # larger projections make attention and the FFN matter in small random models
+        for k in list(w):
+            if w[k].ndim == 2 and k not in ("unembed", "embed"):
+                x = w[k] if w[k].dtype != np.uint16 else si.bf16_bits_to_f32(w[k])
+                x = (x * boost).astype(np.float32)
+                w[k] = si.f32_to_bf16_bits(x) if shape.dtype == "bf16" else x
+    return w
+
+
+SMALL = {
+    "fp32": (si.ModelShape(2, 128, 2, 2, 64, 344, 1024, "fp32"), si.ModelShape(1, 128, 2, 1, 64, 172, 1024, "fp32")),
+    "bf16": (si.ModelShape(2, 128, 4, 2, 64, 352, 1024, "bf16"), si.ModelShape(1, 64, 1, 1, 64, 160, 1024, "bf16")),
+    "bf16_hd128": (si.ModelShape(2, 256, 2, 1, 128, 352, 1024, "bf16"), si.ModelShape(1, 128, 1, 1, 128, 160, 1024, "bf16")),
+}
+
+
+@pytest.mark.parametrize("kind", list(SMALL))
+@pytest.mark.parametrize("mode", ["mtad", "mmtad"])
+@pytest.mark.parametrize("tau", [0.3, 0.0])
+def test_small_pairs_every_iteration_matches(kind, mode, tau):
+    ts, ds = SMALL[kind]
+    print(f"small pair {kind} {mode} tau={tau}", flush=True)
+    wt, wd = _weights(ts, 11, "target", boost=4.0), _weights(ds, 11, "draft", boost=4.0)
+    prompt = np.random.default_rng(5).integers(0, ts.vocab, (1, 37)).astype(np.int32)
+    st = run_pair(ts, ds, wt, wd, prompt, 20, gamma=4, beam=3, mode=mode, tau=tau, seed=7, prefill_rows=16, check_kv=True)
+    assert st["excused"] == 0 and sum(len(t) for t in st["tokens"]) >= 20
+    if tau == 0.0:
+        assert all(e == 4 for e in st["eta"])          # tau = 0 passes every prefix: commit / gather path
+
+
+def test_identical_models_accept_everything():
+    """draft == target: every joint ratio is 1, so eta = gamma in every iteration for any tau < 1."""
+    ts = SMALL["fp32"][0]
+    w = _weights(ts, 3, "target", boost=4.0)
+    prompt = np.random.default_rng(1).integers(0, ts.vocab, (1, 9)).astype(np.int32)
+    for mode in ("mtad", "mmtad"):
+        st = run_pair(ts, ts, w, w, prompt, 25, gamma=4, beam=2, mode=mode, tau=0.9, seed=1, check_kv=True)
+        assert st["excused"] == 0 and all(e == 4 for e in st["eta"])
+
+
+def test_batch_of_sequences_with_stochastic_beams():
+    ts, ds = SMALL["bf16"]
+    wt, wd = _weights(ts, 21, "target", boost=4.0), _weights(ds, 21, "draft", boost=4.0)
+    prompt = np.random.default_rng(2).integers(0, ts.vocab, (3, 21)).astype(np.int32)
+    st = run_pair(ts, ds, wt, wd, prompt, 12, gamma=3, beam=4, mode="mmtad", tau=0.0, seed=9, sample_beam=True, check_kv=True)
+    assert st["excused"] == 0
+
+
+def test_one_token_prompt_and_gamma_one():
+    ts, ds = SMALL["fp32"]
+    wt, wd = _weights(ts, 4, "target"), _weights(ds, 4, "draft")
+    st = run_pair(ts, ds, wt, wd, np.array([[17]], np.int32), 6, gamma=1, beam=1, mode="mtad", tau=0.0, seed=2, check_kv=True)
+    assert st["excused"] == 0 and all(e == 1 for e in st["eta"])
+
+
+def test_workload_c1_full_run():
+    """C1 as specified: fp32 pair, seed 0, prompt 32, gamma 4, beam 2, 64 new tokens; decisions bit-exact."""
+    w = si.WORKLOADS["C1"]
+    wt, wd = si.make_weights(w.target, w.seed, "target"), si.make_weights(w.draft, w.seed, "draft")
+    for tau in (w.tau, 0.0):
+        st = run_pair(w.target, w.draft, wt, wd, si.make_prompt(w), w.new_tokens, gamma=w.gamma, beam=w.beam, mode=w.mode,
+                      tau=tau, seed=w.seed)
+        assert st["excused"] == 0 and len(st["tokens"][0]) >= w.new_tokens
+        print(f"C1 tau={tau}: {st['iters']} iterations, mean eta {np.mean(st['eta']):.2f}, max logit err {st['max_logit_err']:.2e}")
+
+
+def test_workload_c2_shape_short_run():
+    """C2 shapes (bf16, 12-layer target, vocab 32000), prompt 128, first 24 new tokens."""
+    w = si.WORKLOADS["C2"]
+    wt, wd = si.make_weights(w.target, w.seed, "target"), si.make_weights(w.draft, w.seed, "draft")
+    st = run_pair(w.target, w.draft, wt, wd, si.make_prompt(w), 24, gamma=w.gamma, beam=w.beam, mode=w.mode, tau=w.tau,
+                  seed=w.seed)
+    assert st["iters"] >= 5
+    print(f"C2: {st['iters']} iterations, excused {st['excused']}, max logit err {st['max_logit_err']:.2e}")
