@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the MTAD/MMTAD hot path on one MI355X.
+
+A step = one whole iteration of the method (gamma beam steps on the draft model, tree build,
+one target pass, accept, KV commit) over one batch of synthetic input.  Default workload: C3
+(7B-shaped bf16 target, 512-token prompt, gamma 4, beam 4).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def weight_bytes(shape):
+    """Bytes of the matrices one pass streams: every layer matrix and the unembedding, once."""
+    e = 2 if shape.dtype == "bf16" else 4
+    d, f = shape.d_model, shape.d_ffn
+    per_layer = shape.qkv_rows * d + d * shape.n_heads * shape.head_dim + 2 * f * d + d * f
+    return (shape.n_layers * per_layer + shape.vocab * d) * e
+
+
+def kv_bytes_per_token(shape):
+    e = 2 if shape.dtype == "bf16" else 4
+    return 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * e
+
+
+def target_gemm_shapes(shape):
+    d, f = shape.d_model, shape.d_ffn
+    per_layer = [(shape.qkv_rows, d), (d, shape.n_heads * shape.head_dim), (2 * f, d), (d, f)]
+    return per_layer, (shape.vocab, d)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--tau", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (requests are independent; more GPUs would each run this "
+              "same path on their own share of the requests). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2407_09722_amd import binding as mb
+    from paper_2407_09722_amd.engine import DeviceModel, Engine
+    mb.lib()                                            # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    w = si.WORKLOADS[args.workload]
+    tau = w.tau if args.tau is None else args.tau
+    K, W = args.steps, args.warmup
+    threads = min(16, os.cpu_count() or 8)
+
+    t0 = time.time()
+    tm = DeviceModel(w.target, lambda n: si.make_tensor(w.target, w.seed, "target", n), dev, threads=threads)
+    dm = DeviceModel(w.draft, lambda n: si.make_tensor(w.draft, w.seed, "draft", n), dev, threads=threads)
+    t_weights = time.time() - t0
+    prompt = si.make_prompt(w)
+    M = w.tree_rows
+    total_iters = 2 * (K + W) + 8
+    max_ctx = w.prompt_len + total_iters * (w.gamma + 1) + M + 64
+    eng = Engine(tm, dm, batch=w.batch, gamma=w.gamma, beam=w.beam, mode=w.mode, max_context=max_ctx, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def timed_region(tau_run):
+        """W warm-up + K timed iterations from a fresh prefill; returns (seconds, tokens, mean context)."""
+        eng.prefill(prompt)
+        for _ in range(W):
+            eng.iteration(tau_run, seed=w.seed)
+        torch.cuda.synchronize()
+        len0 = eng.tkv.len.clone()
+        t = time.perf_counter()
+        for _ in range(K):
+            eng.iteration(tau_run, seed=w.seed)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        len1 = eng.tkv.len.clone()
+        tokens = int((len1 - len0).sum().item())           # every committed token lengthens the cache by one
+        n_mean = float((len0.float().mean().item() + len1.float().mean().item()) / 2)
+        return dt, tokens, n_mean
+
+    dt, tokens, n_mean = timed_region(tau)
+    status = mb.mtad_device_status(eng.ctx)
+    dt0, tokens0, _ = timed_region(0.0)                  # tau = 0 passes every prefix: gamma+1 tokens per iteration
+    status |= mb.mtad_device_status(eng.ctx)
+
+    # --- verify step alone, HIP events on the launch stream --------------------------------------------------
+    eng.prefill(prompt)
+    eng.draft_phase(seed=w.seed)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(3):
+        eng.verify_phase()
+    ev[0].record(stream)
+    for _ in range(K):
+        eng.verify_phase()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    verify_ms = ev[0].elapsed_time(ev[1]) / K
+    n_ctx = int(eng.tkv.len[0].item())
+    verify_bytes = weight_bytes(w.target) + w.batch * n_ctx * kv_bytes_per_token(w.target)
+    verify = {"ms": round(verify_ms, 4), "context": n_ctx, "rows": w.batch * M,
+              "algorithmic_GB": round(verify_bytes / 1e9, 4),
+              "GBps": round(verify_bytes / verify_ms / 1e6, 1),
+              "frac_of_hbm_peak": round(verify_bytes / verify_ms / 1e6 / HBM_PEAK_GBS, 4)}
+
+    # --- dominant kernel: the skinny GEMM over the target's weight matrices, launched back to back -----------
+    rows = w.batch * M
+    per_layer, head = target_gemm_shapes(w.target)
+    esz = 2 if w.target.dtype == "bf16" else 4
+    dt_id = 1 if w.target.dtype == "bf16" else 0
+    kmax = max(k for _, k in per_layer + [head])
+    nmax = max(n for n, _ in per_layer + [head])
+    X = torch.zeros(2 * rows * kmax, dtype=torch.int16 if dt_id else torch.float32, device=dev)
+    Y = torch.zeros(rows * nmax, dtype=torch.float32, device=dev)
+    launches = []
+    for l in range(w.target.n_layers):
+        for j, idx in enumerate((1, 2, 4, 5)):
+            n, k = per_layer[j]
+            launches.append((tm.tensors[1 + 6 * l + idx], n, k))
+    launches.append((tm.tensors[-1], head[0], head[1]))
+    gemm_bytes = sum(n * k * esz + rows * k * (4 if dt_id else 4) + rows * n * 4 for _, n, k in launches)
+
+    def replay():
+        for Wt, n, k in launches:
+            mb.mtad_k_gemm(dt_id, Wt, X, Y, rows, n, k, n, False)
+    replay()
+    reps = max(3, min(20, K // 3))
+    ev[0].record(stream)
+    for _ in range(reps):
+        replay()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    gemm_ms = ev[0].elapsed_time(ev[1]) / (reps * len(launches))
+    bytes_per_launch = gemm_bytes / len(launches)
+    achieved = bytes_per_launch / gemm_ms / 1e6
+    roofline = {"kernel": "gemm_bf16_kernel (skinny weight-streaming GEMM, all target matrices)" if dt_id else "gemm_f32_kernel",
+                "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(gemm_ms * 1e3, 3),
+                "launches_per_verify": len(launches)}
+
+    # --- the oracle on the host cores, bounded sample ---------------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, tau)
+
+    out = {
+        "metric": "accepted tokens/sec (1 GPU)", "value": round(tokens / dt, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(dt / K * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.target.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.mode.upper()} gamma={w.gamma} beam={w.beam} batch={w.batch} "
+                               f"prompt={w.prompt_len}, target L{w.target.n_layers} d{w.target.d_model} "
+                               f"ffn{w.target.d_ffn} V{w.target.vocab}, draft L{w.draft.n_layers} d{w.draft.d_model}; "
+                               f"random-init weights seed {w.seed}",
+                   "tau": tau, "tokens_per_iteration": round(tokens / K / w.batch, 3), "mean_context": round(n_mean, 1),
+                   "beam_search": "deterministic top-b", "bonus_token": "sampled (Gumbel-argmax)"},
+        "iterations_per_s": round(K / dt, 2),
+        "tau0": {"tokens_per_s": round(tokens0 / dt0, 2), "tokens_per_iteration": round(tokens0 / K / w.batch, 3),
+                 "ms_per_step": round(dt0 / K * 1e3, 4)},
+        "verify": verify, "roofline": roofline, "cpu_baseline": cpu,
+        "device_status": status, "weights_setup_s": round(t_weights, 1),
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, tau):
+    """The oracle as it stands, timed on this host: full iterations of the method at the workload's real widths
+    with a shortened context and the target cut to 2 and to 4 layers; the difference prices one layer and the
+    full depth is extrapolated.  A reported baseline, not a target."""
+    import threadpoolctl  # noqa: F401
+    from oracle import mtad
+    from oracle.lm import CachedSession, DecoderLM
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+    ctx_len, iters = 64, 2
+    L_full = w.target.n_layers
+    L_hi = min(4, L_full)
+    L_lo = min(2, L_hi)
+    shape_hi = w.target.with_layers(L_hi)
+    wt = si.make_weights(shape_hi, w.seed, "target", threads=cores)
+    wd = si.make_weights(w.draft, w.seed, "draft", threads=cores)
+    lm_q = DecoderLM(w.draft, wd)
+    prompt = si.make_prompt(w)[0, :ctx_len]
+    times, emitted = {}, 0
+    for L in sorted({L_lo, L_hi}):
+        lm_p = DecoderLM(w.target.with_layers(L), {k: v for k, v in wt.items() if not k.startswith("L") or int(k.split(".")[0][1:]) < L})
+        sq, sp = CachedSession(lm_q, list(prompt)), CachedSession(lm_p, list(prompt))
+        mtad.iteration(sq, sp, gamma=w.gamma, beam=w.beam, mode=w.mode, tau=tau, seed=w.seed)      # includes the prompt pass
+        t = time.perf_counter()
+        for _ in range(iters):
+            tr = mtad.iteration(sq, sp, gamma=w.gamma, beam=w.beam, mode=w.mode, tau=tau, seed=w.seed)
+            emitted += len(tr["emitted"])
+        times[L] = (time.perf_counter() - t) / iters
+    per_layer = (times[L_hi] - times[L_lo]) / max(1, L_hi - L_lo) if L_hi > L_lo else times[L_hi] / L_hi
+    t_full = times[L_lo] + per_layer * (L_full - L_lo)
+    tok_per_iter = emitted / (iters * len(times))
+    return {"value": round(w.batch * tok_per_iter / (t_full * w.batch), 4), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{iters} full iterations (draft beam search + target pass + accept) of one sequence at the real widths and "
+                      f"vocabulary, context {ctx_len}, target cut to {L_lo} and {L_hi} layers; per-layer time from the difference, "
+                      f"extrapolated to {L_full} layers: {t_full:.2f} s per iteration (numpy float64)",
+            "s_per_iteration_extrapolated": round(t_full, 3)}
+
+
+if __name__ == "__main__":
+    main()

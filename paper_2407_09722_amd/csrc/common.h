@@ -57,7 +57,7 @@ struct RowDesc {
 // Y[r][n] (+)= sum_k X[r][k] * W[n][k];  W [N][K] bf16 (dtype 1) or f32 (dtype 0); X f32 [R][K] (dtype 0) or two
 // bf16 planes [2][R][K] (hi, lo) whose sum is the activation (dtype 1); Y f32 [R][ldy]
 hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate,
-                       hipStream_t s);
+                       hipStream_t s, int tag = 0);
 hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, hipStream_t s);
 // out = rmsnorm(h) * g, written as hi/lo bf16 planes [2][rows][d] (dtype 1) or f32 [rows][d] (dtype 0)
 hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s);

@@ -23,7 +23,9 @@ union Frag {
   bf16x8 v;
 };
 
-template <int MT, int WPB>
+// TAG only names the call site (0 draft pass, 1 target pass, 2 component entry point) so that a kernel trace can
+// tell the target pass's weight stream from the draft's; the code is the same.
+template <int MT, int WPB, int TAG>
 __global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ X,
                                                              float* __restrict__ Y, int R, int N, int K, int ldy,
                                                              int accumulate) {
@@ -143,16 +145,22 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
   }
 }
 
-template <int MT, int WPB>
-static hipError_t run_bf16(const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool acc, hipStream_t s) {
+template <int MT, int WPB, int TAG>
+static hipError_t run_tagged(const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool acc, hipStream_t s) {
   const size_t lds = (size_t)WPB * MT * 64 * sizeof(float) * 4;
-  hipLaunchKernelGGL((gemm_bf16_kernel<MT, WPB>), dim3(N / 16), dim3(WPB * 64), lds, s, (const bf16_t*)W, (const bf16_t*)X, Y, R,
-                     N, K, ldy, acc ? 1 : 0);
+  hipLaunchKernelGGL((gemm_bf16_kernel<MT, WPB, TAG>), dim3(N / 16), dim3(WPB * 64), lds, s, (const bf16_t*)W, (const bf16_t*)X, Y,
+                     R, N, K, ldy, acc ? 1 : 0);
   return hipGetLastError();
+}
+template <int MT, int WPB>
+static hipError_t run_bf16(int tag, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool acc, hipStream_t s) {
+  if (tag == 1) return run_tagged<MT, WPB, 1>(W, X, Y, R, N, K, ldy, acc, s);
+  if (tag == 2) return run_tagged<MT, WPB, 2>(W, X, Y, R, N, K, ldy, acc, s);
+  return run_tagged<MT, WPB, 0>(W, X, Y, R, N, K, ldy, acc, s);
 }
 
 hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate,
-                       hipStream_t s) {
+                       hipStream_t s, int tag) {
   if (R <= 0) return hipSuccess;
   if (dtype == 0) {
     if (K % 4) return hipErrorInvalidValue;
@@ -165,14 +173,14 @@ hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R,
   const int mt = (R + 15) / 16;
   // few output tiles: more waves per tile so that every CU still has many loads in flight
   const bool wide = (N / 16) >= 1024;
-  if (mt <= 1) return wide ? run_bf16<1, 8>(W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<1, 16>(W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 2) return wide ? run_bf16<2, 8>(W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<2, 16>(W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 3) return run_bf16<3, 8>(W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 4) return run_bf16<4, 8>(W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 6) return run_bf16<6, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 8) return run_bf16<8, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 12) return run_bf16<12, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
-  return run_bf16<16, 4>(W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 1) return wide ? run_bf16<1, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<1, 16>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 2) return wide ? run_bf16<2, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<2, 16>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 3) return run_bf16<3, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 4) return run_bf16<4, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 6) return run_bf16<6, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 8) return run_bf16<8, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  if (mt <= 12) return run_bf16<12, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  return run_bf16<16, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
 }
 
 }  // namespace mtad

@@ -138,20 +138,21 @@ int decoder_pass(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hip
   const int qkvw = (H + 2 * m->n_kv_heads) * hd;
   const KvView kvv = view_of(kv, m);
   const int n_splits = splits_for(c, m, R);
+  const int tag = same_shape(m, &c->tshape) ? 1 : 0;
   const void* const* W = m->weights;
   HIP_TRY(c, launch_embed(dt, W[0], c->rd.tok, c->h, rows, d, m->vocab, s));
   HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s));
   for (int l = 0; l < m->n_layers; ++l) {
     const void* const* L = W + 1 + 6 * l;
     HIP_TRY(c, launch_rmsnorm(dt, c->h, (const float*)L[0], c->xn, rows, d, m->rms_eps, s));
-    HIP_TRY(c, launch_gemm(dt, L[1], c->xn, c->qkv, rows, qkvw, d, qkvw, false, s));
+    HIP_TRY(c, launch_gemm(dt, L[1], c->xn, c->qkv, rows, qkvw, d, qkvw, false, s, tag));
     HIP_TRY(c, launch_rope_kv(dt, c->qkv, c->rope, c->rd, kvv, l, B, R, H, c->status, s));
     HIP_TRY(c, launch_attention(dt, c->qkv, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->xn, s));
-    HIP_TRY(c, launch_gemm(dt, L[2], c->xn, c->h, rows, d, H * hd, d, true, s));
+    HIP_TRY(c, launch_gemm(dt, L[2], c->xn, c->h, rows, d, H * hd, d, true, s, tag));
     HIP_TRY(c, launch_rmsnorm(dt, c->h, (const float*)L[3], c->xn, rows, d, m->rms_eps, s));
-    HIP_TRY(c, launch_gemm(dt, L[4], c->xn, c->gu, rows, 2 * f, d, 2 * f, false, s));
+    HIP_TRY(c, launch_gemm(dt, L[4], c->xn, c->gu, rows, 2 * f, d, 2 * f, false, s, tag));
     HIP_TRY(c, launch_silu_mul(dt, c->gu, c->xn, rows, f, s));
-    HIP_TRY(c, launch_gemm(dt, L[5], c->xn, c->h, rows, d, f, d, true, s));
+    HIP_TRY(c, launch_gemm(dt, L[5], c->xn, c->h, rows, d, f, d, true, s, tag));
   }
   return MTAD_OK;
 }
@@ -160,7 +161,8 @@ int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* ls
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
   HIP_TRY(c, launch_rmsnorm(m->dtype, c->h, (const float*)W[tail], c->xn, rows, m->d_model, m->rms_eps, s));
-  HIP_TRY(c, launch_gemm(m->dtype, W[tail + 1], c->xn, logits, rows, m->vocab, m->d_model, m->vocab, false, s));
+  HIP_TRY(c, launch_gemm(m->dtype, W[tail + 1], c->xn, logits, rows, m->vocab, m->d_model, m->vocab, false, s,
+                         same_shape(m, &c->tshape) ? 1 : 0));
   HIP_TRY(c, launch_row_lse(logits, lse, rows, m->vocab, s));
   return MTAD_OK;
 }
@@ -367,7 +369,7 @@ int mtad_k_gemm(int32_t dtype, const void* W, const void* X, float* Y, int32_t R
   if (dtype != 0 && dtype != 1) return MTAD_EINVAL;
   if (dtype == 1 && ((N % 16) || (K % 32) || (ldy % 4) || R > 256)) return MTAD_ESHAPE;
   if (dtype == 0 && (K % 4)) return MTAD_ESHAPE;
-  return launch_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate != 0, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+  return launch_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate != 0, (hipStream_t)stream, 2) == hipSuccess ? MTAD_OK : MTAD_EHIP;
 }
 
 int mtad_k_rmsnorm(int32_t dtype, const float* h, const float* g, void* out, int32_t rows, int32_t d, float eps, void* stream) {

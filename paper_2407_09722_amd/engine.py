@@ -18,18 +18,28 @@ def _dev(x, device):
 class DeviceModel:
     """Weights of one decoder on the GPU plus the mtad_model descriptor pointing at them."""
 
-    def __init__(self, shape, weights: dict, device="cuda:0"):
+    def __init__(self, shape, weights, device="cuda:0", threads=8):
+        """weights: dict name -> array, or a callable name -> array (tensors are then produced a few at a
+        time and dropped after the upload, so a 7B-shaped model never sits in host memory whole)."""
         self.shape = shape
-        self.tensors = []
         names = ["embed"]
         for l in range(shape.n_layers):
             names += [f"L{l}.{k}" for k in ("g_attn", "w_qkv", "w_o", "g_ffn", "w_gu", "w_d")]
         names += ["g_final", "unembed"]
-        for n in names:
-            w = weights[n]
+        self.names = names
+
+        def upload(n):
+            w = weights(n) if callable(weights) else weights[n]
             if w.dtype == np.uint16:
                 w = w.view(np.int16)                       # bfloat16 bit patterns; torch keeps them as raw 16-bit words
-            self.tensors.append(_dev(w, device))
+            return _dev(w, device)
+
+        if callable(weights):
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(max_workers=threads) as ex:
+                self.tensors = list(ex.map(upload, names))
+        else:
+            self.tensors = [upload(n) for n in names]
         self._ptrs = (C.c_void_p * len(self.tensors))(*[t.data_ptr() for t in self.tensors])
         s = shape
         self.desc = mb.mtad_model(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab,
