@@ -159,6 +159,22 @@ def main():
                 "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(gemm_ms * 1e3, 3),
                 "launches_per_verify": len(launches)}
 
+    # --- plain copy of known size: reference for byte counters and for the bandwidth coalesced traffic reaches -----
+    cbytes = 1 << 30
+    src = torch.empty(cbytes, dtype=torch.uint8, device=dev)
+    dst = torch.empty(cbytes, dtype=torch.uint8, device=dev)
+    src.fill_(1)
+    mb.mtad_k_copy(src, dst, cbytes)
+    ev[0].record(stream)
+    for _ in range(5):
+        mb.mtad_k_copy(src, dst, cbytes)
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    copy_ms = ev[0].elapsed_time(ev[1]) / 5
+    copy_ref = {"bytes_read": cbytes, "bytes_written": cbytes, "ms": round(copy_ms, 4),
+                "GBps_read_plus_write": round(2 * cbytes / copy_ms / 1e6, 1)}
+    del src, dst
+
     # --- the oracle on the host cores, bounded sample ---------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -178,7 +194,7 @@ def main():
         "iterations_per_s": round(K / dt, 2),
         "tau0": {"tokens_per_s": round(tokens0 / dt0, 2), "tokens_per_iteration": round(tokens0 / K / w.batch, 3),
                  "ms_per_step": round(dt0 / K * 1e3, 4)},
-        "verify": verify, "roofline": roofline, "cpu_baseline": cpu,
+        "verify": verify, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
         "device_status": status, "weights_setup_s": round(t_weights, 1),
     }
     print(json.dumps(out))

@@ -37,6 +37,12 @@ int mtad_k_beam_topb(mtad_ctx *ctx, const float *logits, const float *lse, mtad_
                      const int32_t *catchup_cnt, const int32_t *len, int32_t rows_per_seq, int32_t vocab,
                      int32_t sample_beam, uint64_t seed, void *stream);
 
+/* Streaming copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned).  It moves exactly `bytes` in
+ * and `bytes` out, which makes it the reference for scaling the hardware's byte counters and for the bandwidth
+ * that perfectly coalesced traffic reaches on the device (the paper's cost model, Section 4, prices runs by
+ * their global-memory traffic). */
+int mtad_k_copy(const void *src, void *dst, int64_t bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -68,6 +68,7 @@ hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowD
 hipError_t launch_attention(int dtype, const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
                             float* partial, int n_splits, void* out, hipStream_t s);
 hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int rows, int f, hipStream_t s);
+hipError_t launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 hipError_t launch_row_lse(const float* logits, float* lse, int rows, int vocab, hipStream_t s);
 
 size_t attention_partial_floats(int B, int R, int n_heads, int head_dim, int n_splits);

@@ -197,4 +197,20 @@ hipError_t launch_row_lse(const float* logits, float* lse, int rows, int vocab, 
   return hipGetLastError();
 }
 
+// Plain streaming copy of n 16-byte words: the reference point for hardware byte counters (it reads and writes
+// exactly 16*n bytes) and for the bandwidth a trivially coalesced kernel reaches.
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t s) {
+  const int64_t n = bytes / 16;
+  if (n <= 0) return hipSuccess;
+  const int64_t want = (n + 255) / 256;
+  const int blocks = (int)(want < 256 * 16 ? want : 256 * 16);
+  hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n);
+  return hipGetLastError();
+}
+
 }  // namespace mtad

@@ -382,6 +382,11 @@ int mtad_k_row_lse(const float* logits, float* lse, int32_t rows, int32_t vocab,
   return launch_row_lse(logits, lse, rows, vocab, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
 }
 
+int mtad_k_copy(const void* src, void* dst, int64_t bytes, void* stream) {
+  if (!src || !dst || bytes < 16 || (bytes % 16) || (((uintptr_t)src | (uintptr_t)dst) & 15)) return MTAD_EINVAL;
+  return launch_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+}
+
 int mtad_k_beam_topb(mtad_ctx* c, const float* logits, const float* lse, mtad_beam* hist, int32_t step, const int32_t* catchup_cnt,
                      const int32_t* len, int32_t rows_per_seq, int32_t vocab, int32_t sample_beam, uint64_t seed, void* stream) {
   if (!c || !c->ws || !logits || !lse || !hist || !hist->tok || !hist->parent || !hist->cum_logq || !catchup_cnt || !len)
