@@ -65,7 +65,10 @@ typedef struct mtad_ctx mtad_ctx; /* opaque; owns the workspace descriptor, neve
  *   v heads), w_o [d_model, n_heads*head_dim], g_ffn [d_model] f32, w_gu [2*d_ffn, d_model] (gate rows,
  *   then up rows), w_d [d_model, d_ffn];
  *   g_final [d_model] f32; unembed [vocab, d_model].
- * Matrices are in `dtype`; norm gains are always float32. */
+ * Matrices are in `dtype`; norm gains are always float32.
+ * dtype 0: every matrix row-major [out_features][in_features].
+ * dtype 1: embed row-major; every other matrix in the tile-packed layout written by mtad_pack_matrix
+ * (w_qkv with MTAD_PACK_QKV, w_gu with MTAD_PACK_GATE_UP, the rest MTAD_PACK_PLAIN). */
 typedef struct {
   int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
   int32_t dtype; /* 0 float32, 1 bfloat16 */
@@ -147,6 +150,19 @@ int mtad_last_hip_error(const mtad_ctx *ctx); /* hipError_t of the last failed H
  * synchronises).  Bit 0: KV capacity exceeded; bit 1: speculative window (64 rows) exceeded;
  * bit 2: bad catch-up count.  0 = clean. */
 int mtad_device_status(mtad_ctx *ctx, uint32_t *host_bits, void *stream);
+
+/* Repacks a row-major bfloat16 matrix [N][K] (device) into the layout the matrix-core kernels stream: the 16x32
+ * tile (nt, kt) is 1 KiB contiguous at element offset (nt*(K/32) + kt)*512, lane l of a wavefront owning the 8
+ * elements of packed row l%16 at k = kt*32 + (l/16)*8.  Packed row j of strip nt is source row
+ *   PLAIN    nt*16 + j
+ *   QKV      head*head_dim + (j < 8 ? 8u + j : head_dim/2 + 8u + j-8), head = nt / (head_dim/16), u = nt % (head_dim/16)
+ *            (a strip holds rotary pairs, so the rotation happens in the product's epilogue)
+ *   GATE_UP  j < 8 ? 8nt + j : N/2 + 8nt + j-8   (a strip holds 8 gate and the matching 8 up features)
+ * Done once per matrix when a model is loaded; not part of an iteration.  src != dst.  N % 16 == 0, K % 32 == 0. */
+#define MTAD_PACK_PLAIN 0
+#define MTAD_PACK_QKV 1
+#define MTAD_PACK_GATE_UP 2
+int mtad_pack_matrix(int32_t kind, const void *src, void *dst, int32_t N, int32_t K, int32_t head_dim, void *stream);
 
 /* ---- prompt ------------------------------------------------------------------------------------ */
 

@@ -14,7 +14,8 @@ extern "C" {
 
 /* The few-row matrix product of every projection, FFN matrix and the lm_head of a pass (the weight stream the
  * paper's cost argument is about, Section 4: time and energy are dominated by reading the weights once per run).
- * Y[r][n] (+)= sum_k X[r][k] * W[n][k], r < R.  dtype 1: W bfloat16 [N][K]; X two bfloat16 planes [2][R][K]
+ * Y[r][n] (+)= sum_k X[r][k] * W[n][k], r < R.  dtype 1: W bfloat16 [N][K] tile-packed (mtad_pack_matrix,
+ * MTAD_PACK_PLAIN); X two bfloat16 planes [2][R][K]
  * (hi, lo) whose sum is the activation; float32 accumulation (N % 16 == 0, K % 32 == 0, R <= 256);
  * dtype 0: W, X float32 (K % 4 == 0).  Y float32 [R][ldy], ldy >= N, ldy % 4 == 0.
  * accumulate != 0 adds to Y (the residual connection). */

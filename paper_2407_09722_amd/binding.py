@@ -17,7 +17,7 @@ MTAD_MODE_MTAD, MTAD_MODE_MMTAD = 0, 1
 MTAD_MAX_ROWS, MTAD_MAX_BEAM = 64, 8
 
 EXPORTS = ["mtad_create", "mtad_destroy", "mtad_workspace_bytes", "mtad_bind_workspace", "mtad_strerror",
-           "mtad_last_hip_error", "mtad_device_status", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
+           "mtad_last_hip_error", "mtad_device_status", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
            "mtad_verify_tree", "mtad_accept", "mtad_kv_commit",
            "mtad_k_gemm", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_beam_topb", "mtad_k_copy"]
 
@@ -81,6 +81,7 @@ def lib():
         L.mtad_strerror.restype = C.c_char_p
         L.mtad_last_hip_error.argtypes = [vp]
         L.mtad_device_status.argtypes = [vp, P(C.c_uint32), vp]
+        L.mtad_pack_matrix.argtypes = [i32, vp, vp, i32, i32, i32, vp]
         L.mtad_prefill.argtypes = [vp, P(mtad_model), P(mtad_kv), vp, i32, vp]
         L.mtad_draft_beam_step.argtypes = [vp, P(mtad_model), P(mtad_kv), P(mtad_beam), i32, P(mtad_state), i32, u64, vp]
         L.mtad_build_tree.argtypes = [vp, P(mtad_beam), i32, P(mtad_tree), vp]
@@ -140,6 +141,13 @@ def mtad_device_status(ctx, stream=None) -> int:
     bits = C.c_uint32(0)
     _check("mtad_device_status", lib().mtad_device_status(ctx, C.byref(bits), _stream_ptr(stream)))
     return bits.value
+
+
+MTAD_PACK_PLAIN, MTAD_PACK_QKV, MTAD_PACK_GATE_UP = 0, 1, 2
+
+
+def mtad_pack_matrix(kind, src, dst, N, K, head_dim=0, stream=None):
+    _check("mtad_pack_matrix", lib().mtad_pack_matrix(kind, ptr(src), ptr(dst), N, K, head_dim, _stream_ptr(stream)))
 
 
 def mtad_prefill(ctx, model, kv, tokens: torch.Tensor, n_tokens: int, stream=None):

@@ -54,19 +54,20 @@ struct RowDesc {
 };
 
 // ---- launchers (kernels_*.hip) ----------------------------------------------------------------
-// Y[r][n] (+)= sum_k X[r][k] * W[n][k];  W [N][K] bf16 (dtype 1) or f32 (dtype 0); X f32 [R][K] (dtype 0) or two
-// bf16 planes [2][R][K] (hi, lo) whose sum is the activation (dtype 1); Y f32 [R][ldy]
-hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate,
-                       hipStream_t s, int tag = 0);
-hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, hipStream_t s);
+// h = E[tok]; bf16 models also get the first RMSNorm's input: planes [2][rows][d] of h*g0 and ssq[rows] = sum h^2
+hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, const float* g0,
+                        void* planes, float* ssq, hipStream_t s);
 // out = rmsnorm(h) * g, written as hi/lo bf16 planes [2][rows][d] (dtype 1) or f32 [rows][d] (dtype 0)
 hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s);
 hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s);
 // rotate q (in place in qkv, float32), rotate k and write k, v to the cache in its storage type
 hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
                           int n_heads, uint32_t* status, hipStream_t s);
-hipError_t launch_attention(int dtype, const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
-                            float* partial, int n_splits, void* out, hipStream_t s);
+// q: [rows][q_stride] float32 with head h at column h*head_dim; counters: zeroed ints [B][n_heads][ceil(R/16)]
+hipError_t launch_attention(int dtype, const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
+                            float* partial, int n_splits, int* counters, void* out, hipStream_t s);
+// lse[row] from per-strip (max, sum exp) partials [rows][NP]
+hipError_t launch_lse_finish(const float* lse_part, float* lse, int rows, int NP, hipStream_t s);
 hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int rows, int f, hipStream_t s);
 hipError_t launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 hipError_t launch_row_lse(const float* logits, float* lse, int rows, int vocab, hipStream_t s);

@@ -4,8 +4,9 @@
 //
 // Split-KV "flash decoding": grid = (key split, head x row chunk, sequence).  A workgroup stages 64-key
 // K and V tiles in LDS once and reuses them for its (up to 16) query rows, keeps running max / sum /
-// output per row, and writes one partial per split; a second kernel merges the partials in a fixed
-// order.  Everything is float32 arithmetic; K/V are read in their storage type (half or float32).
+// output per row, and writes one partial per split; the workgroup that finishes last for a (sequence, head,
+// row chunk) merges the partials in split order (deterministic) and writes the attention output, so no second
+// kernel is needed.  Everything is float32 arithmetic; K/V are read in their storage type (half or float32).
 #include "common.h"
 
 #include <type_traits>
@@ -29,10 +30,10 @@ __device__ __forceinline__ float wmax(float v) {
   return v;
 }
 
-template <typename T, int HD>
-__global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict__ qkv, RowDesc rd, KvView kv, int layer, int R,
-                                                        int n_heads, int n_chunks, float scale, float* __restrict__ partial,
-                                                        int n_splits) {
+template <typename T, typename OutT, int HD>
+__global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
+                                                        int R, int n_heads, int n_chunks, float scale, float* __restrict__ partial,
+                                                        int n_splits, int* __restrict__ counters, OutT* __restrict__ out) {
   using C = AttnCfg<T, HD>;
   constexpr int TK = C::TK, KS = C::KSTRIDE;
   constexpr int NRG = 256 / TK, RPT = RB / NRG;    // score phase: row groups, rows per thread
@@ -44,6 +45,7 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
   __shared__ float s_s[RB][TK];
   __shared__ float m_s[RB], l_s[RB], a_s[RB];
   __shared__ unsigned long long mask_s[RB];
+  __shared__ int last_s;
 
   const int split = blockIdx.x;
   const int head = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
@@ -53,7 +55,6 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
   const int nrows = min(RB, R - row0);
   const int KVH = kv.n_kv_heads;
   const int g = head * KVH / n_heads;
-  const int width = (n_heads + 2 * KVH) * HD;
   const int len = kv.len[seq];
   int nspec = rd.nspec[seq];
   nspec = max(0, min(nspec, 64));
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
   // queries of this chunk and head
   for (int i = t; i < RB * HD; i += 256) {
     const int r = i / HD, d = i % HD;
-    q_s[r][d] = (r < nrows) ? qkv[(int64_t)(seq * R + row0 + r) * width + (int64_t)head * HD + d] : 0.f;
+    q_s[r][d] = (r < nrows) ? q[(int64_t)(seq * R + row0 + r) * q_stride + (int64_t)head * HD + d] : 0.f;
   }
   if (t < RB) {
     m_s[t] = -INFINITY;
@@ -188,27 +189,42 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
       }
     }
   }
-}
 
-// grid (B*R, n_heads), block HD: merge the splits of one (row, head)
-template <typename T, int HD>
-__global__ void attn_combine_kernel(const float* __restrict__ partial, T* __restrict__ out, int R, int n_heads, int n_splits) {
-  const int row = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
-  const int seq = row / R, r = row % R;
-  const float* p = partial + (((int64_t)seq * n_heads + head) * R + r) * n_splits * (HD + 2);
-  float M = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, p[(int64_t)s * (HD + 2)]);
-  float L = 0.f, o = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float m = p[(int64_t)s * (HD + 2)];
-    const float w = (m == -INFINITY) ? 0.f : expf(m - M);
-    L = fmaf(p[(int64_t)s * (HD + 2) + 1], w, L);
-    o = fmaf(p[(int64_t)s * (HD + 2) + 2 + d], w, o);
+  // the workgroup that arrives last merges the splits of its rows
+  __threadfence();
+  __syncthreads();
+  if (t == 0) {
+    int* c = counters + ((int64_t)seq * n_heads + head) * n_chunks + chunk;
+    const int prev = atomicAdd(c, 1);
+    last_s = (prev == n_splits - 1);
+    if (last_s) *c = 0;  // everyone has arrived: leave the counter clean for the next launch
   }
-  const float y = (L > 0.f) ? o / L : 0.f;
-  const int64_t idx = (int64_t)row * n_heads * HD + (int64_t)head * HD + d;
-  if constexpr (sizeof(T) == 2) split_bf16(y, out[idx], out[(int64_t)gridDim.x * n_heads * HD + idx]);  // hi / lo planes
-  else out[idx] = y;
+  __syncthreads();
+  if (!last_s) return;
+  __threadfence();
+  {
+    const int d = t % HD, rg2 = t / HD;
+    const int64_t lo_plane = (int64_t)gridDim.z * R * n_heads * HD;
+#pragma unroll
+    for (int i = 0; i < RPT2; ++i) {
+      const int r = rg2 + NRG2 * i;
+      if (r >= nrows) continue;
+      const volatile float* p = partial + (((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits * (HD + 2);
+      float M = -INFINITY;
+      for (int s2 = 0; s2 < n_splits; ++s2) M = fmaxf(M, p[(int64_t)s2 * (HD + 2)]);
+      float L = 0.f, o = 0.f;
+      for (int s2 = 0; s2 < n_splits; ++s2) {
+        const float m = p[(int64_t)s2 * (HD + 2)];
+        const float w = (m == -INFINITY) ? 0.f : expf(m - M);
+        L = fmaf(p[(int64_t)s2 * (HD + 2) + 1], w, L);
+        o = fmaf(p[(int64_t)s2 * (HD + 2) + 2 + d], w, o);
+      }
+      const float y = (L > 0.f) ? o / L : 0.f;
+      const int64_t idx = (int64_t)(seq * R + row0 + r) * n_heads * HD + (int64_t)head * HD + d;
+      if constexpr (sizeof(OutT) == 2) split_bf16(y, out[idx], out[lo_plane + idx]);  // hi / lo planes
+      else out[idx] = y;
+    }
+  }
 }
 
 size_t attention_partial_floats(int B, int R, int n_heads, int head_dim, int n_splits) {
@@ -216,27 +232,24 @@ size_t attention_partial_floats(int B, int R, int n_heads, int head_dim, int n_s
 }
 
 template <typename T, int HD>
-static hipError_t run_attn(const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads, float* partial,
-                           int n_splits, void* out, hipStream_t s) {
+static hipError_t run_attn(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
+                           float* partial, int n_splits, int* counters, void* out, hipStream_t s) {
   using OutT = typename std::conditional<sizeof(T) == 2, bf16_t, float>::type;  // bf16 hi/lo planes or float32
   const int n_chunks = (R + RB - 1) / RB;
   const float scale = 1.0f / sqrtf((float)HD);
-  hipLaunchKernelGGL((tree_attn_kernel<T, HD>), dim3(n_splits, n_heads * n_chunks, B), dim3(256), 0, s, qkv, rd, kv, layer, R,
-                     n_heads, n_chunks, scale, partial, n_splits);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_combine_kernel<OutT, HD>), dim3(B * R, n_heads), dim3(HD), 0, s, partial, (OutT*)out, R, n_heads, n_splits);
+  hipLaunchKernelGGL((tree_attn_kernel<T, OutT, HD>), dim3(n_splits, n_heads * n_chunks, B), dim3(256), 0, s, q, q_stride, rd, kv,
+                     layer, R, n_heads, n_chunks, scale, partial, n_splits, counters, (OutT*)out);
   return hipGetLastError();
 }
 
-hipError_t launch_attention(int dtype, const float* qkv, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
-                            float* partial, int n_splits, void* out, hipStream_t s) {
+hipError_t launch_attention(int dtype, const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
+                            float* partial, int n_splits, int* counters, void* out, hipStream_t s) {
   if (B * R <= 0) return hipSuccess;
   const int hd = kv.head_dim;
-  if (dtype == 1 && hd == 128) return run_attn<kv16_t, 128>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
-  if (dtype == 1 && hd == 64) return run_attn<kv16_t, 64>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
-  if (dtype == 0 && hd == 128) return run_attn<float, 128>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
-  if (dtype == 0 && hd == 64) return run_attn<float, 64>(qkv, rd, kv, layer, B, R, n_heads, partial, n_splits, out, s);
+  if (dtype == 1 && hd == 128) return run_attn<kv16_t, 128>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (dtype == 1 && hd == 64) return run_attn<kv16_t, 64>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (dtype == 0 && hd == 128) return run_attn<float, 128>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (dtype == 0 && hd == 64) return run_attn<float, 64>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   return hipErrorInvalidValue;
 }
 

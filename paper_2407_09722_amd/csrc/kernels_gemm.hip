@@ -1,54 +1,96 @@
-// Skinny matrix products Y[R][N] (+)= X[R][K] * W[N][K]^T for the few-row projections, FFN and
-// lm_head of the draft and target passes (the weight stream that dominates one target pass).
+// Skinny matrix products Y[R][N] = X[R][K] * W[N][K]^T for the few-row projections, FFN and lm_head of the
+// draft and target passes: the weight stream that dominates one target pass.
 //
-// bf16: the weight matrix is the A operand of v_mfma_f32_16x16x32_bf16 (16 output features x 32 k),
-// the activations are the B operand (32 k x 16 rows, rows beyond R are zero).  An activation is the
-// sum of two bf16 terms (hi + lo planes), so every weight tile feeds two MFMAs per 16 rows; the matrix
-// cores idle anyway.  One workgroup owns 16 output features; its waves interleave over the 32-wide k
-// blocks (wave w takes blocks w, w+WPB, ...),
-// so one iteration of the whole group reads WPB*64 contiguous bytes of each weight row, and every
-// lane keeps several 16-byte loads in flight.  Partial sums are reduced through LDS in a fixed order
-// (deterministic).  Memory bound: weights are read exactly once, activations come from L2.
+// bf16 path.  Weights are tile-packed (pack_matrix_kernel): the 16x32 tile (nt, kt) of the matrix is 1 KiB
+// contiguous, laid out exactly as the A operand of v_mfma_f32_16x16x32_bf16 wants it (lane l holds row l%16,
+// k = (l/16)*8 .. +8), and the tiles of one 16-feature strip follow each other along k.  A wave therefore
+// fetches every A fragment as one fully coalesced 1 KiB read and a workgroup streams one contiguous strip.
+// Activations are the B operand (32 k x 16 rows; rows beyond R are zero), carried as two bf16 planes (hi + lo),
+// so each weight tile feeds two MFMAs per 16 rows; the matrix cores idle anyway at these row counts.
+// One workgroup owns one strip; its WPB waves interleave over the k tiles and reduce through LDS in a fixed
+// order (deterministic).  The epilogue variants fold the neighbouring element-wise work into the product:
+//   STORE   plain store / accumulate; optional per-strip (max, sum-exp) partials of each row (lm_head)
+//   RESID   residual add, then the next RMSNorm's input: planes of h*gain and per-strip sums of squares
+//   SWIGLU  strips hold 8 gate + 8 up features: silu(gate)*up written as planes
+//   QKV     strips hold features i..i+8 and i+hd/2.. of one head: rotary rotation, q to a buffer, k/v to the cache
+// A product whose input is RMS-normalised takes planes of h*gain and multiplies its rows by
+// 1/sqrt(mean h^2 + eps) afterwards (the factor is common to the whole row, so it commutes with the product).
 //
-// fp32 (the tiny all-float32 workload): one wave per output feature, plain FMA, shuffle reduction.
+// fp32 path (the tiny all-float32 workload): one wave per output feature, plain FMA, shuffle reduction.
 #include "common.h"
+#include "gemm.h"
 
 namespace mtad {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float floatx4;
 
+typedef __attribute__((ext_vector_type(4))) unsigned int uintx4;
+
 union Frag {
   uint4 u;
+  uintx4 n;  // native vector: the form the nontemporal-load builtin accepts
   bf16x8 v;
 };
 
+// ---- packing ------------------------------------------------------------------------------------------
+
+// original row of packed row (nt*16 + j)
+__device__ __forceinline__ int packed_src_row(int kind, int nt, int j, int head_dim, int d_ffn) {
+  if (kind == PACK_QKV) {
+    const int tph = head_dim / 16, head = nt / tph, u = nt % tph;
+    return head * head_dim + (j < 8 ? 8 * u + j : head_dim / 2 + 8 * u + (j - 8));
+  }
+  if (kind == PACK_GATE_UP) return j < 8 ? 8 * nt + j : d_ffn + 8 * nt + (j - 8);
+  return nt * 16 + j;
+}
+
+__global__ void pack_matrix_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int N, int K, int kind, int head_dim) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one thread per 8-element lane fragment
+  const int KT = K / 32;
+  if (idx >= (int64_t)(N / 16) * KT * 64) return;
+  const int lane = (int)(idx & 63);
+  const int64_t tile = idx >> 6;
+  const int kt = (int)(tile % KT), nt = (int)(tile / KT);
+  const int row = packed_src_row(kind, nt, lane & 15, head_dim, N / 2);
+  const uint4 v = *(const uint4*)(src + (int64_t)row * K + kt * 32 + (lane >> 4) * 8);
+  *(uint4*)(dst + idx * 8) = v;
+}
+
+hipError_t launch_pack_matrix(const void* src, void* dst, int N, int K, int kind, int head_dim, hipStream_t s) {
+  const int64_t n = (int64_t)(N / 16) * (K / 32) * 64;
+  hipLaunchKernelGGL(pack_matrix_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const bf16_t*)src, (bf16_t*)dst, N, K,
+                     kind, head_dim);
+  return hipGetLastError();
+}
+
+// ---- the product -----------------------------------------------------------------------------------------
+
 // TAG only names the call site (0 draft pass, 1 target pass, 2 component entry point) so that a kernel trace can
 // tell the target pass's weight stream from the draft's; the code is the same.
-template <int MT, int WPB, int TAG>
-__global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ X,
-                                                             float* __restrict__ Y, int R, int N, int K, int ldy,
-                                                             int accumulate) {
-  extern __shared__ float red[];  // [WPB][MT][64] float4
+template <int MT, int WPB, int EPI, int TAG>
+__global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(GemmArgs a) {
+  extern __shared__ float red[];  // [WPB][MT][64] float4, then inv_rms[MT*16]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n0 = blockIdx.x * 16;
+  const int nt = blockIdx.x;
   const int r16 = lane & 15, kg = lane >> 4;
-  const int nkb = K >> 5;
+  const int K = a.K, R = a.R, KT = K >> 5;
+  float* inv_s = red + WPB * MT * 64 * 4;
 
   floatx4 acc[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  const bf16_t* wp = W + (int64_t)(n0 + r16) * K + kg * 8;
-  const bf16_t* xp = X + (int64_t)r16 * K + kg * 8;
+  const uintx4* wp = (const uintx4*)a.W + (int64_t)nt * KT * 64 + lane;
+  const bf16_t* xp = a.X + (int64_t)r16 * K + kg * 8;
   const int64_t lo_plane = (int64_t)R * K;  // the lo plane follows the hi plane
-  constexpr int U = (MT <= 2) ? 4 : 2;
+  constexpr int U = (MT <= 2) ? 8 : (MT <= 4 ? 4 : 2);
 
-  int kb = wave;
-  for (; kb + (U - 1) * WPB < nkb; kb += U * WPB) {
-    Frag a[U];
+  int kt = wave;
+  for (; kt + (U - 1) * WPB < KT; kt += U * WPB) {
+    Frag w[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) a[u].u = *(const uint4*)(wp + (int64_t)(kb + u * WPB) * 32);
+    for (int u = 0; u < U; ++u) w[u].n = __builtin_nontemporal_load(wp + (int64_t)(kt + u * WPB) * 64);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -57,54 +99,169 @@ __global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(const bf16_t* __res
         b.u = make_uint4(0, 0, 0, 0);
         bl.u = make_uint4(0, 0, 0, 0);
         if (mt * 16 + r16 < R) {
-          const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)(kb + u * WPB) * 32;
+          const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)(kt + u * WPB) * 32;
           b.u = *(const uint4*)x;
           bl.u = *(const uint4*)(x + lo_plane);
         }
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u].v, b.v, acc[mt], 0, 0, 0);
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u].v, bl.v, acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u].v, b.v, acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u].v, bl.v, acc[mt], 0, 0, 0);
       }
     }
   }
-  for (; kb < nkb; kb += WPB) {
-    Frag a;
-    a.u = *(const uint4*)(wp + (int64_t)kb * 32);
+  for (; kt < KT; kt += WPB) {
+    Frag w;
+    w.n = __builtin_nontemporal_load(wp + (int64_t)kt * 64);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       Frag b, bl;
       b.u = make_uint4(0, 0, 0, 0);
       bl.u = make_uint4(0, 0, 0, 0);
       if (mt * 16 + r16 < R) {
-        const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)kb * 32;
+        const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)kt * 32;
         b.u = *(const uint4*)x;
         bl.u = *(const uint4*)(x + lo_plane);
       }
-      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[mt], 0, 0, 0);
-      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, bl.v, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.v, b.v, acc[mt], 0, 0, 0);
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.v, bl.v, acc[mt], 0, 0, 0);
     }
   }
 
   floatx4* red4 = (floatx4*)red;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) red4[(wave * MT + mt) * 64 + lane] = acc[mt];
+
+  // row factors of a fused RMSNorm: 1/sqrt(sum of the producer's partial sums of squares / K + eps)
+  if (a.ssq) {
+    for (int m = wave; m < R; m += WPB) {
+      float s = 0.f;
+      for (int p = lane; p < a.NP; p += 64) s += a.ssq[(int64_t)m * a.NP + p];
+      for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+      if (lane == 0) inv_s[m] = 1.0f / sqrtf(s / (float)K + a.eps);
+    }
+  }
   __syncthreads();
-  // D[i][j]: lane l, register i holds output feature n0 + (l/16)*4 + i of row (l%16)
+
+  // D[i][j]: lane l, register i holds packed feature (l/16)*4 + i of row (l%16)
   for (int idx = threadIdx.x; idx < MT * 64; idx += WPB * 64) {
-    const int mt = idx >> 6, l = idx & 63;
+    const int mt = idx >> 6, l = idx & 63, g = l >> 4;
+    const int m = mt * 16 + (l & 15);
+    const bool live = m < R;
     floatx4 s = red4[mt * 64 + l];
     for (int w = 1; w < WPB; ++w) {
-      floatx4 t = red4[(w * MT + mt) * 64 + l];
+      const floatx4 t = red4[(w * MT + mt) * 64 + l];
       s[0] += t[0]; s[1] += t[1]; s[2] += t[2]; s[3] += t[3];
     }
-    const int m = mt * 16 + (l & 15);
-    if (m < R) {
-      float4* y = (float4*)(Y + (int64_t)m * ldy + n0 + (l >> 4) * 4);
-      float4 o = make_float4(s[0], s[1], s[2], s[3]);
-      if (accumulate) {
-        float4 p = *y;
-        o.x += p.x; o.y += p.y; o.z += p.z; o.w += p.w;
+    const float inv = (a.ssq && live) ? inv_s[m] : 1.0f;
+
+    if constexpr (EPI == EPI_STORE) {
+      const int n = nt * 16 + g * 4;
+      float4 o = make_float4(s[0] * inv, s[1] * inv, s[2] * inv, s[3] * inv);
+      if (live) {
+        float4* y = (float4*)(a.Y + (int64_t)m * a.ldy + n);
+        if (a.accumulate) {
+          const float4 p = *y;
+          o.x += p.x; o.y += p.y; o.z += p.z; o.w += p.w;
+        }
+        *y = o;
       }
-      *y = o;
+      if (a.lse_part) {  // (max, sum exp) over this strip's 16 features of row m, merged over the four lane groups
+        float mx = fmaxf(fmaxf(o.x, o.y), fmaxf(o.z, o.w));
+        float sm = expf(o.x - mx) + expf(o.y - mx) + expf(o.z - mx) + expf(o.w - mx);
+        for (int off = 16; off <= 32; off <<= 1) {
+          const float omx = __shfl_xor(mx, off, 64), osm = __shfl_xor(sm, off, 64);
+          const float nm = fmaxf(mx, omx);
+          sm = sm * expf(mx - nm) + osm * expf(omx - nm);
+          mx = nm;
+        }
+        if (live && g == 0) {
+          float2* p = (float2*)a.lse_part + (int64_t)m * gridDim.x + nt;
+          *p = make_float2(mx, sm);
+        }
+      }
+    } else if constexpr (EPI == EPI_RESID) {
+      const int n = nt * 16 + g * 4;
+      float4 hn = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (live) {
+        float4* hp = (float4*)(a.h + (int64_t)m * a.N + n);
+        const float4 p = *hp;
+        hn = make_float4(p.x + s[0], p.y + s[1], p.z + s[2], p.w + s[3]);
+        *hp = hn;
+        const float4 gn = *(const float4*)(a.g_next + n);
+        ushort4 hi, lo;
+        split_bf16(hn.x * gn.x, hi.x, lo.x);
+        split_bf16(hn.y * gn.y, hi.y, lo.y);
+        split_bf16(hn.z * gn.z, hi.z, lo.z);
+        split_bf16(hn.w * gn.w, hi.w, lo.w);
+        *(ushort4*)(a.planes_out + (int64_t)m * a.N + n) = hi;
+        *(ushort4*)(a.planes_out + (int64_t)R * a.N + (int64_t)m * a.N + n) = lo;
+      }
+      float q = hn.x * hn.x + hn.y * hn.y + hn.z * hn.z + hn.w * hn.w;
+      q += __shfl_xor(q, 16, 64);
+      q += __shfl_xor(q, 32, 64);
+      if (live && g == 0) a.ssq_out[(int64_t)m * gridDim.x + nt] = q;
+    } else {
+      // paired strips: packed features 0..7 and their partners 8..15 (lane + 32)
+      floatx4 t = red4[mt * 64 + (l ^ 32)];
+      for (int w = 1; w < WPB; ++w) {
+        const floatx4 o = red4[(w * MT + mt) * 64 + (l ^ 32)];
+        t[0] += o[0]; t[1] += o[1]; t[2] += o[2]; t[3] += o[3];
+      }
+      if (g < 2 && live) {
+        const int i0 = g * 4;  // 0 or 4 within the strip's 8 pairs
+        if constexpr (EPI == EPI_SWIGLU) {
+          const int f = a.N >> 1;
+          ushort4 hi, lo;
+          bf16_t* hip = (bf16_t*)&hi;
+          bf16_t* lop = (bf16_t*)&lo;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float gate = s[e] * inv, up = t[e] * inv;
+            split_bf16(gate / (1.0f + expf(-gate)) * up, hip[e], lop[e]);
+          }
+          const int64_t o = (int64_t)m * f + nt * 8 + i0;
+          *(ushort4*)(a.act_out + o) = hi;
+          *(ushort4*)(a.act_out + (int64_t)R * f + o) = lo;
+        } else {  // EPI_QKV
+          const int hd = a.kv.head_dim, half = hd >> 1, tph = hd >> 4;
+          const int head = nt / tph, i = (nt % tph) * 8 + i0;
+          const int H = a.n_heads, KVH = a.kv.n_kv_heads;
+          float x1[4], x2[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { x1[e] = s[e] * inv; x2[e] = t[e] * inv; }
+          if (head < H + KVH) {  // q and k heads are rotated
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float2 cs = a.rope[(int64_t)m * half + i + e];
+              const float y1 = x1[e] * cs.x - x2[e] * cs.y, y2 = x2[e] * cs.x + x1[e] * cs.y;
+              x1[e] = y1;
+              x2[e] = y2;
+            }
+          }
+          if (head < H) {
+            float* q = a.q_out + (int64_t)m * H * hd + (int64_t)head * hd + i;
+            *(float4*)q = make_float4(x1[0], x1[1], x1[2], x1[3]);
+            *(float4*)(q + half) = make_float4(x2[0], x2[1], x2[2], x2[3]);
+          } else {
+            const int slot = a.slot[m];
+            if (slot >= 0) {
+              if (slot >= kv_capacity(a.kv)) {
+                atomicOr(a.status, (uint32_t)ST_KV_CAP);
+              } else {
+                const bool is_k = head < H + KVH;
+                const int gh = is_k ? head - H : head - H - KVH;
+                kv16_t* dst = (kv16_t*)(is_k ? a.kv.k : a.kv.v) + (int64_t)a.layer * a.kv.layer_stride +
+                              kv_token_offset(a.kv, m / a.Rseq, slot) + (int64_t)gh * hd + i;
+                typedef kv16_t half4_t __attribute__((ext_vector_type(4)));
+                half4_t v1, v2;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v1[e] = (kv16_t)x1[e]; v2[e] = (kv16_t)x2[e]; }
+                *(half4_t*)dst = v1;
+                *(half4_t*)(dst + half) = v2;
+              }
+            }
+          }
+        }
+      }
     }
   }
 }
@@ -145,42 +302,52 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
   }
 }
 
-template <int MT, int WPB, int TAG>
-static hipError_t run_tagged(const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool acc, hipStream_t s) {
-  const size_t lds = (size_t)WPB * MT * 64 * sizeof(float) * 4;
-  hipLaunchKernelGGL((gemm_bf16_kernel<MT, WPB, TAG>), dim3(N / 16), dim3(WPB * 64), lds, s, (const bf16_t*)W, (const bf16_t*)X, Y,
-                     R, N, K, ldy, acc ? 1 : 0);
+hipError_t launch_gemm_f32(const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate, hipStream_t s) {
+  if (R <= 0) return hipSuccess;
+  if (K % 4) return hipErrorInvalidValue;
+  constexpr int RB = 8;
+  hipLaunchKernelGGL((gemm_f32_kernel<RB>), dim3((N + 3) / 4, (R + RB - 1) / RB), dim3(256), 0, s, (const float*)W, (const float*)X,
+                     Y, R, N, K, ldy, accumulate ? 1 : 0);
   return hipGetLastError();
 }
-template <int MT, int WPB>
-static hipError_t run_bf16(int tag, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool acc, hipStream_t s) {
-  if (tag == 1) return run_tagged<MT, WPB, 1>(W, X, Y, R, N, K, ldy, acc, s);
-  if (tag == 2) return run_tagged<MT, WPB, 2>(W, X, Y, R, N, K, ldy, acc, s);
-  return run_tagged<MT, WPB, 0>(W, X, Y, R, N, K, ldy, acc, s);
+
+template <int MT, int WPB, int EPI, int TAG>
+static hipError_t run_one(const GemmArgs& a, hipStream_t s) {
+  const size_t lds = (size_t)WPB * MT * 64 * 16 + (size_t)MT * 16 * sizeof(float);
+  hipLaunchKernelGGL((gemm_bf16_kernel<MT, WPB, EPI, TAG>), dim3(a.N / 16), dim3(WPB * 64), lds, s, a);
+  return hipGetLastError();
 }
 
-hipError_t launch_gemm(int dtype, const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate,
-                       hipStream_t s, int tag) {
-  if (R <= 0) return hipSuccess;
-  if (dtype == 0) {
-    if (K % 4) return hipErrorInvalidValue;
-    constexpr int RB = 8;
-    hipLaunchKernelGGL((gemm_f32_kernel<RB>), dim3((N + 3) / 4, (R + RB - 1) / RB), dim3(256), 0, s, (const float*)W,
-                       (const float*)X, Y, R, N, K, ldy, accumulate ? 1 : 0);
-    return hipGetLastError();
+template <int MT, int WPB, int EPI>
+static hipError_t run_tag(const GemmArgs& a, int tag, hipStream_t s) {
+  if constexpr (MT <= 2) {
+    if (tag == 1) return run_one<MT, WPB, EPI, 1>(a, s);
+    if (tag == 2) return run_one<MT, WPB, EPI, 2>(a, s);
   }
-  if ((N % 16) || (K % 32) || (ldy % 4) || R > 256) return hipErrorInvalidValue;
-  const int mt = (R + 15) / 16;
-  // few output tiles: more waves per tile so that every CU still has many loads in flight
-  const bool wide = (N / 16) >= 1024;
-  if (mt <= 1) return wide ? run_bf16<1, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<1, 16>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 2) return wide ? run_bf16<2, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s) : run_bf16<2, 16>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 3) return run_bf16<3, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 4) return run_bf16<4, 8>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 6) return run_bf16<6, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 8) return run_bf16<8, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
-  if (mt <= 12) return run_bf16<12, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
-  return run_bf16<16, 4>(tag, W, X, Y, R, N, K, ldy, accumulate, s);
+  return run_one<MT, WPB, EPI, 0>(a, s);
+}
+
+template <int EPI>
+static hipError_t run_epi(const GemmArgs& a, int tag, hipStream_t s) {
+  const int mt = (a.R + 15) / 16;
+  if (mt <= 1) return run_tag<1, 16, EPI>(a, tag, s);
+  if (mt <= 2) return run_tag<2, 16, EPI>(a, tag, s);
+  if (mt <= 4) return run_tag<4, 8, EPI>(a, tag, s);
+  if (mt <= 8) return run_tag<8, 4, EPI>(a, tag, s);
+  if (mt <= 12) return run_tag<12, 4, EPI>(a, tag, s);
+  return run_tag<16, 3, EPI>(a, tag, s);
+}
+
+hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s) {
+  if (a.R <= 0) return hipSuccess;
+  if ((a.N % 16) || (a.K % 32) || a.R > 256) return hipErrorInvalidValue;
+  switch (epi) {
+    case EPI_STORE: return (a.ldy % 4) ? hipErrorInvalidValue : run_epi<EPI_STORE>(a, tag, s);
+    case EPI_RESID: return run_epi<EPI_RESID>(a, tag, s);
+    case EPI_SWIGLU: return run_epi<EPI_SWIGLU>(a, tag, s);
+    case EPI_QKV: return run_epi<EPI_QKV>(a, tag, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace mtad

@@ -34,22 +34,41 @@ __device__ __forceinline__ float block_max(float v, float* sh) {
   return t;
 }
 
+// h[row] = E[tok[row]]; bf16 models: also planes of h*g0 (input of the first fused RMSNorm) and ssq[row] = sum h^2
 template <typename T>
-__global__ void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ h, int d, int vocab) {
+__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ h, int d,
+                                                    int vocab, const float* __restrict__ g0, bf16_t* __restrict__ planes,
+                                                    float* __restrict__ ssq) {
+  __shared__ float sh[4];
   const int row = blockIdx.x;
   int t = tok[row];
   if (t < 0 || t >= vocab) t = 0;  // inactive rows carry no meaningful token
   const T* e = E + (int64_t)t * d;
+  const int64_t lo_plane = (int64_t)gridDim.x * d;
+  float ss = 0.f;
   for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    if constexpr (sizeof(T) == 2) h[(int64_t)row * d + i] = bf16_to_f32(e[i]);
-    else h[(int64_t)row * d + i] = e[i];
+    float v;
+    if constexpr (sizeof(T) == 2) v = bf16_to_f32(e[i]);
+    else v = e[i];
+    h[(int64_t)row * d + i] = v;
+    if (planes) {
+      ss += v * v;
+      split_bf16(v * g0[i], planes[(int64_t)row * d + i], planes[lo_plane + (int64_t)row * d + i]);
+    }
+  }
+  if (planes) {
+    ss = block_sum(ss, sh);
+    if (threadIdx.x == 0) ssq[row] = ss;
   }
 }
 
-hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, hipStream_t s) {
+hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, const float* g0,
+                        void* planes, float* ssq, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
-  if (dtype == 1) hipLaunchKernelGGL((embed_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t*)E, tok, h, d, vocab);
-  else hipLaunchKernelGGL((embed_kernel<float>), dim3(rows), dim3(256), 0, s, (const float*)E, tok, h, d, vocab);
+  if (dtype == 1)
+    hipLaunchKernelGGL((embed_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t*)E, tok, h, d, vocab, g0, (bf16_t*)planes, ssq);
+  else
+    hipLaunchKernelGGL((embed_kernel<float>), dim3(rows), dim3(256), 0, s, (const float*)E, tok, h, d, vocab, nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 
@@ -143,7 +162,7 @@ __global__ void rope_kv_kernel(float* __restrict__ qkv, const float2* __restrict
   T* dst = (T*)(is_k ? kv.k : kv.v) + off;
   float y1 = x1, y2 = x2;
   if (is_k) { y1 = x1 * cs.x - x2 * cs.y; y2 = x2 * cs.x + x1 * cs.y; }
-  dst[i] = (T)y1;  // round to nearest even for the half type
+  dst[i] = (T)y1;
   dst[i + half] = (T)y2;
 }
 
@@ -152,7 +171,7 @@ hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowD
   const int rows = B * R;
   if (rows <= 0) return hipSuccess;
   dim3 grid(rows, n_heads + 2 * kv.n_kv_heads), block(kv.head_dim / 2);
-  if (dtype == 1) hipLaunchKernelGGL((rope_kv_kernel<kv16_t>), grid, block, 0, s, qkv, table, rd, kv, layer, R, n_heads, status);
+  if (dtype == 1) return hipErrorInvalidValue;  // bf16 models rotate and store in the QKV product's epilogue
   else hipLaunchKernelGGL((rope_kv_kernel<float>), grid, block, 0, s, qkv, table, rd, kv, layer, R, n_heads, status);
   return hipGetLastError();
 }
@@ -194,6 +213,25 @@ __global__ __launch_bounds__(256) void row_lse_kernel(const float* __restrict__ 
 hipError_t launch_row_lse(const float* logits, float* lse, int rows, int vocab, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(row_lse_kernel, dim3(rows), dim3(256), 0, s, logits, lse, vocab);
+  return hipGetLastError();
+}
+
+// lse[row] = log sum exp over the row from per-strip partials (max, sum exp), merged in strip order
+__global__ __launch_bounds__(256) void lse_finish_kernel(const float2* __restrict__ part, float* __restrict__ lse, int NP) {
+  __shared__ float sh[4];
+  const float2* p = part + (int64_t)blockIdx.x * NP;
+  float m = -INFINITY;
+  for (int i = threadIdx.x; i < NP; i += 256) m = fmaxf(m, p[i].x);
+  m = block_max(m, sh);
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < NP; i += 256) sum += p[i].y * expf(p[i].x - m);
+  sum = block_sum(sum, sh);
+  if (threadIdx.x == 0) lse[blockIdx.x] = m + logf(sum);
+}
+
+hipError_t launch_lse_finish(const float* lse_part, float* lse, int rows, int NP, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(lse_finish_kernel, dim3(rows), dim3(256), 0, s, (const float2*)lse_part, lse, NP);
   return hipGetLastError();
 }
 

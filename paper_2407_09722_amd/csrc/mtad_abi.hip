@@ -4,6 +4,7 @@
 #include "../../include/mtad_kernels.h"
 #include "beam.h"
 #include "common.h"
+#include "gemm.h"
 
 #include <math.h>
 #include <new>
@@ -20,8 +21,9 @@ struct mtad_ctx {
   size_t ws_need;
   char* ws;
   // workspace carve-up
-  float *h, *qkv, *gu, *dlogits, *lse, *partial, *part_key;
-  void* xn;
+  float *h, *qkv, *gu, *dlogits, *lse, *partial, *part_key, *ssq, *lse_part;
+  void *xn, *xg;  // xn: attention output / FFN activation; xg: h*gain planes feeding the next normalised product
+  int* attn_cnt;
   float2* rope;
   int* part_idx;
   RowDesc rd;
@@ -80,6 +82,10 @@ void carve(mtad_ctx* c, char* base) {
   c->status = k.take<uint32_t>(64);
   c->h = k.take<float>(rows * dmax);
   c->xn = k.take<float>(rows * imax(imax(dmax, hhd), fmax));
+  c->xg = k.take<float>(rows * dmax);
+  c->ssq = k.take<float>(rows * (size_t)(dmax / 16 + 1));
+  c->lse_part = k.take<float>(rows * (size_t)(imax(t.vocab, d.vocab) / 16 + 1) * 2);
+  c->attn_cnt = k.take<int>((size_t)c->cfg.batch * imax(t.n_heads, d.n_heads) * 4);
   c->qkv = k.take<float>(rows * qkv);
   c->gu = k.take<float>(rows * 2 * fmax);
   c->dlogits = k.take<float>((size_t)c->cfg.batch * c->draft_rows * d.vocab);
@@ -131,38 +137,102 @@ int same_shape(const mtad_model* a, const mtad_model* b) {
     }                                   \
   } while (0)
 
-// The decoder pass over B*R rows described by ctx->rd; hidden states end in ctx->h.
-int decoder_pass(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s) {
-  const int B = c->cfg.batch, rows = B * R, dt = m->dtype;
+// The decoder pass over B*R rows described by ctx->rd.  float32 models: hidden states end in ctx->h.
+// bf16 models: additionally ctx->xg holds the planes of h*g_final and ctx->ssq the per-strip sums of squares,
+// ready for the lm_head product.
+int decoder_pass_f32(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s) {
+  const int B = c->cfg.batch, rows = B * R;
+  const int d = m->d_model, f = m->d_ffn, H = m->n_heads, hd = m->head_dim;
+  const int qkvw = (H + 2 * m->n_kv_heads) * hd;
+  const KvView kvv = view_of(kv, m);
+  const int n_splits = splits_for(c, m, R);
+  const void* const* W = m->weights;
+  HIP_TRY(c, launch_embed(0, W[0], c->rd.tok, c->h, rows, d, m->vocab, nullptr, nullptr, nullptr, s));
+  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s));
+  for (int l = 0; l < m->n_layers; ++l) {
+    const void* const* L = W + 1 + 6 * l;
+    HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)L[0], c->xn, rows, d, m->rms_eps, s));
+    HIP_TRY(c, launch_gemm_f32(L[1], c->xn, c->qkv, rows, qkvw, d, qkvw, false, s));
+    HIP_TRY(c, launch_rope_kv(0, c->qkv, c->rope, c->rd, kvv, l, B, R, H, c->status, s));
+    HIP_TRY(c, launch_attention(0, c->qkv, qkvw, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->attn_cnt, c->xn, s));
+    HIP_TRY(c, launch_gemm_f32(L[2], c->xn, c->h, rows, d, H * hd, d, true, s));
+    HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)L[3], c->xn, rows, d, m->rms_eps, s));
+    HIP_TRY(c, launch_gemm_f32(L[4], c->xn, c->gu, rows, 2 * f, d, 2 * f, false, s));
+    HIP_TRY(c, launch_silu_mul(0, c->gu, c->xn, rows, f, s));
+    HIP_TRY(c, launch_gemm_f32(L[5], c->xn, c->h, rows, d, f, d, true, s));
+  }
+  return MTAD_OK;
+}
+
+// bf16 models: five kernels per layer.  Every element-wise step rides on a product's epilogue:
+//   qkv product   (rows scaled by the fused RMSNorm factor) -> rotary, q to a buffer, k/v to the cache
+//   attention     -> planes of the attention output
+//   o product     -> h += ., planes of h*g_ffn, sums of squares
+//   gate/up prod. (scaled) -> planes of silu(gate)*up
+//   down product  -> h += ., planes of h*g_next, sums of squares
+int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s) {
+  const int B = c->cfg.batch, rows = B * R;
   const int d = m->d_model, f = m->d_ffn, H = m->n_heads, hd = m->head_dim;
   const int qkvw = (H + 2 * m->n_kv_heads) * hd;
   const KvView kvv = view_of(kv, m);
   const int n_splits = splits_for(c, m, R);
   const int tag = same_shape(m, &c->tshape) ? 1 : 0;
   const void* const* W = m->weights;
-  HIP_TRY(c, launch_embed(dt, W[0], c->rd.tok, c->h, rows, d, m->vocab, s));
+  const int tail = 1 + 6 * m->n_layers;
+  HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, s));
   HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s));
+  int np = 1;  // partial sums of squares per row currently in ctx->ssq
   for (int l = 0; l < m->n_layers; ++l) {
     const void* const* L = W + 1 + 6 * l;
-    HIP_TRY(c, launch_rmsnorm(dt, c->h, (const float*)L[0], c->xn, rows, d, m->rms_eps, s));
-    HIP_TRY(c, launch_gemm(dt, L[1], c->xn, c->qkv, rows, qkvw, d, qkvw, false, s, tag));
-    HIP_TRY(c, launch_rope_kv(dt, c->qkv, c->rope, c->rd, kvv, l, B, R, H, c->status, s));
-    HIP_TRY(c, launch_attention(dt, c->qkv, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->xn, s));
-    HIP_TRY(c, launch_gemm(dt, L[2], c->xn, c->h, rows, d, H * hd, d, true, s, tag));
-    HIP_TRY(c, launch_rmsnorm(dt, c->h, (const float*)L[3], c->xn, rows, d, m->rms_eps, s));
-    HIP_TRY(c, launch_gemm(dt, L[4], c->xn, c->gu, rows, 2 * f, d, 2 * f, false, s, tag));
-    HIP_TRY(c, launch_silu_mul(dt, c->gu, c->xn, rows, f, s));
-    HIP_TRY(c, launch_gemm(dt, L[5], c->xn, c->h, rows, d, f, d, true, s, tag));
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.R = rows;
+    a.eps = m->rms_eps;
+    // qkv
+    a.W = (const bf16_t*)L[1]; a.X = (const bf16_t*)c->xg; a.N = qkvw; a.K = d;
+    a.ssq = c->ssq; a.NP = np;
+    a.q_out = c->qkv; a.rope = c->rope; a.slot = c->rd.slot; a.kv = kvv; a.layer = l; a.Rseq = R; a.n_heads = H; a.status = c->status;
+    HIP_TRY(c, launch_gemm_bf16(a, EPI_QKV, tag, s));
+    HIP_TRY(c, launch_attention(1, c->qkv, H * hd, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->attn_cnt, c->xn, s));
+    // o projection + residual; prepares the FFN's normalised input
+    a.W = (const bf16_t*)L[2]; a.X = (const bf16_t*)c->xn; a.N = d; a.K = H * hd;
+    a.ssq = nullptr; a.NP = 0;
+    a.h = c->h; a.g_next = (const float*)L[3]; a.planes_out = (bf16_t*)c->xg; a.ssq_out = c->ssq;
+    HIP_TRY(c, launch_gemm_bf16(a, EPI_RESID, tag, s));
+    np = d / 16;
+    // gate/up + SwiGLU
+    a.W = (const bf16_t*)L[4]; a.X = (const bf16_t*)c->xg; a.N = 2 * f; a.K = d;
+    a.ssq = c->ssq; a.NP = np;
+    a.act_out = (bf16_t*)c->xn;
+    HIP_TRY(c, launch_gemm_bf16(a, EPI_SWIGLU, tag, s));
+    // down projection + residual; prepares the next layer's (or the final) normalised input
+    a.W = (const bf16_t*)L[5]; a.X = (const bf16_t*)c->xn; a.N = d; a.K = f;
+    a.ssq = nullptr; a.NP = 0;
+    a.g_next = (const float*)(l + 1 < m->n_layers ? W[1 + 6 * (l + 1)] : W[tail]);
+    HIP_TRY(c, launch_gemm_bf16(a, EPI_RESID, tag, s));
   }
   return MTAD_OK;
+}
+
+int decoder_pass(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s) {
+  return m->dtype == 1 ? decoder_pass_bf16(c, m, kv, R, s) : decoder_pass_f32(c, m, kv, R, s);
 }
 
 int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* lse, hipStream_t s) {
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
-  HIP_TRY(c, launch_rmsnorm(m->dtype, c->h, (const float*)W[tail], c->xn, rows, m->d_model, m->rms_eps, s));
-  HIP_TRY(c, launch_gemm(m->dtype, W[tail + 1], c->xn, logits, rows, m->vocab, m->d_model, m->vocab, false, s,
-                         same_shape(m, &c->tshape) ? 1 : 0));
+  if (m->dtype == 1) {
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.W = (const bf16_t*)W[tail + 1]; a.X = (const bf16_t*)c->xg; a.R = rows; a.N = m->vocab; a.K = m->d_model;
+    a.ssq = c->ssq; a.NP = m->d_model / 16; a.eps = m->rms_eps;
+    a.Y = logits; a.ldy = m->vocab; a.lse_part = c->lse_part;
+    HIP_TRY(c, launch_gemm_bf16(a, EPI_STORE, same_shape(m, &c->tshape) ? 1 : 0, s));
+    HIP_TRY(c, launch_lse_finish(c->lse_part, lse, rows, m->vocab / 16, s));
+    return MTAD_OK;
+  }
+  HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)W[tail], c->xn, rows, m->d_model, m->rms_eps, s));
+  HIP_TRY(c, launch_gemm_f32(W[tail + 1], c->xn, logits, rows, m->vocab, m->d_model, m->vocab, false, s));
   HIP_TRY(c, launch_row_lse(logits, lse, rows, m->vocab, s));
   return MTAD_OK;
 }
@@ -233,6 +303,7 @@ int mtad_bind_workspace(mtad_ctx* c, void* buf, size_t bytes) {
   c->ws = (char*)buf;
   carve(c, c->ws);
   hipError_t e = hipMemset(c->status, 0, 256);
+  if (e == hipSuccess) e = hipMemset(c->attn_cnt, 0, sizeof(int) * (size_t)c->cfg.batch * imax(c->tshape.n_heads, c->dshape.n_heads) * 4);
   if (e != hipSuccess) {
     c->last_hip = (int)e;
     return MTAD_EHIP;
@@ -369,7 +440,21 @@ int mtad_k_gemm(int32_t dtype, const void* W, const void* X, float* Y, int32_t R
   if (dtype != 0 && dtype != 1) return MTAD_EINVAL;
   if (dtype == 1 && ((N % 16) || (K % 32) || (ldy % 4) || R > 256)) return MTAD_ESHAPE;
   if (dtype == 0 && (K % 4)) return MTAD_ESHAPE;
-  return launch_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate != 0, (hipStream_t)stream, 2) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+  if (dtype == 0) return launch_gemm_f32(W, X, Y, R, N, K, ldy, accumulate != 0, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+  GemmArgs a;
+  memset(&a, 0, sizeof(a));
+  a.W = (const bf16_t*)W; a.X = (const bf16_t*)X; a.R = R; a.N = N; a.K = K;
+  a.Y = Y; a.ldy = ldy; a.accumulate = accumulate != 0;
+  return launch_gemm_bf16(a, EPI_STORE, 2, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+}
+
+int mtad_pack_matrix(int32_t kind, const void* src, void* dst, int32_t N, int32_t K, int32_t head_dim, void* stream) {
+  if (!src || !dst || src == dst || N < 16 || K < 32) return MTAD_EINVAL;
+  if (kind != MTAD_PACK_PLAIN && kind != MTAD_PACK_QKV && kind != MTAD_PACK_GATE_UP) return MTAD_EINVAL;
+  if ((N % 16) || (K % 32)) return MTAD_ESHAPE;
+  if (kind == MTAD_PACK_QKV && (head_dim < 16 || (head_dim % 16) || (N % head_dim))) return MTAD_ESHAPE;
+  if (kind == MTAD_PACK_GATE_UP && (N % 32)) return MTAD_ESHAPE;
+  return launch_pack_matrix(src, dst, N, K, kind, head_dim, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
 }
 
 int mtad_k_rmsnorm(int32_t dtype, const float* h, const float* g, void* out, int32_t rows, int32_t d, float eps, void* stream) {

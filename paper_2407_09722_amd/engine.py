@@ -30,9 +30,17 @@ class DeviceModel:
 
         def upload(n):
             w = weights(n) if callable(weights) else weights[n]
-            if w.dtype == np.uint16:
-                w = w.view(np.int16)                       # bfloat16 bit patterns; torch keeps them as raw 16-bit words
-            return _dev(w, device)
+            if w.dtype != np.uint16:
+                return _dev(w, device)
+            t = _dev(w.view(np.int16), device)              # bfloat16 bit patterns; torch keeps them as raw 16-bit words
+            kind = n.split(".")[-1]
+            if kind == "embed":
+                return t                                    # gathered by token id: stays row-major
+            packed = torch.empty_like(t)                    # the layout the matrix-core kernels stream (done once)
+            mode = {"w_qkv": mb.MTAD_PACK_QKV, "w_gu": mb.MTAD_PACK_GATE_UP}.get(kind, mb.MTAD_PACK_PLAIN)
+            mb.mtad_pack_matrix(mode, t, packed, t.shape[0], t.shape[1], shape.head_dim)
+            torch.cuda.current_stream().synchronize()
+            return packed
 
         if callable(weights):
             from concurrent.futures import ThreadPoolExecutor

@@ -28,7 +28,9 @@ def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None):
     if dtype == 1:
         hi = si.bf16_bits_to_f32(si.f32_to_bf16_bits(X))
         lo = si.bf16_bits_to_f32(si.f32_to_bf16_bits(X - hi))
-        Wd, Xd = _bits(W), _bits(np.stack([hi, lo]))                     # activation = hi + lo planes
+        Wrow, Xd = _bits(W), _bits(np.stack([hi, lo]))                   # activation = hi + lo planes
+        Wd = torch.empty_like(Wrow)
+        mb.mtad_pack_matrix(mb.MTAD_PACK_PLAIN, Wrow, Wd, N, K)          # the layout the kernel streams
         W, X = si.bf16_bits_to_f32(si.f32_to_bf16_bits(W)), hi.astype(np.float64) + lo
     else:
         Wd, Xd = torch.from_numpy(W).to(DEV), torch.from_numpy(X).to(DEV)
