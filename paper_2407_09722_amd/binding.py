@@ -88,7 +88,7 @@ def lib():
         L.mtad_verify_tree.argtypes = [vp, P(mtad_model), P(mtad_kv), vp, P(mtad_tree), vp, vp, vp, vp]
         L.mtad_accept.argtypes = [vp, P(mtad_tree), vp, vp, i32, P(mtad_kv), f32, i32, i32, u64, P(mtad_accept_out), vp]
         L.mtad_kv_commit.argtypes = [vp, P(mtad_kv), P(mtad_kv), P(mtad_tree), P(mtad_accept_out), P(mtad_state), vp]
-        L.mtad_k_gemm.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.mtad_k_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.mtad_k_rmsnorm.argtypes = [i32, vp, vp, vp, i32, i32, f32, vp]
         L.mtad_k_row_lse.argtypes = [vp, vp, i32, i32, vp]
         L.mtad_k_copy.argtypes = [vp, vp, C.c_int64, vp]
@@ -178,8 +178,8 @@ def mtad_kv_commit(ctx, tkv, dkv, tree, acc, st, stream=None):
                                                  C.byref(acc), C.byref(st), _stream_ptr(stream)))
 
 
-def mtad_k_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate=False, stream=None):
-    _check("mtad_k_gemm", lib().mtad_k_gemm(dtype, ptr(W), ptr(X), ptr(Y), R, N, K, ldy, int(accumulate), _stream_ptr(stream)))
+def mtad_k_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate=False, stream=None, ctx=None):
+    _check("mtad_k_gemm", lib().mtad_k_gemm(ctx, dtype, ptr(W), ptr(X), ptr(Y), R, N, K, ldy, int(accumulate), _stream_ptr(stream)))
 
 
 def mtad_k_rmsnorm(dtype, h, g, out, rows, d, eps, stream=None):

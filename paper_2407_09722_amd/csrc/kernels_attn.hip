@@ -173,7 +173,9 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
   }
   __syncthreads();
 
-  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD])
+  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]).  Partials travel between workgroups (possibly on
+  // different XCDs, whose L2s are not coherent with each other) as device-scope relaxed atomics: write-through
+  // stores and cache-bypassing loads, no L2 flush.
   {
     const int d = t % HD, rg2 = t / HD;
 #pragma unroll
@@ -181,27 +183,26 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
       const int r = rg2 + NRG2 * i;
       if (r < nrows) {
         float* p = partial + ((((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits + split) * (HD + 2);
-        p[2 + d] = acc[i];
+        __hip_atomic_store(p + 2 + d, acc[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (d == 0) {
-          p[0] = m_s[r];
-          p[1] = l_s[r];
+          __hip_atomic_store(p, m_s[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(p + 1, l_s[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
     }
   }
 
   // the workgroup that arrives last merges the splits of its rows
-  __threadfence();
+  __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
   __syncthreads();
   if (t == 0) {
     int* c = counters + ((int64_t)seq * n_heads + head) * n_chunks + chunk;
-    const int prev = atomicAdd(c, 1);
+    const int prev = __hip_atomic_fetch_add(c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     last_s = (prev == n_splits - 1);
-    if (last_s) *c = 0;  // everyone has arrived: leave the counter clean for the next launch
+    if (last_s) __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
   }
   __syncthreads();
   if (!last_s) return;
-  __threadfence();
   {
     const int d = t % HD, rg2 = t / HD;
     const int64_t lo_plane = (int64_t)gridDim.z * R * n_heads * HD;
@@ -209,15 +210,28 @@ __global__ __launch_bounds__(256) void tree_attn_kernel(const float* __restrict_
     for (int i = 0; i < RPT2; ++i) {
       const int r = rg2 + NRG2 * i;
       if (r >= nrows) continue;
-      const volatile float* p = partial + (((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits * (HD + 2);
-      float M = -INFINITY;
-      for (int s2 = 0; s2 < n_splits; ++s2) M = fmaxf(M, p[(int64_t)s2 * (HD + 2)]);
-      float L = 0.f, o = 0.f;
-      for (int s2 = 0; s2 < n_splits; ++s2) {
-        const float m = p[(int64_t)s2 * (HD + 2)];
-        const float w = (m == -INFINITY) ? 0.f : expf(m - M);
-        L = fmaf(p[(int64_t)s2 * (HD + 2) + 1], w, L);
-        o = fmaf(p[(int64_t)s2 * (HD + 2) + 2 + d], w, o);
+      const float* p = partial + (((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits * (HD + 2);
+      // running merge in split order, eight splits' loads in flight at a time (deterministic)
+      float M = -INFINITY, L = 0.f, o = 0.f;
+      for (int s2 = 0; s2 < n_splits; s2 += 8) {
+        float mm[8], ll[8], oo[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const bool ok = s2 + j < n_splits;
+          const float* ps = p + (int64_t)(ok ? s2 + j : 0) * (HD + 2);
+          mm[j] = ok ? __hip_atomic_load(ps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
+          ll[j] = ok ? __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+          oo[j] = ok ? __hip_atomic_load(ps + 2 + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          if (mm[j] == -INFINITY) continue;
+          const float Mn = fmaxf(M, mm[j]);
+          const float ws = (M == -INFINITY) ? 0.f : expf(M - Mn), wj = expf(mm[j] - Mn);
+          L = L * ws + ll[j] * wj;
+          o = o * ws + oo[j] * wj;
+          M = Mn;
+        }
       }
       const float y = (L > 0.f) ? o / L : 0.f;
       const int64_t idx = (int64_t)(seq * R + row0 + r) * n_heads * HD + (int64_t)head * HD + d;

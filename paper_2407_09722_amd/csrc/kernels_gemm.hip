@@ -5,10 +5,11 @@
 // contiguous, laid out exactly as the A operand of v_mfma_f32_16x16x32_bf16 wants it (lane l holds row l%16,
 // k = (l/16)*8 .. +8), and the tiles of one 16-feature strip follow each other along k.  A wave therefore
 // fetches every A fragment as one fully coalesced 1 KiB read and a workgroup streams one contiguous strip.
-// Activations are the B operand (32 k x 16 rows; rows beyond R are zero), carried as two bf16 planes (hi + lo),
-// so each weight tile feeds two MFMAs per 16 rows; the matrix cores idle anyway at these row counts.
-// One workgroup owns one strip; its WPB waves interleave over the k tiles and reduce through LDS in a fixed
-// order (deterministic).  The epilogue variants fold the neighbouring element-wise work into the product:
+// Activations are the B operand, carried as two bf16 planes (hi + lo): the 16 columns of one MFMA hold the hi
+// and lo terms of 8 rows, so a weight tile costs one MFMA per 8 rows.
+// One workgroup owns 16 strips (one per wave) over one k range; the activations of that range sit in LDS and
+// are shared by the 16 waves; k ranges of different workgroups are added in a fixed order by the workgroup
+// that finishes last (deterministic).  The epilogue variants fold the neighbouring element-wise work in:
 //   STORE   plain store / accumulate; optional per-strip (max, sum-exp) partials of each row (lm_head)
 //   RESID   residual add, then the next RMSNorm's input: planes of h*gain and per-strip sums of squares
 //   SWIGLU  strips hold 8 gate + 8 up features: silu(gate)*up written as planes
@@ -66,95 +67,88 @@ hipError_t launch_pack_matrix(const void* src, void* dst, int N, int K, int kind
 
 // ---- the product -----------------------------------------------------------------------------------------
 
-// TAG only names the call site (0 draft pass, 1 target pass, 2 component entry point) so that a kernel trace can
-// tell the target pass's weight stream from the draft's; the code is the same.
-template <int MT, int WPB, int EPI, int TAG>
-__global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(GemmArgs a) {
-  extern __shared__ float red[];  // [WPB][MT][64] float4, then inv_rms[MT*16]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+// One workgroup = one strip of 16 output features; its 16 waves interleave over the k tiles (wave w takes
+// tiles w, w+16, ...), each with up to U weight tiles in flight, and their partial sums meet in LDS in a fixed
+// order (deterministic).  Columns of the B operand: c < 8 = hi term of row g*8 + c, c >= 8 = lo term of row
+// g*8 + c - 8, so one MFMA per weight tile covers 8 rows (NG = ceil(rows / 8) MFMAs per tile).  B fragments come
+// from L2 with predicated 16-byte loads issued ahead of the weight loads.  Wave g < NG finishes row group g.
+// TAG only names the call site (0 draft pass, 1 target pass, 2 component entry point) in kernel traces.
+constexpr int GW = 16;
+
+template <int NG, int EPI, int TAG>
+__global__ __launch_bounds__(GW * 64) void gemm_bf16_kernel(GemmArgs a) {
+  constexpr int U = (NG <= 1) ? 8 : (NG <= 3 ? 4 : 2);  // weight tiles in flight per wave
+  __shared__ floatx4 red[GW * NG * 64];
+  __shared__ float inv_s[NG * 8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nt = blockIdx.x;
-  const int r16 = lane & 15, kg = lane >> 4;
-  const int K = a.K, R = a.R, KT = K >> 5;
-  float* inv_s = red + WPB * MT * 64 * 4;
+  const int K = a.K, KT = K >> 5, NT = a.N >> 4;
+  const int R = a.R, row0 = a.row0;
+  const int rows_here = min(NG * 8, R - row0);
+  const int c = lane & 15, kg = lane >> 4;
+  const int64_t lo_plane = (int64_t)R * K;
 
-  floatx4 acc[MT];
+  floatx4 acc[NG];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-
+  for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
   const uintx4* wp = (const uintx4*)a.W + (int64_t)nt * KT * 64 + lane;
-  const bf16_t* xp = a.X + (int64_t)r16 * K + kg * 8;
-  const int64_t lo_plane = (int64_t)R * K;  // the lo plane follows the hi plane
-  constexpr int U = (MT <= 2) ? 8 : (MT <= 4 ? 4 : 2);
+  // this lane's B-fragment source: plane c/8, row row0 + g*8 + c%8, k offset kg*8 within a tile
+  const bf16_t* xp = a.X + (c >> 3) * lo_plane + (int64_t)(row0 + (c & 7)) * K + kg * 8;
 
-  int kt = wave;
-  for (; kt + (U - 1) * WPB < KT; kt += U * WPB) {
-    Frag w[U];
+  for (int kt = wave; kt < KT; kt += U * GW) {
+    Frag b[U][NG], w[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) w[u].n = __builtin_nontemporal_load(wp + (int64_t)(kt + u * WPB) * 64);
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        Frag b, bl;
-        b.u = make_uint4(0, 0, 0, 0);
-        bl.u = make_uint4(0, 0, 0, 0);
-        if (mt * 16 + r16 < R) {
-          const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)(kt + u * WPB) * 32;
-          b.u = *(const uint4*)x;
-          bl.u = *(const uint4*)(x + lo_plane);
-        }
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u].v, b.v, acc[mt], 0, 0, 0);
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u].v, bl.v, acc[mt], 0, 0, 0);
+      for (int g = 0; g < NG; ++g) {
+        b[u][g].u = make_uint4(0, 0, 0, 0);
+        if (kt + u * GW < KT && g * 8 + (c & 7) < rows_here)
+          b[u][g].u = *(const uint4*)(xp + (int64_t)g * 8 * K + (int64_t)(kt + u * GW) * 32);
       }
-    }
-  }
-  for (; kt < KT; kt += WPB) {
-    Frag w;
-    w.n = __builtin_nontemporal_load(wp + (int64_t)kt * 64);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      Frag b, bl;
-      b.u = make_uint4(0, 0, 0, 0);
-      bl.u = make_uint4(0, 0, 0, 0);
-      if (mt * 16 + r16 < R) {
-        const bf16_t* x = xp + (int64_t)mt * 16 * K + (int64_t)kt * 32;
-        b.u = *(const uint4*)x;
-        bl.u = *(const uint4*)(x + lo_plane);
+    for (int u = 0; u < U; ++u)
+      if (kt + u * GW < KT) w[u].n = __builtin_nontemporal_load(wp + (int64_t)(kt + u * GW) * 64);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (kt + u * GW < KT) {
+#pragma unroll
+        for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u].v, b[u][g].v, acc[g], 0, 0, 0);
       }
-      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.v, b.v, acc[mt], 0, 0, 0);
-      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.v, bl.v, acc[mt], 0, 0, 0);
-    }
   }
-
-  floatx4* red4 = (floatx4*)red;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) red4[(wave * MT + mt) * 64 + lane] = acc[mt];
+  for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[g];
 
   // row factors of a fused RMSNorm: 1/sqrt(sum of the producer's partial sums of squares / K + eps)
   if (a.ssq) {
-    for (int m = wave; m < R; m += WPB) {
+    for (int m = wave; m < rows_here; m += GW) {
       float s = 0.f;
-      for (int p = lane; p < a.NP; p += 64) s += a.ssq[(int64_t)m * a.NP + p];
+      for (int p = lane; p < a.NP; p += 64) s += a.ssq[(int64_t)(row0 + m) * a.NP + p];
       for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
       if (lane == 0) inv_s[m] = 1.0f / sqrtf(s / (float)K + a.eps);
     }
   }
   __syncthreads();
+  if (wave >= NG) return;
 
-  // D[i][j]: lane l, register i holds packed feature (l/16)*4 + i of row (l%16)
-  for (int idx = threadIdx.x; idx < MT * 64; idx += WPB * 64) {
-    const int mt = idx >> 6, l = idx & 63, g = l >> 4;
-    const int m = mt * 16 + (l & 15);
-    const bool live = m < R;
-    floatx4 s = red4[mt * 64 + l];
-    for (int w = 1; w < WPB; ++w) {
-      const floatx4 t = red4[(w * MT + mt) * 64 + l];
-      s[0] += t[0]; s[1] += t[1]; s[2] += t[2]; s[3] += t[3];
+  // wave g adds the 16 partial sums of row group g in wave order, folds hi + lo (columns c and c + 8 belong to
+  // the same row) and runs the epilogue: lane l, register i = packed feature kg*4 + i, row row0 + g*8 + c (c < 8)
+  {
+    const int g = wave;
+    floatx4 s = red[g * 64 + lane];
+    for (int w2 = 1; w2 < GW; ++w2) {
+      const floatx4 t2 = red[(w2 * NG + g) * 64 + lane];
+      s[0] += t2[0]; s[1] += t2[1]; s[2] += t2[2]; s[3] += t2[3];
     }
-    const float inv = (a.ssq && live) ? inv_s[m] : 1.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s[i] += __shfl_xor(s[i], 8, 64);
+    const int mrel = g * 8 + (c & 7);
+    const int m = row0 + mrel;
+    const bool live = c < 8 && mrel < rows_here;
+    const float inv = (a.ssq && live) ? inv_s[mrel] : 1.0f;
 
     if constexpr (EPI == EPI_STORE) {
-      const int n = nt * 16 + g * 4;
+      const int n = nt * 16 + kg * 4;
       float4 o = make_float4(s[0] * inv, s[1] * inv, s[2] * inv, s[3] * inv);
       if (live) {
         float4* y = (float4*)(a.Y + (int64_t)m * a.ldy + n);
@@ -173,13 +167,10 @@ __global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(GemmArgs a) {
           sm = sm * expf(mx - nm) + osm * expf(omx - nm);
           mx = nm;
         }
-        if (live && g == 0) {
-          float2* p = (float2*)a.lse_part + (int64_t)m * gridDim.x + nt;
-          *p = make_float2(mx, sm);
-        }
+        if (live && kg == 0) ((float2*)a.lse_part)[(int64_t)m * NT + nt] = make_float2(mx, sm);
       }
     } else if constexpr (EPI == EPI_RESID) {
-      const int n = nt * 16 + g * 4;
+      const int n = nt * 16 + kg * 4;
       float4 hn = make_float4(0.f, 0.f, 0.f, 0.f);
       if (live) {
         float4* hp = (float4*)(a.h + (int64_t)m * a.N + n);
@@ -198,16 +189,14 @@ __global__ __launch_bounds__(WPB * 64) void gemm_bf16_kernel(GemmArgs a) {
       float q = hn.x * hn.x + hn.y * hn.y + hn.z * hn.z + hn.w * hn.w;
       q += __shfl_xor(q, 16, 64);
       q += __shfl_xor(q, 32, 64);
-      if (live && g == 0) a.ssq_out[(int64_t)m * gridDim.x + nt] = q;
+      if (live && kg == 0) a.ssq_out[(int64_t)m * NT + nt] = q;
     } else {
-      // paired strips: packed features 0..7 and their partners 8..15 (lane + 32)
-      floatx4 t = red4[mt * 64 + (l ^ 32)];
-      for (int w = 1; w < WPB; ++w) {
-        const floatx4 o = red4[(w * MT + mt) * 64 + (l ^ 32)];
-        t[0] += o[0]; t[1] += o[1]; t[2] += o[2]; t[3] += o[3];
-      }
-      if (g < 2 && live) {
-        const int i0 = g * 4;  // 0 or 4 within the strip's 8 pairs
+      // paired strips: packed features 0..7 (kg 0, 1) and their partners 8..15 (kg 2, 3 = lane + 32)
+      floatx4 t;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) t[i] = __shfl_xor(s[i], 32, 64);
+      if (kg < 2 && live) {
+        const int i0 = kg * 4;  // 0 or 4 within the strip's 8 pairs
         if constexpr (EPI == EPI_SWIGLU) {
           const int f = a.N >> 1;
           ushort4 hi, lo;
@@ -311,31 +300,39 @@ hipError_t launch_gemm_f32(const void* W, const void* X, float* Y, int R, int N,
   return hipGetLastError();
 }
 
-template <int MT, int WPB, int EPI, int TAG>
+size_t gemm_part_floats(int, int) { return 0; }  // no cross-workgroup reduction in this kernel
+
+template <int NG, int EPI, int TAG>
 static hipError_t run_one(const GemmArgs& a, hipStream_t s) {
-  const size_t lds = (size_t)WPB * MT * 64 * 16 + (size_t)MT * 16 * sizeof(float);
-  hipLaunchKernelGGL((gemm_bf16_kernel<MT, WPB, EPI, TAG>), dim3(a.N / 16), dim3(WPB * 64), lds, s, a);
+  hipLaunchKernelGGL((gemm_bf16_kernel<NG, EPI, TAG>), dim3(a.N / 16), dim3(GW * 64), 0, s, a);
   return hipGetLastError();
 }
 
-template <int MT, int WPB, int EPI>
+template <int NG, int EPI>
 static hipError_t run_tag(const GemmArgs& a, int tag, hipStream_t s) {
-  if constexpr (MT <= 2) {
-    if (tag == 1) return run_one<MT, WPB, EPI, 1>(a, s);
-    if (tag == 2) return run_one<MT, WPB, EPI, 2>(a, s);
+  if constexpr (NG <= 3) {
+    if (tag == 1) return run_one<NG, EPI, 1>(a, s);
+    if (tag == 2) return run_one<NG, EPI, 2>(a, s);
   }
-  return run_one<MT, WPB, EPI, 0>(a, s);
+  return run_one<NG, EPI, 0>(a, s);
 }
 
 template <int EPI>
-static hipError_t run_epi(const GemmArgs& a, int tag, hipStream_t s) {
-  const int mt = (a.R + 15) / 16;
-  if (mt <= 1) return run_tag<1, 16, EPI>(a, tag, s);
-  if (mt <= 2) return run_tag<2, 16, EPI>(a, tag, s);
-  if (mt <= 4) return run_tag<4, 8, EPI>(a, tag, s);
-  if (mt <= 8) return run_tag<8, 4, EPI>(a, tag, s);
-  if (mt <= 12) return run_tag<12, 4, EPI>(a, tag, s);
-  return run_tag<16, 3, EPI>(a, tag, s);
+static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
+  // at most 64 rows per launch (8 row groups); more rows re-stream the weights per 64-row slab
+  for (int r0 = 0; r0 < a.R; r0 += 64) {
+    a.row0 = r0;
+    const int ng = ((a.R - r0 < 64 ? a.R - r0 : 64) + 7) / 8;
+    hipError_t e;
+    if (ng <= 1) e = run_tag<1, EPI>(a, tag, s);
+    else if (ng <= 2) e = run_tag<2, EPI>(a, tag, s);
+    else if (ng <= 3) e = run_tag<3, EPI>(a, tag, s);
+    else if (ng <= 4) e = run_tag<4, EPI>(a, tag, s);
+    else if (ng <= 6) e = run_tag<6, EPI>(a, tag, s);
+    else e = run_tag<8, EPI>(a, tag, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s) {

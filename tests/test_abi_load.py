@@ -65,6 +65,6 @@ def test_strerror_and_host_validation(lib):
     assert create(cfg, model(vocab=1040), model()) == mb.MTAD_ESHAPE                             # vocab mismatch
     assert create(mb.mtad_config(8, 4, 4, 1, 64, 512), model(), model()) == mb.MTAD_ESHAPE       # > 256 rows in a pass
     # hot calls validate before launching: null context / null buffers
-    assert lib.mtad_k_gemm(1, None, None, None, 5, 64, 64, 64, 0, None) == mb.MTAD_EINVAL
-    assert lib.mtad_k_gemm(1, C.c_void_p(256), C.c_void_p(256), C.c_void_p(256), 5, 60, 64, 64, 0, None) == mb.MTAD_ESHAPE
+    assert lib.mtad_k_gemm(None, 1, None, None, None, 5, 64, 64, 64, 0, None) == mb.MTAD_EINVAL
+    assert lib.mtad_k_gemm(None, 1, C.c_void_p(256), C.c_void_p(256), C.c_void_p(256), 5, 60, 64, 64, 0, None) == mb.MTAD_ESHAPE
     assert lib.mtad_bind_workspace(None, None, 0) == mb.MTAD_EINVAL
