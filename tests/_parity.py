@@ -42,7 +42,7 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
     sp = [CachedSession(lm_p, list(prompt[s])) for s in range(B)]
     sq = [CachedSession(lm_q, list(prompt[s])) for s in range(B)]
     eng.prefill(prompt)
-    stats = {"iters": 0, "excused": 0, "max_logit_err": 0.0, "eta": [], "tokens": [[] for _ in range(B)]}
+    stats = {"iters": 0, "excused": 0, "max_logit_err": 0.0, "eta": [], "tokens": [[] for _ in range(B)], "events": []}
     _, atol = logit_tolerance(dtype)
     margin_tol = max(atol, 1e-4) * 2
     alive = [True] * B
@@ -71,6 +71,8 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
                     assert h["margin"][i] < margin_tol or _near_tie(h["score"][i], margin_tol), \
                         f"seq {s} iter {stats['iters']} beam step {i}: survivors differ, margin {h['margin'][i]}"
                     alive[s] = False
+                    diff = np.abs(np.sort(g["h_cum"][s, i].astype(np.float64)) - np.sort(h["score"][i].astype(np.float64))).max()
+                    stats["events"].append(("beam step", stats["iters"], i, float(h["margin"][i]), float(diff)))
                     break
                 close(g["h_cum"][s, i], h["score"][i], dtype, f"cum_logq step {i}")
             if not alive[s]:
@@ -90,12 +92,14 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
             # --- accept + bonus
             if g["eta"][s] != tr["eta"] or g["bonus_row"][s] != tr["node"]:
                 assert min(tr["accept_margins"]) < margin_tol * gamma, f"accept differs: {g['eta'][s]} vs {tr['eta']}"
+                stats["events"].append(("accept", stats["iters"], float(min(tr["accept_margins"]))))
                 alive[s] = False
                 stats["excused"] += 1
                 continue
             assert list(g["path"][s, :tr["eta"]]) == tr["path_rows"] and np.all(g["path"][s, tr["eta"]:] == -1)
             if g["bonus_tok"][s] != tr["bonus"]:
                 assert tr["bonus_gap"] < margin_tol, f"bonus token differs with gap {tr['bonus_gap']}"
+                stats["events"].append(("bonus", stats["iters"], float(tr["bonus_gap"])))
                 alive[s] = False
                 stats["excused"] += 1
                 continue
