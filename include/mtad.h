@@ -144,11 +144,16 @@ void mtad_destroy(mtad_ctx *ctx);
  * any hot call.  The contents need no initialisation.  ECAP if too small. */
 size_t mtad_workspace_bytes(const mtad_ctx *ctx);
 int mtad_bind_workspace(mtad_ctx *ctx, void *device_buf, size_t bytes);
+/* bf16 models with at most 32 rows in a pass run all layers of a pass in one persistent kernel (one workgroup per
+ * compute unit, software grid barriers with bounded waits; a wait that gives up sets status bit 3).  on = 0 selects
+ * one kernel per product instead (same arithmetic; used for comparison and as the path for larger passes).
+ * Default on; the environment variable MTAD_PERSISTENT=0 turns it off at context creation. */
+int mtad_set_persistent(mtad_ctx *ctx, int32_t on);
 const char *mtad_strerror(int status);
 int mtad_last_hip_error(const mtad_ctx *ctx); /* hipError_t of the last failed HIP call, 0 if none */
 /* Copies the sticky device status word to *host_bits after synchronising `stream` (the only call that
  * synchronises).  Bit 0: KV capacity exceeded; bit 1: speculative window (64 rows) exceeded;
- * bit 2: bad catch-up count.  0 = clean. */
+ * bit 2: bad catch-up count; bit 3: a grid-barrier wait of the persistent kernel gave up.  0 = clean. */
 int mtad_device_status(mtad_ctx *ctx, uint32_t *host_bits, void *stream);
 
 /* Repacks a row-major bfloat16 matrix [N][K] (device) into the layout the matrix-core kernels stream: the 16x32

@@ -24,8 +24,42 @@ __device__ __forceinline__ void split_bf16(float x, bf16_t& hi, bf16_t& lo) {
   lo = f32_to_bf16(x - bf16_to_f32(hi));
 }
 
+// Device-scope ("coherent") accesses for data that workgroups of ONE kernel hand to each other.  The XCDs' L2
+// caches are not coherent with each other; relaxed device-scope atomics compile to write-through stores and
+// cache-bypassing loads, which avoids flushing or invalidating whole caches.  COH = false: plain accesses (data
+// produced by an earlier kernel).
+template <bool COH>
+__device__ __forceinline__ uint4 ld16(const void* p) {
+  if constexpr (COH) {
+    const unsigned long long* q = (const unsigned long long*)p;
+    const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
+  } else {
+    return *(const uint4*)p;
+  }
+}
+template <bool COH>
+__device__ __forceinline__ float ld4(const float* p) {
+  if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+template <bool COH>
+__device__ __forceinline__ void st8(void* p, uint2 v) {
+  if constexpr (COH)
+    __hip_atomic_store((unsigned long long*)p, (unsigned long long)v.x | ((unsigned long long)v.y << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *(uint2*)p = v;
+}
+template <bool COH>
+__device__ __forceinline__ void st4(float* p, float v) {
+  if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+
 // Device status bits (sticky, OR-ed by kernels that refuse an out-of-range access)
-enum : uint32_t { ST_KV_CAP = 1u, ST_SPEC_WINDOW = 2u, ST_BAD_CATCHUP = 4u };
+enum : uint32_t { ST_KV_CAP = 1u, ST_SPEC_WINDOW = 2u, ST_BAD_CATCHUP = 4u, ST_TIMEOUT = 8u };
 
 // Paged KV addressing: element offset of (layer, logical position pos, kv head 0, dim 0)
 struct KvView {
@@ -59,7 +93,9 @@ hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, 
                         void* planes, float* ssq, hipStream_t s);
 // out = rmsnorm(h) * g, written as hi/lo bf16 planes [2][rows][d] (dtype 1) or f32 [rows][d] (dtype 0)
 hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s);
-hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s);
+// also zeroes the two words at `zero2` when given (the persistent pass kernel's barrier counter and abort flag)
+hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s,
+                             unsigned long long* zero2);
 // rotate q (in place in qkv, float32), rotate k and write k, v to the cache in its storage type
 hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
                           int n_heads, uint32_t* status, hipStream_t s);

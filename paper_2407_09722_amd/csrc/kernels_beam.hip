@@ -61,7 +61,7 @@ __global__ void draft_rows_kernel(RowDesc rd, const int32_t* __restrict__ len, B
       mask = chain_bits(cnt - 1) | (1ull << rel);
       int jj = r;
       for (int ii = step - 1; ii >= 1; --ii) {  // ancestors fed at steps ii = step-1 .. 1
-        jj = hist.parent[(s * gamma + ii) * beam + jj];
+        jj = min(max(hist.parent[(s * gamma + ii) * beam + jj], 0), beam - 1);  // caller-owned memory: stay in range
         mask |= 1ull << (cnt + (ii - 1) * beam + jj);
       }
     } else if (r == 0) {
@@ -251,6 +251,7 @@ __global__ __launch_bounds__(256) void topb_stage1_kernel(const float* __restric
     const int r = c / V, v = c % V;
     float k = cand_score(logits, lse, cum_s, row0, r, v, V);
     if (sample) k += gumbel(nk, (uint64_t)c);
+    if (!(k == k)) k = -INFINITY;  // a NaN score never wins and never leaves an empty slot behind
     list_insert(L, beam, k, c);
   }
   block_merge(L, beam, okey, oidx, shk, shi);
@@ -287,7 +288,8 @@ __global__ __launch_bounds__(256) void topb_stage2_kernel(const float* __restric
   block_merge(L, beam, okey, oidx, shk, shi);
   __syncthreads();
   if (threadIdx.x < beam) {
-    const int c = oidx[threadIdx.x];
+    int c = oidx[threadIdx.x];
+    if (c < 0 || c >= ((step == 0) ? 1 : beam) * V) c = 0;  // only reachable with non-finite logits: stay in bounds
     const int o = (s * gamma + step) * beam + threadIdx.x;
     const int r = c / V, v = c % V;
     hist.tok[o] = v;
@@ -324,7 +326,7 @@ __global__ void build_tree_kernel(BeamView hist, TreeView tree, int B, int gamma
   int beams[MTAD_MAX_GAMMA];
   for (int i = gamma - 1; i >= 0; --i) {
     beams[i] = j;
-    j = hpar[i * beam + j];
+    j = min(max(hpar[i * beam + j], 0), beam - 1);  // caller-owned memory: stay in range
   }
   int32_t* tok = tree.tok + (int64_t)s * M;
   int32_t* par = tree.parent + (int64_t)s * M;
@@ -346,7 +348,7 @@ __global__ void build_tree_kernel(BeamView hist, TreeView tree, int B, int gamma
     for (int i = 0; i < gamma; ++i)
       for (int k = 0; k < beam; ++k) {
         const int r = 1 + i * beam + k;
-        const int p = (i == 0) ? 0 : 1 + (i - 1) * beam + hpar[i * beam + k];
+        const int p = (i == 0) ? 0 : 1 + (i - 1) * beam + min(max(hpar[i * beam + k], 0), beam - 1);
         tok[r] = htok[i * beam + k];
         par[r] = p;
         dep[r] = i + 1;
@@ -438,6 +440,7 @@ __global__ __launch_bounds__(256) void accept_kernel(TreeView tree, const float*
     if (better(k, v, bk, bi)) { bk = k; bi = v; }
   }
   block_best(bk, bi, shk, shi);
+  if (bi < 0 || bi >= V) bi = 0;  // only reachable with non-finite logits: stay in the vocabulary
   if (threadIdx.x == 0) {
     out.bonus_tok[s] = bi;
     out.out_tok[s * (gamma + 1) + eta] = bi;

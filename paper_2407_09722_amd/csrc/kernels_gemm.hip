@@ -20,19 +20,9 @@
 // fp32 path (the tiny all-float32 workload): one wave per output feature, plain FMA, shuffle reduction.
 #include "common.h"
 #include "gemm.h"
+#include "gemm_device.h"
 
 namespace mtad {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float floatx4;
-
-typedef __attribute__((ext_vector_type(4))) unsigned int uintx4;
-
-union Frag {
-  uint4 u;
-  uintx4 n;  // native vector: the form the nontemporal-load builtin accepts
-  bf16x8 v;
-};
 
 // ---- packing ------------------------------------------------------------------------------------------
 
@@ -74,7 +64,6 @@ hipError_t launch_pack_matrix(const void* src, void* dst, int N, int K, int kind
 // g*8 + c - 8, so one MFMA per weight tile covers 8 rows (NG = ceil(rows / 8) MFMAs per tile).  B fragments come
 // from L2 with predicated 16-byte loads issued ahead of the weight loads.  Wave g < NG finishes row group g.
 // TAG only names the call site (0 draft pass, 1 target pass, 2 component entry point) in kernel traces.
-constexpr int GW = 16;
 
 template <int NG, int EPI, int TAG>
 __global__ __launch_bounds__(GW * 64) void gemm_bf16_kernel(GemmArgs a) {
@@ -119,140 +108,9 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
   for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[g];
 
-  // row factors of a fused RMSNorm: 1/sqrt(sum of the producer's partial sums of squares / K + eps)
-  if (a.ssq) {
-    for (int m = wave; m < rows_here; m += GW) {
-      float s = 0.f;
-      for (int p = lane; p < a.NP; p += 64) s += a.ssq[(int64_t)(row0 + m) * a.NP + p];
-      for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-      if (lane == 0) inv_s[m] = 1.0f / sqrtf(s / (float)K + a.eps);
-    }
-  }
+  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
   __syncthreads();
-  if (wave >= NG) return;
-
-  // wave g adds the 16 partial sums of row group g in wave order, folds hi + lo (columns c and c + 8 belong to
-  // the same row) and runs the epilogue: lane l, register i = packed feature kg*4 + i, row row0 + g*8 + c (c < 8)
-  {
-    const int g = wave;
-    floatx4 s = red[g * 64 + lane];
-    for (int w2 = 1; w2 < GW; ++w2) {
-      const floatx4 t2 = red[(w2 * NG + g) * 64 + lane];
-      s[0] += t2[0]; s[1] += t2[1]; s[2] += t2[2]; s[3] += t2[3];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) s[i] += __shfl_xor(s[i], 8, 64);
-    const int mrel = g * 8 + (c & 7);
-    const int m = row0 + mrel;
-    const bool live = c < 8 && mrel < rows_here;
-    const float inv = (a.ssq && live) ? inv_s[mrel] : 1.0f;
-
-    if constexpr (EPI == EPI_STORE) {
-      const int n = nt * 16 + kg * 4;
-      float4 o = make_float4(s[0] * inv, s[1] * inv, s[2] * inv, s[3] * inv);
-      if (live) {
-        float4* y = (float4*)(a.Y + (int64_t)m * a.ldy + n);
-        if (a.accumulate) {
-          const float4 p = *y;
-          o.x += p.x; o.y += p.y; o.z += p.z; o.w += p.w;
-        }
-        *y = o;
-      }
-      if (a.lse_part) {  // (max, sum exp) over this strip's 16 features of row m, merged over the four lane groups
-        float mx = fmaxf(fmaxf(o.x, o.y), fmaxf(o.z, o.w));
-        float sm = expf(o.x - mx) + expf(o.y - mx) + expf(o.z - mx) + expf(o.w - mx);
-        for (int off = 16; off <= 32; off <<= 1) {
-          const float omx = __shfl_xor(mx, off, 64), osm = __shfl_xor(sm, off, 64);
-          const float nm = fmaxf(mx, omx);
-          sm = sm * expf(mx - nm) + osm * expf(omx - nm);
-          mx = nm;
-        }
-        if (live && kg == 0) ((float2*)a.lse_part)[(int64_t)m * NT + nt] = make_float2(mx, sm);
-      }
-    } else if constexpr (EPI == EPI_RESID) {
-      const int n = nt * 16 + kg * 4;
-      float4 hn = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (live) {
-        float4* hp = (float4*)(a.h + (int64_t)m * a.N + n);
-        const float4 p = *hp;
-        hn = make_float4(p.x + s[0], p.y + s[1], p.z + s[2], p.w + s[3]);
-        *hp = hn;
-        const float4 gn = *(const float4*)(a.g_next + n);
-        ushort4 hi, lo;
-        split_bf16(hn.x * gn.x, hi.x, lo.x);
-        split_bf16(hn.y * gn.y, hi.y, lo.y);
-        split_bf16(hn.z * gn.z, hi.z, lo.z);
-        split_bf16(hn.w * gn.w, hi.w, lo.w);
-        *(ushort4*)(a.planes_out + (int64_t)m * a.N + n) = hi;
-        *(ushort4*)(a.planes_out + (int64_t)R * a.N + (int64_t)m * a.N + n) = lo;
-      }
-      float q = hn.x * hn.x + hn.y * hn.y + hn.z * hn.z + hn.w * hn.w;
-      q += __shfl_xor(q, 16, 64);
-      q += __shfl_xor(q, 32, 64);
-      if (live && kg == 0) a.ssq_out[(int64_t)m * NT + nt] = q;
-    } else {
-      // paired strips: packed features 0..7 (kg 0, 1) and their partners 8..15 (kg 2, 3 = lane + 32)
-      floatx4 t;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) t[i] = __shfl_xor(s[i], 32, 64);
-      if (kg < 2 && live) {
-        const int i0 = kg * 4;  // 0 or 4 within the strip's 8 pairs
-        if constexpr (EPI == EPI_SWIGLU) {
-          const int f = a.N >> 1;
-          ushort4 hi, lo;
-          bf16_t* hip = (bf16_t*)&hi;
-          bf16_t* lop = (bf16_t*)&lo;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float gate = s[e] * inv, up = t[e] * inv;
-            split_bf16(gate / (1.0f + expf(-gate)) * up, hip[e], lop[e]);
-          }
-          const int64_t o = (int64_t)m * f + nt * 8 + i0;
-          *(ushort4*)(a.act_out + o) = hi;
-          *(ushort4*)(a.act_out + (int64_t)R * f + o) = lo;
-        } else {  // EPI_QKV
-          const int hd = a.kv.head_dim, half = hd >> 1, tph = hd >> 4;
-          const int head = nt / tph, i = (nt % tph) * 8 + i0;
-          const int H = a.n_heads, KVH = a.kv.n_kv_heads;
-          float x1[4], x2[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { x1[e] = s[e] * inv; x2[e] = t[e] * inv; }
-          if (head < H + KVH) {  // q and k heads are rotated
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float2 cs = a.rope[(int64_t)m * half + i + e];
-              const float y1 = x1[e] * cs.x - x2[e] * cs.y, y2 = x2[e] * cs.x + x1[e] * cs.y;
-              x1[e] = y1;
-              x2[e] = y2;
-            }
-          }
-          if (head < H) {
-            float* q = a.q_out + (int64_t)m * H * hd + (int64_t)head * hd + i;
-            *(float4*)q = make_float4(x1[0], x1[1], x1[2], x1[3]);
-            *(float4*)(q + half) = make_float4(x2[0], x2[1], x2[2], x2[3]);
-          } else {
-            const int slot = a.slot[m];
-            if (slot >= 0) {
-              if (slot >= kv_capacity(a.kv)) {
-                atomicOr(a.status, (uint32_t)ST_KV_CAP);
-              } else {
-                const bool is_k = head < H + KVH;
-                const int gh = is_k ? head - H : head - H - KVH;
-                kv16_t* dst = (kv16_t*)(is_k ? a.kv.k : a.kv.v) + (int64_t)a.layer * a.kv.layer_stride +
-                              kv_token_offset(a.kv, m / a.Rseq, slot) + (int64_t)gh * hd + i;
-                typedef kv16_t half4_t __attribute__((ext_vector_type(4)));
-                half4_t v1, v2;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { v1[e] = (kv16_t)x1[e]; v2[e] = (kv16_t)x2[e]; }
-                *(half4_t*)dst = v1;
-                *(half4_t*)(dst + half) = v2;
-              }
-            }
-          }
-        }
-      }
-    }
-  }
+  if (wave < NG) gemm_finish_group<NG, EPI>(a, nt, wave, red, inv_s, rows_here, lane);
 }
 
 template <int RB>

@@ -115,8 +115,10 @@ hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, 
 
 // table[row][i] = (cos, sin)(pos[row] * theta^(-2i/head_dim)), evaluated in double so that positions in
 // the thousands keep float32-exact angles
-__global__ void rope_table_kernel(const int32_t* __restrict__ pos, float2* __restrict__ table, int rows, int half, float theta) {
+__global__ void rope_table_kernel(const int32_t* __restrict__ pos, float2* __restrict__ table, int rows, int half, float theta,
+                                  unsigned long long* zero2) {
   const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (zero2 && idx < 2) zero2[idx] = 0ull;
   if (idx >= rows * half) return;
   const int row = idx / half, i = idx % half;
   const double inv_freq = pow((double)theta, -(double)i / (double)half);
@@ -126,10 +128,11 @@ __global__ void rope_table_kernel(const int32_t* __restrict__ pos, float2* __res
   table[idx] = make_float2((float)cs, (float)sn);
 }
 
-hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s) {
+hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s,
+                             unsigned long long* zero2) {
   if (rows <= 0) return hipSuccess;
   const int half = head_dim / 2, n = rows * half;
-  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, pos, table, rows, half, theta);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, pos, table, rows, half, theta, zero2);
   return hipGetLastError();
 }
 

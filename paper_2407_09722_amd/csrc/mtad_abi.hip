@@ -5,9 +5,11 @@
 #include "beam.h"
 #include "common.h"
 #include "gemm.h"
+#include "pass.h"
 
 #include <math.h>
 #include <new>
+#include <stdlib.h>
 #include <string.h>
 
 using namespace mtad;
@@ -30,7 +32,17 @@ struct mtad_ctx {
   RowDesc rd;
   uint32_t* status;
   int gemm_groups;
+  unsigned long long* bar;  // grid barrier counter + abort flag of the persistent pass kernel
+  int n_cus;                // compute units of the device (workgroups of the persistent kernel)
+  int persistent;           // use the persistent pass kernel where it applies
   size_t gemm_part_cap;
+  // persistent pass: device copies of the step lists of (up to) two models, the host copies they were made from,
+  // and the device copy of the arguments of the pass being launched
+  PassStep* steps_dev[2];
+  PassStep steps_host[2][pass_steps(PASS_MAX_LAYERS, true)];
+  int steps_n[2];
+  int steps_evict;
+  PassArgs* pass_args;
   int last_hip;
 };
 
@@ -105,6 +117,9 @@ void carve(mtad_ctx* c, char* base) {
   c->gemm_part_cap = pf;
   c->gemm_groups = groups + 1;
   c->gemm_cnt = k.take<int>((size_t)c->gemm_groups);
+  c->bar = k.take<unsigned long long>(32);
+  for (int i = 0; i < 2; ++i) c->steps_dev[i] = k.take<PassStep>(pass_steps(PASS_MAX_LAYERS, true));
+  c->pass_args = k.take<PassArgs>(1);
   c->qkv = k.take<float>(rows * qkv);
   c->gu = k.take<float>(rows * 2 * fmax);
   c->dlogits = k.take<float>((size_t)c->cfg.batch * c->draft_rows * d.vocab);
@@ -156,6 +171,8 @@ int same_shape(const mtad_model* a, const mtad_model* b) {
     }                                   \
   } while (0)
 
+int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* lse, hipStream_t s);
+
 // The decoder pass over B*R rows described by ctx->rd.  float32 models: hidden states end in ctx->h.
 // bf16 models: additionally ctx->xg holds the planes of h*g_final and ctx->ssq the per-strip sums of squares,
 // ready for the lm_head product.
@@ -167,7 +184,7 @@ int decoder_pass_f32(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R,
   const int n_splits = splits_for(c, m, R);
   const void* const* W = m->weights;
   HIP_TRY(c, launch_embed(0, W[0], c->rd.tok, c->h, rows, d, m->vocab, nullptr, nullptr, nullptr, s));
-  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s));
+  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s, nullptr));
   for (int l = 0; l < m->n_layers; ++l) {
     const void* const* L = W + 1 + 6 * l;
     HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)L[0], c->xn, rows, d, m->rms_eps, s));
@@ -189,7 +206,7 @@ int decoder_pass_f32(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R,
 //   o product     -> h += ., planes of h*g_ffn, sums of squares
 //   gate/up prod. (scaled) -> planes of silu(gate)*up
 //   down product  -> h += ., planes of h*g_next, sums of squares
-int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s) {
+int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s, float* logits, float* lse) {
   const int B = c->cfg.batch, rows = B * R;
   const int d = m->d_model, f = m->d_ffn, H = m->n_heads, hd = m->head_dim;
   const int qkvw = (H + 2 * m->n_kv_heads) * hd;
@@ -198,8 +215,38 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const int tag = same_shape(m, &c->tshape) ? 1 : 0;
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
+  const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
   HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, s));
-  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s));
+  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s, nullptr));
+  if (persistent) {  // every layer (and the lm_head) in one launch
+    // step list of this model: built on the host, uploaded when it differs from both cached lists
+    PassStep built[pass_steps(PASS_MAX_LAYERS, true)];
+    const int n_all = pass_steps(m->n_layers, true);
+    pass_build_steps(built, W, m->n_layers, d, f, H, m->n_kv_heads, hd, m->vocab);
+    int slot = -1;
+    for (int i = 0; i < 2; ++i)
+      if (c->steps_n[i] == n_all && memcmp(c->steps_host[i], built, sizeof(PassStep) * n_all) == 0) slot = i;
+    if (slot < 0) {
+      slot = c->steps_evict;
+      c->steps_evict ^= 1;
+      HIP_TRY(c, hipStreamSynchronize(s));  // passes that still read the evicted list have finished
+      HIP_TRY(c, hipMemcpy(c->steps_dev[slot], built, sizeof(PassStep) * n_all, hipMemcpyHostToDevice));
+      memcpy(c->steps_host[slot], built, sizeof(PassStep) * n_all);
+      c->steps_n[slot] = n_all;
+    }
+    PassArgs p;
+    memset(&p, 0, sizeof(p));
+    p.steps = c->steps_dev[slot];
+    p.n_steps = pass_steps(m->n_layers, logits != nullptr);
+    p.d = d; p.f = f; p.H = H; p.KVH = m->n_kv_heads; p.hd = hd; p.vocab = m->vocab;
+    p.rows = rows; p.Rseq = R; p.B = B; p.n_splits = n_splits; p.eps = m->rms_eps;
+    p.kv = kvv; p.rd = c->rd; p.h = c->h; p.xg = (bf16_t*)c->xg; p.xn = (bf16_t*)c->xn; p.ssq = c->ssq; p.q = c->qkv;
+    p.rope = c->rope; p.partial = c->partial; p.attn_cnt = c->attn_cnt; p.logits = logits; p.lse_part = c->lse_part;
+    p.status = c->status; p.bar = c->bar;
+    HIP_TRY(c, launch_pass(p, c->pass_args, c->n_cus, s));
+    if (logits) HIP_TRY(c, launch_lse_finish(c->lse_part, lse, rows, m->vocab / 16, s));
+    return MTAD_OK;
+  }
   int np = 1;  // partial sums of squares per row currently in ctx->ssq
   for (int l = 0; l < m->n_layers; ++l) {
     const void* const* L = W + 1 + 6 * l;
@@ -232,11 +279,15 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     a.g_next = (const float*)(l + 1 < m->n_layers ? W[1 + 6 * (l + 1)] : W[tail]);
     HIP_TRY(c, launch_gemm_bf16(a, EPI_RESID, tag, s));
   }
-  return MTAD_OK;
+  return logits ? lm_head(c, m, rows, logits, lse, s) : MTAD_OK;
 }
 
-int decoder_pass(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s) {
-  return m->dtype == 1 ? decoder_pass_bf16(c, m, kv, R, s) : decoder_pass_f32(c, m, kv, R, s);
+// The pass, followed by final norm + lm_head + row logsumexp when `logits` is given.
+int decoder_pass(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s, float* logits, float* lse) {
+  if (m->dtype == 1) return decoder_pass_bf16(c, m, kv, R, s, logits, lse);
+  int rc = decoder_pass_f32(c, m, kv, R, s);
+  if (rc || !logits) return rc;
+  return lm_head(c, m, c->cfg.batch * R, logits, lse, s);
 }
 
 int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* lse, hipStream_t s) {
@@ -309,6 +360,8 @@ int mtad_create(mtad_ctx** out, const mtad_config* cfg, const mtad_model* target
     delete c;
     return MTAD_ESHAPE;
   }
+  c->persistent = 0;  // opt-in (mtad_set_persistent) until it is the faster path
+  if (const char* e = getenv("MTAD_PERSISTENT")) c->persistent = atoi(e) != 0;
   carve(c, nullptr);
   *out = c;
   return MTAD_OK;
@@ -324,6 +377,12 @@ int mtad_bind_workspace(mtad_ctx* c, void* buf, size_t bytes) {
   if (bytes < c->ws_need) return MTAD_ECAP;
   c->ws = (char*)buf;
   carve(c, c->ws);
+  c->steps_n[0] = c->steps_n[1] = 0;  // the device copies of the step lists live in the workspace
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    c->n_cus = cus;
+  }
   hipError_t e = hipMemset(c->status, 0, 256);
   if (e == hipSuccess) e = hipMemset(c->gemm_cnt, 0, sizeof(int) * (size_t)c->gemm_groups);
   if (e == hipSuccess) e = hipMemset(c->attn_cnt, 0, sizeof(int) * (size_t)c->cfg.batch * imax(c->tshape.n_heads, c->dshape.n_heads) * 4);
@@ -364,7 +423,7 @@ int mtad_prefill(mtad_ctx* c, const mtad_model* model, mtad_kv* kv, const int32_
   for (int c0 = 0; c0 < n_tokens; c0 += R) {
     const int r = imin(R, n_tokens - c0);
     HIP_TRY(c, launch_prefill_rows(c->rd, kv->len, tokens, n_tokens, c0, B, r, cap, c->status, s));
-    int st = decoder_pass(c, model, kv, r, s);
+    int st = decoder_pass(c, model, kv, r, s, nullptr, nullptr);
     if (st) return st;
     HIP_TRY(c, launch_advance_len(kv->len, c->rd.nspec, B, cap, s));
   }
@@ -384,9 +443,7 @@ int mtad_draft_beam_step(mtad_ctx* c, const mtad_model* draft, mtad_kv* dkv, mta
   const BeamView hv{hist->tok, hist->parent, hist->cum_logq};
   HIP_TRY(c, launch_draft_rows(c->rd, dkv->len, hv, st->catchup_tok, st->catchup_cnt, step, B, R, gamma, beam,
                                dkv->page_size * dkv->max_pages, c->status, s));
-  int rc = decoder_pass(c, draft, dkv, R, s);
-  if (rc) return rc;
-  rc = lm_head(c, draft, B * R, c->dlogits, c->lse, s);
+  int rc = decoder_pass(c, draft, dkv, R, s, c->dlogits, c->lse);
   if (rc) return rc;
   HIP_TRY(c, launch_topb(c->dlogits, c->lse, hv, st->catchup_cnt, dkv->len, step, B, R, gamma, beam, draft->vocab, sample_beam ? 1 : 0,
                          seed, c->part_key, c->part_idx, TOPB_BLOCKS, s));
@@ -413,9 +470,7 @@ int mtad_verify_tree(mtad_ctx* c, const mtad_model* target, mtad_kv* tkv, const 
   hipStream_t s = (hipStream_t)stream;
   const int B = c->cfg.batch, M = tree->M;
   HIP_TRY(c, launch_verify_rows(c->rd, tkv->len, root_tok, tview(tree), B, tkv->page_size * tkv->max_pages, c->status, s));
-  int rc = decoder_pass(c, target, tkv, M, s);
-  if (rc) return rc;
-  rc = lm_head(c, target, B * M, logits, row_lse, s);
+  int rc = decoder_pass(c, target, tkv, M, s, logits, row_lse);
   if (rc) return rc;
   HIP_TRY(c, launch_gather_logp(logits, row_lse, tview(tree), B, target->vocab, logp_cond, s));
   return MTAD_OK;
@@ -456,6 +511,12 @@ int mtad_kv_commit(mtad_ctx* c, mtad_kv* tkv, mtad_kv* dkv, const mtad_tree* tre
 }
 
 // ---- component entry points (include/mtad_kernels.h) ------------------------------------------------------------
+
+int mtad_set_persistent(mtad_ctx* c, int32_t on) {
+  if (!c) return MTAD_EINVAL;
+  c->persistent = on != 0;
+  return MTAD_OK;
+}
 
 int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float* Y, int32_t R, int32_t N, int32_t K, int32_t ldy, int32_t accumulate,
                 void* stream) {

@@ -41,6 +41,16 @@ def test_small_pairs_every_iteration_matches(kind, mode, tau):
         assert all(e == 4 for e in st["eta"])          # tau = 0 passes every prefix: commit / gather path
 
 
+@pytest.mark.parametrize("persistent", [True, False])
+def test_both_pass_implementations(persistent):
+    """bf16 passes run either as one persistent kernel or as one kernel per product: same results to tolerance."""
+    ts, ds = SMALL["bf16_hd128"]
+    wt, wd = _weights(ts, 13, "target", boost=4.0), _weights(ds, 13, "draft", boost=4.0)
+    prompt = np.random.default_rng(8).integers(0, ts.vocab, (2, 41)).astype(np.int32)
+    st = run_pair(ts, ds, wt, wd, prompt, 10, gamma=3, beam=3, mode="mmtad", tau=0.0, seed=3, check_kv=True, persistent=persistent)
+    assert st["excused"] == 0
+
+
 def test_identical_models_accept_everything():
     """draft == target: every joint ratio is 1, so eta = gamma in every iteration for any tau < 1."""
     ts = SMALL["fp32"][0]
