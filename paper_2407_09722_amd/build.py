@@ -29,22 +29,23 @@ def _run(cmd):
     return out
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, defines=(), lib: str = LIB, objdir_name: str = "_build") -> str:
+    """Compiles every source for gfx950 and links `lib`.  `defines` adds -D macros (development builds)."""
     hipcc = _hipcc()
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, objdir_name)
     os.makedirs(objdir, exist_ok=True)
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
 
     def one(pair):
         src, obj = pair
-        return _run([hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+        return _run([hipcc, *FLAGS, *["-D" + d for d in defines], "-c", os.path.join(CSRC, src), "-o", obj])
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         logs = list(ex.map(one, zip(SOURCES, objs)))
-    logs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
+    logs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]))
     if verbose:
         print("\n".join(l for l in logs if l.strip()))
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

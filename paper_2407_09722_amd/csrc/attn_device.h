@@ -94,8 +94,8 @@ __device__ __forceinline__ void attn_item(AttnSmem<T, HD, NTHR>& sm, const float
       uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
       if (kj < kend) {
         const int64_t off = kv_token_offset(kv, seq, kj) + e;
-        kk = ld16<COH>(kbase + off);
-        vv = ld16<COH>(vbase + off);
+        kk = *(const uint4*)(kbase + off);  // cache rows are written once per pass, before anyone reads them: no stale copy can exist
+        vv = *(const uint4*)(vbase + off);
       }
       uint32_t* kd = (uint32_t*)(k_s + j * KS + e);  // padded stride: 4-byte aligned only
       kd[0] = kk.x; kd[1] = kk.y; kd[2] = kk.z; kd[3] = kk.w;

@@ -43,6 +43,11 @@ struct mtad_ctx {
   int steps_n[2];
   int steps_evict;
   PassArgs* pass_args;
+  bf16_t* pass_act;  // per-layer activation planes of the persistent pass
+  int pass_rows;     // rows those planes are sized for
+#ifdef MTAD_PASS_PROFILE
+  unsigned long long* prof;
+#endif
   int last_hip;
 };
 
@@ -120,6 +125,19 @@ void carve(mtad_ctx* c, char* base) {
   c->bar = k.take<unsigned long long>(32);
   for (int i = 0; i < 2; ++i) c->steps_dev[i] = k.take<PassStep>(pass_steps(PASS_MAX_LAYERS, true));
   c->pass_args = k.take<PassArgs>(1);
+  {
+    c->pass_rows = (int)(rows < (size_t)PASS_MAX_ROWS ? rows : (size_t)PASS_MAX_ROWS);
+    size_t need = 0;
+    for (const mtad_model* m : {&t, &d}) {
+      if (m->dtype != 1 || m->n_layers > PASS_MAX_LAYERS) continue;
+      const size_t e = (size_t)m->n_layers * pass_act_elems_per_layer(m->d_model, m->n_heads * m->head_dim, m->d_ffn, c->pass_rows);
+      if (e > need) need = e;
+    }
+    c->pass_act = k.take<bf16_t>(need);
+  }
+#ifdef MTAD_PASS_PROFILE
+  c->prof = k.take<unsigned long long>(1024 * 3 * 32);
+#endif
   c->qkv = k.take<float>(rows * qkv);
   c->gu = k.take<float>(rows * 2 * fmax);
   c->dlogits = k.take<float>((size_t)c->cfg.batch * c->draft_rows * d.vocab);
@@ -222,7 +240,7 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     // step list of this model: built on the host, uploaded when it differs from both cached lists
     PassStep built[pass_steps(PASS_MAX_LAYERS, true)];
     const int n_all = pass_steps(m->n_layers, true);
-    pass_build_steps(built, W, m->n_layers, d, f, H, m->n_kv_heads, hd, m->vocab);
+    pass_build_steps(built, W, m->n_layers, d, f, H, m->n_kv_heads, hd, m->vocab, (const bf16_t*)c->xg, c->pass_act, c->pass_rows);
     int slot = -1;
     for (int i = 0; i < 2; ++i)
       if (c->steps_n[i] == n_all && memcmp(c->steps_host[i], built, sizeof(PassStep) * n_all) == 0) slot = i;
@@ -240,9 +258,12 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     p.n_steps = pass_steps(m->n_layers, logits != nullptr);
     p.d = d; p.f = f; p.H = H; p.KVH = m->n_kv_heads; p.hd = hd; p.vocab = m->vocab;
     p.rows = rows; p.Rseq = R; p.B = B; p.n_splits = n_splits; p.eps = m->rms_eps;
-    p.kv = kvv; p.rd = c->rd; p.h = c->h; p.xg = (bf16_t*)c->xg; p.xn = (bf16_t*)c->xn; p.ssq = c->ssq; p.q = c->qkv;
+    p.kv = kvv; p.rd = c->rd; p.h = c->h; p.ssq = c->ssq; p.q = c->qkv;
     p.rope = c->rope; p.partial = c->partial; p.attn_cnt = c->attn_cnt; p.logits = logits; p.lse_part = c->lse_part;
     p.status = c->status; p.bar = c->bar;
+#ifdef MTAD_PASS_PROFILE
+    p.prof = c->prof;
+#endif
     HIP_TRY(c, launch_pass(p, c->pass_args, c->n_cus, s));
     if (logits) HIP_TRY(c, launch_lse_finish(c->lse_part, lse, rows, m->vocab / 16, s));
     return MTAD_OK;
@@ -511,6 +532,10 @@ int mtad_kv_commit(mtad_ctx* c, mtad_kv* tkv, mtad_kv* dkv, const mtad_tree* tre
 }
 
 // ---- component entry points (include/mtad_kernels.h) ------------------------------------------------------------
+
+#ifdef MTAD_PASS_PROFILE
+extern "C" void* mtad_pass_profile(mtad_ctx* c) { return c ? c->prof : nullptr; }
+#endif
 
 int mtad_set_persistent(mtad_ctx* c, int32_t on) {
   if (!c) return MTAD_EINVAL;
