@@ -99,9 +99,14 @@ hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int he
 // rotate q (in place in qkv, float32), rotate k and write k, v to the cache in its storage type
 hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
                           int n_heads, uint32_t* status, hipStream_t s);
-// q: [rows][q_stride] float32 with head h at column h*head_dim; counters: zeroed ints [B][n_heads][ceil(R/16)]
+// q: [rows][q_stride] float32 with head h at column h*head_dim; counters: zeroed ints [B][n_heads][ceil(R/8)]
+// (bf16 models work on chunks of 8 rows, float32 models on chunks of 16)
 hipError_t launch_attention(int dtype, const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
                             float* partial, int n_splits, int* counters, void* out, hipStream_t s);
+// bf16 models (kernels_attn_mfma.hip): half-precision cache, output = bf16 hi / lo planes; n_splits = upper bound on the
+// key splits (the kernel uses fewer for short contexts)
+hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
+                                 float* partial, int n_splits, int* counters, void* out, hipStream_t s);
 // lse[row] from per-strip (max, sum exp) partials [rows][NP]
 hipError_t launch_lse_finish(const float* lse_part, float* lse, int rows, int NP, hipStream_t s);
 hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int rows, int f, hipStream_t s);

@@ -16,7 +16,7 @@ union Frag {
   bf16x8 v;
 };
 
-constexpr int GW = 16;  // waves per workgroup
+constexpr int GW = 8;  // waves per workgroup of the stand-alone product kernel
 
 // Epilogue of one row group of one strip.  s: this lane's four sums (packed features kg*4 .. +3 of strip nt, row m;
 // hi and lo already folded), live: the lane holds a real row, inv: the row's fused-RMSNorm factor (1 if none).

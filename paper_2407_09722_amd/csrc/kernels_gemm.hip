@@ -7,9 +7,8 @@
 // fetches every A fragment as one fully coalesced 1 KiB read and a workgroup streams one contiguous strip.
 // Activations are the B operand, carried as two bf16 planes (hi + lo): the 16 columns of one MFMA hold the hi
 // and lo terms of 8 rows, so a weight tile costs one MFMA per 8 rows.
-// One workgroup owns 16 strips (one per wave) over one k range; the activations of that range sit in LDS and
-// are shared by the 16 waves; k ranges of different workgroups are added in a fixed order by the workgroup
-// that finishes last (deterministic).  The epilogue variants fold the neighbouring element-wise work in:
+// One workgroup owns one strip; its waves split the k tiles and add their partial sums in a fixed order
+// (deterministic).  The epilogue variants fold the neighbouring element-wise work in:
 //   STORE   plain store / accumulate; optional per-strip (max, sum-exp) partials of each row (lm_head)
 //   RESID   residual add, then the next RMSNorm's input: planes of h*gain and per-strip sums of squares
 //   SWIGLU  strips hold 8 gate + 8 up features: silu(gate)*up written as planes
@@ -58,57 +57,87 @@ hipError_t launch_pack_matrix(const void* src, void* dst, int N, int K, int kind
 // ---- the product -----------------------------------------------------------------------------------------
 
 
-// One workgroup = one strip of 16 output features; its 16 waves interleave over the k tiles (wave w takes
-// tiles w, w+16, ...), each with up to U weight tiles in flight, and their partial sums meet in LDS in a fixed
-// order (deterministic).  Columns of the B operand: c < 8 = hi term of row g*8 + c, c >= 8 = lo term of row
-// g*8 + c - 8, so one MFMA per weight tile covers 8 rows (NG = ceil(rows / 8) MFMAs per tile).  B fragments come
-// from L2 with predicated 16-byte loads issued ahead of the weight loads.  Wave g < NG finishes row group g.
+// One workgroup = one strip of 16 output features; its GW waves interleave over the k tiles (wave w takes tiles
+// w, w + GW, ...) in batches of U tiles, and their partial sums meet in LDS in a fixed order (deterministic).
+// Columns of the B operand: c < 8 = hi term of row g*8 + c, c >= 8 = lo term of row g*8 + c - 8, so one MFMA per
+// weight tile covers 8 rows (NG = ceil(rows / 8) MFMAs per tile).  Wave g < NG finishes row group g.
+// Each wave keeps TWO batches in flight (register sets 0 and 1): when a batch has been consumed its registers take
+// the batch two places ahead.  Loads complete in issue order, so a wave that waits for its newest load has waited
+// for all of them; the activation fragments of a batch (L2 hits) are therefore issued BEFORE its weight tiles, two
+// batches ahead of their use, never between a batch's weight loads and its use.  Workgroups are small (512 threads,
+// few registers) so that several are resident per compute unit: while one runs its epilogue or waits for its first
+// tiles, the others keep the memory pipe full.
 // TAG only names the call site (0 draft pass, 1 target pass, 2 component entry point) in kernel traces.
 
+template <int U>
+__device__ __forceinline__ void gemm_load_w(Frag (&w)[U], const char* strip, int KT, int kt, unsigned voff) {
+  const char* base = strip + ((size_t)kt << 10);  // tiles are 1 KiB each, k-major within the strip
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (kt + u * GW < KT) w[u].n = __builtin_nontemporal_load((const uintx4*)(base + (size_t)u * (GW << 10) + voff));
+}
+
+template <int NG, int U>
+__device__ __forceinline__ void gemm_load_b(Frag (&b)[U][NG], const char* X, unsigned xoff, int K, int KT, int kt, int rows_here, int c) {
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      b[u][g].u = make_uint4(0, 0, 0, 0);
+      const char* base = X + ((size_t)g * 8 * K + (size_t)(kt + u * GW) * 32) * 2;
+      if (kt + u * GW < KT && g * 8 + (c & 7) < rows_here) b[u][g].u = *(const uint4*)(base + xoff);
+    }
+}
+
 template <int NG, int EPI, int TAG>
-__global__ __launch_bounds__(GW * 64) void gemm_bf16_kernel(GemmArgs a) {
-  constexpr int U = (NG <= 1) ? 8 : (NG <= 3 ? 4 : 2);  // weight tiles in flight per wave
+__global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1 ? 6 : 4))) void gemm_bf16_kernel(GemmArgs a) {
+  constexpr int U = (NG <= 2) ? 4 : (NG <= 4 ? 2 : 1);  // weight tiles per batch and wave
   __shared__ floatx4 red[GW * NG * 64];
   __shared__ float inv_s[NG * 8];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform by construction: keep it scalar
   const int nt = blockIdx.x;
-  const int K = a.K, KT = K >> 5, NT = a.N >> 4;
+  const int K = a.K, KT = K >> 5;
   const int R = a.R, row0 = a.row0;
   const int rows_here = min(NG * 8, R - row0);
   const int c = lane & 15, kg = lane >> 4;
-  const int64_t lo_plane = (int64_t)R * K;
+
+  // (wave-uniform base) + (32-bit lane offset): the scalar-base addressing mode, one offset register per stream
+  const char* strip = (const char*)a.W + (((size_t)nt * KT) << 10);
+  const unsigned voff = (unsigned)lane * 16u;
+  const char* X = (const char*)a.X + (size_t)row0 * K * 2;
+  const unsigned xoff = (unsigned)((((size_t)(c >> 3) * R + (c & 7)) * K + kg * 8) * 2);  // plane c/8, row c%8, k group kg
+
+  constexpr int span = U * GW;
+  Frag w[2][U], b[2][U][NG];
+  gemm_load_b<NG, U>(b[0], X, xoff, K, KT, wave, rows_here, c);
+  gemm_load_w<U>(w[0], strip, KT, wave, voff);
+  gemm_load_b<NG, U>(b[1], X, xoff, K, KT, wave + span, rows_here, c);
+  gemm_load_w<U>(w[1], strip, KT, wave + span, voff);
 
   floatx4 acc[NG];
 #pragma unroll
   for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-  const uintx4* wp = (const uintx4*)a.W + (int64_t)nt * KT * 64 + lane;
-  // this lane's B-fragment source: plane c/8, row row0 + g*8 + c%8, k offset kg*8 within a tile
-  const bf16_t* xp = a.X + (c >> 3) * lo_plane + (int64_t)(row0 + (c & 7)) * K + kg * 8;
+  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
 
-  for (int kt = wave; kt < KT; kt += U * GW) {
-    Frag b[U][NG], w[U];
+  for (int kt = wave; kt < KT; kt += 2 * span) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int h = 0; h < 2; ++h) {
+      const int k0 = kt + h * span;
 #pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        b[u][g].u = make_uint4(0, 0, 0, 0);
-        if (kt + u * GW < KT && g * 8 + (c & 7) < rows_here)
-          b[u][g].u = *(const uint4*)(xp + (int64_t)g * 8 * K + (int64_t)(kt + u * GW) * 32);
+      for (int u = 0; u < U; ++u)
+        if (k0 + u * GW < KT) {
+#pragma unroll
+          for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[h][u].v, b[h][u][g].v, acc[g], 0, 0, 0);
+        }
+      if (k0 + 2 * span < KT) {
+        gemm_load_b<NG, U>(b[h], X, xoff, K, KT, k0 + 2 * span, rows_here, c);
+        gemm_load_w<U>(w[h], strip, KT, k0 + 2 * span, voff);
       }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (kt + u * GW < KT) w[u].n = __builtin_nontemporal_load(wp + (int64_t)(kt + u * GW) * 64);
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      if (kt + u * GW < KT) {
-#pragma unroll
-        for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[u].v, b[u][g].v, acc[g], 0, 0, 0);
-      }
+    }
   }
 #pragma unroll
   for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[g];
-
-  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
   __syncthreads();
   if (wave < NG) gemm_finish_group<NG, EPI>(a, nt, wave, red, inv_s, rows_here, lane);
 }

@@ -152,9 +152,10 @@ __global__ __launch_bounds__(PT) void pass_kernel(const PassArgs* args) {
   }
 
 #ifdef MTAD_PASS_PROFILE
-  // timestamps (100 MHz): [workgroup][step - 20][start, products done, end]
+  // timestamps (100 MHz): [workgroup][step - first recorded step][start, products done, end]
   unsigned long long* const prof = A0->prof + bid * 3 * 32;  // steps 20 .. 51 of every workgroup
-#define PROF(k) if (s >= 20 && s < 52 && threadIdx.x == 0) prof[(s - 20) * 3 + (k)] = wall_clock64()
+  const int prof0 = n_steps > 52 ? 20 : 0;
+#define PROF(k) if (s >= prof0 && s < prof0 + 32 && threadIdx.x == 0) prof[(s - prof0) * 3 + (k)] = wall_clock64()
 #else
 #define PROF(k)
 #endif

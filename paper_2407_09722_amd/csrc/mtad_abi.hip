@@ -26,6 +26,7 @@ struct mtad_ctx {
   float *h, *qkv, *gu, *dlogits, *lse, *partial, *part_key, *ssq, *lse_part;
   void *xn, *xg;  // xn: attention output / FFN activation; xg: h*gain planes feeding the next normalised product
   int *attn_cnt, *gemm_cnt;
+  size_t attn_cnt_n;
   float* gemm_part;
   float2* rope;
   int* part_idx;
@@ -105,7 +106,8 @@ void carve(mtad_ctx* c, char* base) {
   c->xg = k.take<float>(rows * dmax);
   c->ssq = k.take<float>(rows * (size_t)(dmax / 16 + 1));
   c->lse_part = k.take<float>(rows * (size_t)(imax(t.vocab, d.vocab) / 16 + 1) * 2);
-  c->attn_cnt = k.take<int>((size_t)c->cfg.batch * imax(t.n_heads, d.n_heads) * 4);
+  c->attn_cnt_n = (size_t)c->cfg.batch * imax(t.n_heads, d.n_heads) * (size_t)((c->Rmax + 7) / 8);
+  c->attn_cnt = k.take<int>(c->attn_cnt_n);
   size_t pf = 0;
   int groups = 0;
   for (const mtad_model* m : {&t, &d}) {
@@ -282,7 +284,8 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     a.ssq = c->ssq; a.NP = np;
     a.q_out = c->qkv; a.rope = c->rope; a.slot = c->rd.slot; a.kv = kvv; a.layer = l; a.Rseq = R; a.n_heads = H; a.status = c->status;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_QKV, tag, s));
-    HIP_TRY(c, launch_attention(1, c->qkv, H * hd, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->attn_cnt, c->xn, s));
+    HIP_TRY(c, launch_attention(1, c->qkv, H * hd, c->rd, kvv, l, B, R, H, c->partial, imin(32, (c->cfg.max_context + 1023) / 1024), c->attn_cnt,
+                                c->xn, s));
     // o projection + residual; prepares the FFN's normalised input
     a.W = (const bf16_t*)L[2]; a.X = (const bf16_t*)c->xn; a.N = d; a.K = H * hd;
     a.ssq = nullptr; a.NP = 0;
@@ -406,7 +409,7 @@ int mtad_bind_workspace(mtad_ctx* c, void* buf, size_t bytes) {
   }
   hipError_t e = hipMemset(c->status, 0, 256);
   if (e == hipSuccess) e = hipMemset(c->gemm_cnt, 0, sizeof(int) * (size_t)c->gemm_groups);
-  if (e == hipSuccess) e = hipMemset(c->attn_cnt, 0, sizeof(int) * (size_t)c->cfg.batch * imax(c->tshape.n_heads, c->dshape.n_heads) * 4);
+  if (e == hipSuccess) e = hipMemset(c->attn_cnt, 0, sizeof(int) * c->attn_cnt_n);
   if (e != hipSuccess) {
     c->last_hip = (int)e;
     return MTAD_EHIP;
