@@ -3,9 +3,9 @@
 //
 // Work item = (key split, head, chunk of 8 query rows, sequence) = one workgroup of 8 waves.  The keys of the item
 // are cut into 32-key tiles dealt round-robin to the waves; every wave runs its own online softmax over its tiles
-// and the 8 waves merge through LDS at the end, so a context of a few hundred keys needs no exchange through
-// global memory at all: with one split the workgroup writes the attention output itself.  Longer contexts use
-// several splits and the last-arriver merge of the generic kernel (same partial layout, same fixed merge order).
+// and the 8 waves merge through LDS at the end.  A context of up to 256 keys is one workgroup, which writes the
+// attention output itself; longer contexts use one split per 256 keys and the last-arriver merge of the generic
+// kernel (same partial layout, same fixed merge order).
 //
 // Scores are computed transposed, S^T = K Q^T, on the matrix cores: the A operand of v_mfma_f32_16x16x32_f16 wants,
 // per lane, 8 consecutive dims of one key = 16 contiguous bytes of a cache row, so K goes from global memory
@@ -24,7 +24,7 @@ namespace {
 constexpr int AW = 8;        // waves per workgroup
 constexpr int ARB = 8;       // query rows per work item
 constexpr int ATK = 32;      // keys per tile
-constexpr int KEYS_PER_SPLIT = 1024;  // a workgroup streams at most this many keys when splits are available
+constexpr int KEYS_PER_SPLIT = 256;  // keys per workgroup when splits are available: one 32-key tile per wave (measured best at 512 keys)
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));

@@ -284,7 +284,7 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     a.ssq = c->ssq; a.NP = np;
     a.q_out = c->qkv; a.rope = c->rope; a.slot = c->rd.slot; a.kv = kvv; a.layer = l; a.Rseq = R; a.n_heads = H; a.status = c->status;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_QKV, tag, s));
-    HIP_TRY(c, launch_attention(1, c->qkv, H * hd, c->rd, kvv, l, B, R, H, c->partial, imin(32, (c->cfg.max_context + 1023) / 1024), c->attn_cnt,
+    HIP_TRY(c, launch_attention(1, c->qkv, H * hd, c->rd, kvv, l, B, R, H, c->partial, imin(32, (c->cfg.max_context + 127) / 128), c->attn_cnt,
                                 c->xn, s));
     // o projection + residual; prepares the FFN's normalised input
     a.W = (const bf16_t*)L[2]; a.X = (const bf16_t*)c->xn; a.N = d; a.K = H * hd;
