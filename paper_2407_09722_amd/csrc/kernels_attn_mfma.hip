@@ -1,30 +1,30 @@
 // Tree-masked paged attention for bf16 models (half-precision K/V cache), few query rows per sequence
 // (Section 3.3: tree attention gives every tree token its conditional likelihood in one pass).
 //
-// Work item = (key split, head, chunk of 8 query rows, sequence) = one workgroup of 8 waves.  The keys of the item
-// are cut into 32-key tiles dealt round-robin to the waves; every wave runs its own online softmax over its tiles
-// and the 8 waves merge through LDS at the end.  A context of up to 256 keys is one workgroup, which writes the
-// attention output itself; longer contexts use one split per 256 keys and the last-arriver merge of the generic
-// kernel (same partial layout, same fixed merge order).
+// Work item = (key split, head, chunk of 16 or 32 query rows, sequence) = one workgroup of 4 waves.  The keys of the
+// item are cut into 32-key tiles dealt round-robin to the waves; every wave runs its own online softmax over its
+// tiles and the 4 waves merge through LDS at the end.  A context of up to 128 keys is one workgroup, which writes the
+// attention output itself; longer contexts use one split per 128 keys and the workgroup that arrives last merges
+// the splits in split order (same partial layout and protocol as the generic kernel).
 //
-// Scores are computed transposed, S^T = K Q^T, on the matrix cores: the A operand of v_mfma_f32_16x16x32_f16 wants,
-// per lane, 8 consecutive dims of one key = 16 contiguous bytes of a cache row, so K goes from global memory
-// straight into the operand registers; Q^T (B operand) is the float32 query split into two half terms (hi + lo, two
-// MFMAs), which keeps the product at float32 accuracy.  The result leaves lane (g, r) with the scores of row r for
-// 8 of the tile's keys, which is what the per-row softmax needs (two cross-lane steps).  P V runs on the vector
-// ALU: lane = (8-dim chunk of the head, key subgroup); probabilities reach it through a wave-private LDS tile.
-// Loads are issued a tile ahead: K of the next tile is requested before the scores of this one are computed, and
-// V of a tile before its scores, so that one memory latency is exposed per workgroup, not one per tile.
+// Both products run on the matrix cores, transposed, so that every operand is cheap to fetch:
+//   S^T = K Q^T   A operand = 8 consecutive dims of one key per lane = 16 contiguous bytes of a cache row, loaded from
+//                 global memory straight into the operand registers; B operand = Q as two half terms (hi + lo, two
+//                 MFMAs: float32 accuracy) from LDS.  Lane (g, r) ends up with the scores of row r for 8 keys of
+//                 the tile: the per-row softmax needs two cross-lane steps and stays in that lane.
+//   O^T = V^T P^T the probabilities a lane holds are exactly its B operand (the k index of the contraction is
+//                 assigned to keys in the order the score product left them), again as hi + lo halves; V^T fragments
+//                 are read transposed from a wave-private LDS copy of the V tile (padded rows: conflict free).
+// The running output, maximum and sum of a row all live in the lanes of that row: no exchange inside the tile loop.
 #include "common.h"
 
 namespace mtad {
 
 namespace {
 
-constexpr int AW = 8;        // waves per workgroup
-constexpr int ARB = 8;       // query rows per work item
-constexpr int ATK = 32;      // keys per tile
-constexpr int KEYS_PER_SPLIT = 256;  // keys per workgroup when splits are available: one 32-key tile per wave (measured best at 512 keys)
+constexpr int AW = 4;                // waves per workgroup
+constexpr int ATK = 32;              // keys per tile
+constexpr int KEYS_PER_SPLIT = 128;  // keys per workgroup when splits are available: one tile per wave
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -34,12 +34,17 @@ union KFrag {
   half8 h;
 };
 
-template <int HD>
+template <int HD, int NRG>
 struct MfmaAttnSmem {
-  float p[AW][ATK][ARB];       // probabilities of the wave's current tile, [key][row]
-  float alpha[AW][ARB];        // rescale factor of the running output, per row
-  float o[AW][ARB][HD];        // per-wave outputs for the final merge
-  float m[AW][ARB], l[AW][ARB];
+  static constexpr int VS = HD + 8;  // padded row of halves: 16-byte aligned, keys 4 apart land 16 banks apart
+  union {
+    struct {
+      _Float16 v[AW][ATK][VS];         // V tile of each wave
+      _Float16 q[2][NRG * 16][VS];     // query rows, hi and lo halves
+    } a;
+    float o[AW][16][HD];               // per-wave outputs of one row group for the final merge
+  };
+  float m[AW][NRG * 16], l[AW][NRG * 16];
   int last;
 };
 
@@ -53,21 +58,26 @@ __device__ __forceinline__ int token_index(const KvView& kv, int seq, int pos) {
   return page * kv.page_size + pos % kv.page_size;
 }
 
-template <int HD>
+template <int HD, int NRG>
 __global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
                                                                int R, int n_heads, int n_chunks, float scale, float* __restrict__ partial,
                                                                int n_splits, int* __restrict__ counters, bf16_t* __restrict__ out) {
-  constexpr int KS = HD / 32;      // k-steps of the score product
-  constexpr int CH = HD / 8;       // 8-dim chunks of a head
-  constexpr int SG = 64 / CH;      // key subgroups in the P V phase
-  constexpr int KPS = ATK / SG;    // keys per subgroup and tile
-  __shared__ MfmaAttnSmem<HD> sm;
+  constexpr int KS = HD / 32;    // k-steps of the score product
+  constexpr int DB = HD / 16;    // 16-dim blocks of the output
+  constexpr int CH = HD / 8;     // 16-byte chunks of a cache row
+  constexpr int KPL = 64 / CH;   // keys one V load instruction covers
+  constexpr int NV = ATK / KPL;  // V load instructions per tile
+  constexpr int RBK = NRG * 16;  // query rows per work item
+  constexpr int DPT = HD / 16;   // output dims per thread in the merge (16 threads per row)
+  using Smem = MfmaAttnSmem<HD, NRG>;
+  constexpr int VS = Smem::VS;
+  __shared__ Smem sm;
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int split = blockIdx.x, head = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks, seq = blockIdx.z;
   const int B = gridDim.z;
-  const int row0 = chunk * ARB, nrows = min(ARB, R - row0);
+  const int row0 = chunk * RBK, nrows = min(RBK, R - row0);
   const int KVH = kv.n_kv_heads, g = head * KVH / n_heads;
   const int len = kv.len[seq];
   const int nspec = max(0, min(rd.nspec[seq], 64));
@@ -81,50 +91,24 @@ __global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __
   const int kbeg = split * per, kend = min(ktot, kbeg + per);
   const int n_tiles = kend > kbeg ? (kend - kbeg + ATK - 1) / ATK : 0;
 
-  // score-phase role: query row and key group; output-phase role: dim chunk and key subgroup
-  const int srow = lane & 15, sg4 = lane >> 4;
-  const int dc = lane % CH, kq = lane / CH;
-  const bool row_ok = srow < nrows;
-  const unsigned long long rmask = row_ok ? rd.mask[seq * R + row0 + srow] : 0ull;
-
-  // Q^T operand: row srow, dims ks*32 + sg4*8 .. +8, as hi + lo halves
-  half8 qh[KS], ql[KS];
-  {
-    const float* qp = q + (int64_t)(seq * R + row0 + srow) * q_stride + (int64_t)head * HD + sg4 * 8;
+  const int srow = lane & 15, sg4 = lane >> 4;  // this lane's query row (within a row group) and key group
+  unsigned long long rmask[NRG];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b2 = a;
-      if (row_ok) {
-        a = *(const float4*)(qp + ks * 32);
-        b2 = *(const float4*)(qp + ks * 32 + 4);
-      }
-      const float v[8] = {a.x, a.y, a.z, a.w, b2.x, b2.y, b2.z, b2.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const _Float16 hi = (_Float16)v[e];
-        qh[ks][e] = hi;
-        ql[ks][e] = (_Float16)(v[e] - (float)hi);
-      }
-    }
-  }
-
-  const int64_t tok_stride = (int64_t)KVH * HD;  // elements per cached token
-  const kv16_t* kbase = (const kv16_t*)kv.k + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
-  const kv16_t* vbase = (const kv16_t*)kv.v + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
-
-  float m_run = -INFINITY, l_run = 0.f;  // of row srow (replicated over the four key groups)
-  float acc[ARB][8];
-#pragma unroll
-  for (int r = 0; r < ARB; ++r)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+  for (int rg = 0; rg < NRG; ++rg) rmask[rg] = (rg * 16 + srow < nrows) ? rd.mask[seq * R + row0 + rg * 16 + srow] : 0ull;
 
   // token index of key (tile start + lane % 32), looked up once per tile and handed round by shuffles
   auto lookup = [&](int ti) -> int {
     const int kj = kbeg + ti * ATK + (lane & 31);
     return (ti < n_tiles && kj < kend) ? token_index(kv, seq, kj) : -1;
   };
-  auto load_k = [&](KFrag (&kf)[2][KS], int tok32) {
+  const int64_t tok_stride = (int64_t)KVH * HD;  // elements per cached token
+  const kv16_t* kbase = (const kv16_t*)kv.k + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
+  const kv16_t* vbase = (const kv16_t*)kv.v + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
+
+  // first tile's K and V are requested before the queries are staged
+  int tok_cur = lookup(wave);
+  KFrag kf[2][KS], vf[NV];
+  auto load_kv = [&](int tok32) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
       const int tk = __shfl(tok32, blk * 16 + srow, 64);
@@ -134,178 +118,186 @@ __global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __
         if (tk >= 0) kf[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
       }
     }
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int tk = __shfl(tok32, j * KPL + lane / CH, 64);
+      vf[j].u = make_uint4(0, 0, 0, 0);  // keys past the end contribute exact zeros
+      if (tk >= 0) vf[j].u = *(const uint4*)(vbase + (int64_t)tk * tok_stride + (lane % CH) * 8);
+    }
   };
+  if (wave < n_tiles) load_kv(tok_cur);
 
-  KFrag kf[2][KS], kn[2][KS];
-  int tok_cur = lookup(wave), tok_next = -1;
-  if (wave < n_tiles) load_k(kf, tok_cur);
-
-  for (int ti = wave; ti < n_tiles; ti += AW) {
-    // V of this tile, then K of the next: both in flight while the scores are computed
-    KFrag vf[KPS];
+  // queries of the item as half hi / lo terms in LDS (rows beyond the item are zero)
+  for (int i = t; i < RBK * (HD / 4); i += AW * 64) {
+    const int r = i / (HD / 4), d = (i % (HD / 4)) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r < nrows) v = *(const float4*)(q + (int64_t)(seq * R + row0 + r) * q_stride + (int64_t)head * HD + d);
+    const float x[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int j = 0; j < KPS; ++j) {
-      const int tk = __shfl(tok_cur, kq * KPS + j, 64);
-      vf[j].u = make_uint4(0, 0, 0, 0);
-      if (tk >= 0) vf[j].u = *(const uint4*)(vbase + (int64_t)tk * tok_stride + dc * 8);
+    for (int e = 0; e < 4; ++e) {
+      const _Float16 hi = (_Float16)x[e];
+      sm.a.q[0][r][d + e] = hi;
+      sm.a.q[1][r][d + e] = (_Float16)(x[e] - (float)hi);
     }
-    const bool more = ti + AW < n_tiles;
-    if (more) {
-      tok_next = lookup(ti + AW);
-      load_k(kn, tok_next);
-    }
-
-    // S^T = K Q^T: lane (sg4, srow) gets keys blk*16 + sg4*4 + i of row srow
-    floatx4 s2[2];
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
-      s2[blk] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        s2[blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, qh[ks], s2[blk], 0, 0, 0);
-        s2[blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, ql[ks], s2[blk], 0, 0, 0);
-      }
-    }
-    // visibility, scale, running softmax of row srow
-    float tmax = -INFINITY;
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int kj = kbeg + ti * ATK + blk * 16 + sg4 * 4 + i;
-        bool vis = kj < kend;
-        if (vis && kj >= len) vis = (rmask >> (kj - len)) & 1ull;
-        const float sv = vis ? s2[blk][i] * scale : -INFINITY;
-        s2[blk][i] = sv;
-        tmax = fmaxf(tmax, sv);
-      }
-    tmax = xmax(xmax(tmax, 16), 32);
-    const float m_new = fmaxf(m_run, tmax);
-    const float alpha = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
-    float psum = 0.f;
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float pv = (s2[blk][i] == -INFINITY) ? 0.f : expf(s2[blk][i] - m_new);
-        s2[blk][i] = pv;
-        psum += pv;
-      }
-    psum = xsum(xsum(psum, 16), 32);
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    if (srow < ARB) {
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sm.p[wave][blk * 16 + sg4 * 4 + i][srow] = s2[blk][i];
-      if (sg4 == 0) sm.alpha[wave][srow] = alpha;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // O = alpha O + P V for this lane's 8 dims and KPS keys
-    {
-      float al[ARB];
-#pragma unroll
-      for (int r = 0; r < ARB; ++r) al[r] = sm.alpha[wave][r];
-#pragma unroll
-      for (int r = 0; r < ARB; ++r)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[r][e] *= al[r];
-#pragma unroll
-      for (int j = 0; j < KPS; ++j) {
-        float pr[ARB];
-        const float4 p0 = *(const float4*)&sm.p[wave][kq * KPS + j][0];
-        const float4 p1 = *(const float4*)&sm.p[wave][kq * KPS + j][4];
-        pr[0] = p0.x; pr[1] = p0.y; pr[2] = p0.z; pr[3] = p0.w; pr[4] = p1.x; pr[5] = p1.y; pr[6] = p1.z; pr[7] = p1.w;
-        float vv[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vv[e] = (float)vf[j].h[e];
-#pragma unroll
-        for (int r = 0; r < ARB; ++r)
-          if (r < nrows) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[r][e] = fmaf(pr[r], vv[e], acc[r][e]);
-          }
-      }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();  // the tile's probabilities have been read before the next tile overwrites them
-    if (more) {
-#pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kf[blk][ks] = kn[blk][ks];
-      tok_cur = tok_next;
-    }
-  }
-
-  // the key subgroups of a wave add up (fixed order), then the waves meet in LDS
-#pragma unroll
-  for (int r = 0; r < ARB; ++r)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float v = acc[r][e];
-      for (int off = CH; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
-      acc[r][e] = v;
-    }
-  if (kq == 0) {
-#pragma unroll
-    for (int r = 0; r < ARB; ++r) {
-      *(float4*)&sm.o[wave][r][dc * 8] = make_float4(acc[r][0], acc[r][1], acc[r][2], acc[r][3]);
-      *(float4*)&sm.o[wave][r][dc * 8 + 4] = make_float4(acc[r][4], acc[r][5], acc[r][6], acc[r][7]);
-    }
-  }
-  if (sg4 == 0 && srow < ARB) {
-    sm.m[wave][srow] = m_run;
-    sm.l[wave][srow] = l_run;
   }
   __syncthreads();
 
-  // merge of the 8 waves in wave order: thread = (row, dim); HD = 128 takes two dims per thread
-  const int mr = t >> 6;  // 0 .. 7 = row
-  float M = -INFINITY;
+  float m_run[NRG], l_run[NRG];  // of row rg*16 + srow (replicated over the four key groups)
+  floatx4 acc[NRG][DB];          // O^T: dims db*16 + sg4*4 + i of row rg*16 + srow
 #pragma unroll
-  for (int w2 = 0; w2 < AW; ++w2) M = fmaxf(M, sm.m[w2][mr]);
-  float L = 0.f, o[HD / 64];
+  for (int rg = 0; rg < NRG; ++rg) {
+    m_run[rg] = -INFINITY;
+    l_run[rg] = 0.f;
 #pragma unroll
-  for (int x = 0; x < HD / 64; ++x) o[x] = 0.f;
-#pragma unroll
-  for (int w2 = 0; w2 < AW; ++w2) {
-    const float mw = sm.m[w2][mr];
-    const float e = (mw == -INFINITY) ? 0.f : expf(mw - M);
-    L += sm.l[w2][mr] * e;
-#pragma unroll
-    for (int x = 0; x < HD / 64; ++x) o[x] += sm.o[w2][mr][lane + 64 * x] * e;
-  }
-  const int64_t lo_plane = (int64_t)B * R * n_heads * HD;
-  if (eff == 1) {  // nothing to exchange: this workgroup saw every key
-    if (mr < nrows) {
-#pragma unroll
-      for (int x = 0; x < HD / 64; ++x) {
-        const float y = (L > 0.f) ? o[x] / L : 0.f;
-        const int64_t idx = (int64_t)(seq * R + row0 + mr) * n_heads * HD + (int64_t)head * HD + lane + 64 * x;
-        bf16_t hi, lo;
-        split_bf16(y, hi, lo);
-        out[idx] = hi;
-        out[lo_plane + idx] = lo;
-      }
-    }
-    return;
+    for (int db = 0; db < DB; ++db) acc[rg][db] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]); device-scope write-through stores, cache-bypassing loads
-  if (mr < nrows) {
-    float* p = partial + ((((int64_t)seq * n_heads + head) * R + row0 + mr) * n_splits + split) * (HD + 2);
+  for (int ti = wave; ti < n_tiles; ti += AW) {
+    // V tile -> wave-private LDS copy
 #pragma unroll
-    for (int x = 0; x < HD / 64; ++x) __hip_atomic_store(p + 2 + lane + 64 * x, o[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (lane == 0) {
-      __hip_atomic_store(p, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(p + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int j = 0; j < NV; ++j) *(uint4*)&sm.a.v[wave][j * KPL + lane / CH][(lane % CH) * 8] = vf[j].u;
+
+    // S^T = K Q^T: lane (sg4, srow) gets keys blk*16 + sg4*4 + i of row rg*16 + srow
+    floatx4 s2[NRG][2];
+#pragma unroll
+    for (int rg = 0; rg < NRG; ++rg)
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk) s2[rg][blk] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int rg = 0; rg < NRG; ++rg) {
+        const half8 qh = *(const half8*)&sm.a.q[0][rg * 16 + srow][ks * 32 + sg4 * 8];
+        const half8 ql = *(const half8*)&sm.a.q[1][rg * 16 + srow][ks * 32 + sg4 * 8];
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, qh, s2[rg][blk], 0, 0, 0);
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, ql, s2[rg][blk], 0, 0, 0);
+        }
+      }
+    // the next tile's K and V can go now: their registers are free
+    const bool more = ti + AW < n_tiles;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the V tile is in LDS (the wave reads what other lanes wrote)
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    int tok_next = -1;
+    if (more) {
+      tok_next = lookup(ti + AW);
+      load_kv(tok_next);
+    }
+
+    // visibility, scale, running softmax per row; probabilities become the B operand of the second product
+    half8 ph[NRG], pl[NRG];
+#pragma unroll
+    for (int rg = 0; rg < NRG; ++rg) {
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int kj = kbeg + ti * ATK + blk * 16 + sg4 * 4 + i;
+          bool vis = kj < kend;
+          if (vis && kj >= len) vis = (rmask[rg] >> (kj - len)) & 1ull;
+          const float sv = vis ? s2[rg][blk][i] * scale : -INFINITY;
+          s2[rg][blk][i] = sv;
+          tmax = fmaxf(tmax, sv);
+        }
+      tmax = xmax(xmax(tmax, 16), 32);
+      const float m_new = fmaxf(m_run[rg], tmax);
+      const float alpha = (m_run[rg] == -INFINITY) ? 0.f : expf(m_run[rg] - m_new);
+      float psum = 0.f;
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pv = (s2[rg][blk][i] == -INFINITY) ? 0.f : expf(s2[rg][blk][i] - m_new);
+          psum += pv;
+          const _Float16 hi = (_Float16)pv;
+          ph[rg][blk * 4 + i] = hi;
+          pl[rg][blk * 4 + i] = (_Float16)(pv - (float)hi);
+        }
+      psum = xsum(xsum(psum, 16), 32);
+      l_run[rg] = l_run[rg] * alpha + psum;
+      m_run[rg] = m_new;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[rg][db][i] *= alpha;
+    }
+
+    // O^T += V^T P^T: contraction slot e of key group sg4 is key (e/4)*16 + sg4*4 + e%4, as the scores came out
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      half8 vt;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vt[e] = sm.a.v[wave][(e >> 2) * 16 + sg4 * 4 + (e & 3)][db * 16 + srow];
+#pragma unroll
+      for (int rg = 0; rg < NRG; ++rg) {
+        acc[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vt, ph[rg], acc[rg][db], 0, 0, 0);
+        acc[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vt, pl[rg], acc[rg][db], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the V tile has been read before the next one overwrites it
+    tok_cur = tok_next;
+  }
+
+  // ---- the 4 waves meet in LDS, one row group at a time (the buffer aliases the V tiles and the queries)
+  const int mrow = t >> 4, md = (t & 15) * DPT;  // merge role: row within the group, first of DPT dims
+  const int64_t lo_plane = (int64_t)B * R * n_heads * HD;
+#pragma unroll
+  for (int rg = 0; rg < NRG; ++rg) {
+    if (sg4 == 0) {
+      sm.m[wave][rg * 16 + srow] = m_run[rg];
+      sm.l[wave][rg * 16 + srow] = l_run[rg];
     }
   }
+#pragma unroll
+  for (int rg = 0; rg < NRG; ++rg) {
+    __syncthreads();  // everyone is done with the tiles (first pass) / with the previous row group's buffer
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      *(float4*)&sm.o[wave][srow][db * 16 + sg4 * 4] = make_float4(acc[rg][db][0], acc[rg][db][1], acc[rg][db][2], acc[rg][db][3]);
+    __syncthreads();
+    const int r = rg * 16 + mrow;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w2 = 0; w2 < AW; ++w2) M = fmaxf(M, sm.m[w2][r]);
+    float L = 0.f, o[DPT];
+#pragma unroll
+    for (int x = 0; x < DPT; ++x) o[x] = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < AW; ++w2) {  // wave order (deterministic)
+      const float mw = sm.m[w2][r];
+      const float e = (mw == -INFINITY) ? 0.f : expf(mw - M);
+      L += sm.l[w2][r] * e;
+#pragma unroll
+      for (int x = 0; x < DPT; ++x) o[x] += sm.o[w2][mrow][md + x] * e;
+    }
+    if (r < nrows) {
+      if (eff == 1) {  // nothing to exchange: this workgroup saw every key
+        const int64_t idx = (int64_t)(seq * R + row0 + r) * n_heads * HD + (int64_t)head * HD + md;
+#pragma unroll
+        for (int x = 0; x < DPT; ++x) {
+          bf16_t hi, lo;
+          split_bf16((L > 0.f) ? o[x] / L : 0.f, hi, lo);
+          out[idx + x] = hi;
+          out[lo_plane + idx + x] = lo;
+        }
+      } else {  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]); device-scope write-through stores
+        float* p = partial + ((((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits + split) * (HD + 2);
+#pragma unroll
+        for (int x = 0; x < DPT; ++x) __hip_atomic_store(p + 2 + md + x, o[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((t & 15) == 0) {
+          __hip_atomic_store(p, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(p + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+  }
+  if (eff == 1) return;
+
+  // the workgroup that arrives last merges the splits of its rows (split order: deterministic)
   __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
   __syncthreads();
   if (t == 0) {
@@ -315,56 +307,70 @@ __global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __
     if (sm.last) __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
   }
   __syncthreads();
-  if (!sm.last || mr >= nrows) return;
-  {
-    const float* p = partial + (((int64_t)seq * n_heads + head) * R + row0 + mr) * n_splits * (HD + 2);
-    float M2 = -INFINITY, L2 = 0.f, o2[HD / 64];
+  if (!sm.last) return;
 #pragma unroll
-    for (int x = 0; x < HD / 64; ++x) o2[x] = 0.f;
-    for (int s2 = 0; s2 < eff; ++s2) {  // split order (deterministic)
-      const float* ps = p + (int64_t)s2 * (HD + 2);
-      const float mm = __hip_atomic_load(ps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float ll = __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      float oo[HD / 64];
+  for (int rg = 0; rg < NRG; ++rg) {
+    const int r = rg * 16 + mrow;
+    if (r >= nrows) continue;
+    const float* p = partial + (((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits * (HD + 2);
+    float M2 = -INFINITY, L2 = 0.f, o2[DPT];
 #pragma unroll
-      for (int x = 0; x < HD / 64; ++x) oo[x] = __hip_atomic_load(ps + 2 + lane + 64 * x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (mm == -INFINITY) continue;
-      const float Mn = fmaxf(M2, mm);
-      const float ws = (M2 == -INFINITY) ? 0.f : expf(M2 - Mn), wj = expf(mm - Mn);
-      L2 = L2 * ws + ll * wj;
+    for (int x = 0; x < DPT; ++x) o2[x] = 0.f;
+    for (int s0 = 0; s0 < eff; s0 += 4) {  // four splits' loads in flight at a time
+      float mm[4], ll[4], oo[4][DPT];
 #pragma unroll
-      for (int x = 0; x < HD / 64; ++x) o2[x] = o2[x] * ws + oo[x] * wj;
-      M2 = Mn;
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = s0 + j < eff;
+        const float* ps = p + (int64_t)(ok ? s0 + j : 0) * (HD + 2);
+        mm[j] = ok ? __hip_atomic_load(ps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
+        ll[j] = ok ? __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+#pragma unroll
+        for (int x = 0; x < DPT; ++x) oo[j][x] = ok ? __hip_atomic_load(ps + 2 + md + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (mm[j] == -INFINITY) continue;
+        const float Mn = fmaxf(M2, mm[j]);
+        const float ws = (M2 == -INFINITY) ? 0.f : expf(M2 - Mn), wj = expf(mm[j] - Mn);
+        L2 = L2 * ws + ll[j] * wj;
+#pragma unroll
+        for (int x = 0; x < DPT; ++x) o2[x] = o2[x] * ws + oo[j][x] * wj;
+        M2 = Mn;
+      }
     }
+    const int64_t idx = (int64_t)(seq * R + row0 + r) * n_heads * HD + (int64_t)head * HD + md;
 #pragma unroll
-    for (int x = 0; x < HD / 64; ++x) {
-      const float y = (L2 > 0.f) ? o2[x] / L2 : 0.f;
-      const int64_t idx = (int64_t)(seq * R + row0 + mr) * n_heads * HD + (int64_t)head * HD + lane + 64 * x;
+    for (int x = 0; x < DPT; ++x) {
       bf16_t hi, lo;
-      split_bf16(y, hi, lo);
-      out[idx] = hi;
-      out[lo_plane + idx] = lo;
+      split_bf16((L2 > 0.f) ? o2[x] / L2 : 0.f, hi, lo);
+      out[idx + x] = hi;
+      out[lo_plane + idx + x] = lo;
     }
   }
+}
+
+template <int HD, int NRG>
+hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvView& kv, int layer, int B, int R, int n_heads, float* partial,
+                    int n_splits, int* counters, void* out, hipStream_t s) {
+  const int n_chunks = (R + NRG * 16 - 1) / (NRG * 16);
+  const float scale = 1.0f / sqrtf((float)HD);
+  hipLaunchKernelGGL((tree_attn_mfma_kernel<HD, NRG>), dim3(n_splits, n_heads * n_chunks, B), dim3(AW * 64), 0, s, q, q_stride, rd, kv, layer,
+                     R, n_heads, n_chunks, scale, partial, n_splits, counters, (bf16_t*)out);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 // bf16 models: q float32 [B*R][q_stride], half-precision cache, output = bf16 hi / lo planes [2][B*R][n_heads*hd].
+// Passes of up to 16 rows per sequence use 16-row work items, larger ones 32-row items (K and V are read once per item).
 hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
                                  float* partial, int n_splits, int* counters, void* out, hipStream_t s) {
-  const int n_chunks = (R + ARB - 1) / ARB;
-  const float scale = 1.0f / sqrtf((float)kv.head_dim);
-  const dim3 grid(n_splits, n_heads * n_chunks, B), block(AW * 64);
-  if (kv.head_dim == 128)
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<128>), grid, block, 0, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale, partial,
-                       n_splits, counters, (bf16_t*)out);
-  else if (kv.head_dim == 64)
-    hipLaunchKernelGGL((tree_attn_mfma_kernel<64>), grid, block, 0, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale, partial,
-                       n_splits, counters, (bf16_t*)out);
-  else
-    return hipErrorInvalidValue;
-  return hipGetLastError();
+  const int hd = kv.head_dim;
+  if (hd == 128 && R <= 16) return run_mfma<128, 1>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 128) return run_mfma<128, 2>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 64 && R <= 16) return run_mfma<64, 1>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 64) return run_mfma<64, 2>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace mtad
