@@ -4,8 +4,9 @@
 // Work item = (key split, head, chunk of 16 or 32 query rows, sequence) = one workgroup of 4 waves.  The keys of the
 // item are cut into 32-key tiles dealt round-robin to the waves; every wave runs its own online softmax over its
 // tiles and the 4 waves merge through LDS at the end.  A context of up to 128 keys is one workgroup, which writes the
-// attention output itself; longer contexts use one split per 128 keys and the workgroup that arrives last merges
-// the splits in split order (same partial layout and protocol as the generic kernel).
+// attention output itself; longer contexts are cut into as many splits as fill the machine once (never below 128 keys
+// each) and the workgroup that arrives last merges the splits in split order (same partial layout and protocol as
+// the generic kernel).
 //
 // Both products run on the matrix cores, transposed, so that every operand is cheap to fetch:
 //   S^T = K Q^T   A operand = 8 consecutive dims of one key per lane = 16 contiguous bytes of a cache row, loaded from
@@ -24,7 +25,7 @@ namespace {
 
 constexpr int AW = 4;                // waves per workgroup
 constexpr int ATK = 32;              // keys per tile
-constexpr int KEYS_PER_SPLIT = 128;  // keys per workgroup when splits are available: one tile per wave
+constexpr int MIN_KEYS_PER_SPLIT = 128;  // a split is worth its exchange only with at least one 32-key tile per wave
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -59,9 +60,9 @@ __device__ __forceinline__ int token_index(const KvView& kv, int seq, int pos) {
 }
 
 template <int HD, int NRG>
-__global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
+__global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 1 ? 3 : 2))) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
                                                                int R, int n_heads, int n_chunks, float scale, float* __restrict__ partial,
-                                                               int n_splits, int* __restrict__ counters, bf16_t* __restrict__ out) {
+                                                               int n_splits, int* __restrict__ counters, bf16_t* __restrict__ out, int want_splits) {
   constexpr int KS = HD / 32;    // k-steps of the score product
   constexpr int DB = HD / 16;    // 16-dim blocks of the output
   constexpr int CH = HD / 8;     // 16-byte chunks of a cache row
@@ -83,8 +84,9 @@ __global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __
   const int nspec = max(0, min(rd.nspec[seq], 64));
   const int ktot = min(len + nspec, kv_capacity(kv));
 
-  // splits actually used for this sequence: short contexts stay in one workgroup (all workgroups agree on this)
-  const int eff = max(1, min(n_splits, (ktot + KEYS_PER_SPLIT - 1) / KEYS_PER_SPLIT));
+  // splits actually used for this sequence (all workgroups agree on this): as many as fill the machine once, but
+  // short contexts are not cut below MIN_KEYS_PER_SPLIT keys
+  const int eff = max(1, min(min(n_splits, want_splits), (ktot + MIN_KEYS_PER_SPLIT - 1) / MIN_KEYS_PER_SPLIT));
   if (split >= eff) return;
   int per = (ktot + eff - 1) / eff;
   per = ((per + ATK - 1) / ATK) * ATK;
@@ -316,10 +318,11 @@ __global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __
     float M2 = -INFINITY, L2 = 0.f, o2[DPT];
 #pragma unroll
     for (int x = 0; x < DPT; ++x) o2[x] = 0.f;
-    for (int s0 = 0; s0 < eff; s0 += 4) {  // four splits' loads in flight at a time
-      float mm[4], ll[4], oo[4][DPT];
+    constexpr int SB = 8;  // splits whose loads are in flight together
+    for (int s0 = 0; s0 < eff; s0 += SB) {
+      float mm[SB], ll[SB], oo[SB][DPT];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < SB; ++j) {
         const bool ok = s0 + j < eff;
         const float* ps = p + (int64_t)(ok ? s0 + j : 0) * (HD + 2);
         mm[j] = ok ? __hip_atomic_load(ps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
@@ -328,7 +331,7 @@ __global__ __launch_bounds__(AW * 64) void tree_attn_mfma_kernel(const float* __
         for (int x = 0; x < DPT; ++x) oo[j][x] = ok ? __hip_atomic_load(ps + 2 + md + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
       }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < SB; ++j) {
         if (mm[j] == -INFINITY) continue;
         const float Mn = fmaxf(M2, mm[j]);
         const float ws = (M2 == -INFINITY) ? 0.f : expf(M2 - Mn), wj = expf(mm[j] - Mn);
@@ -354,8 +357,17 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
                     int n_splits, int* counters, void* out, hipStream_t s) {
   const int n_chunks = (R + NRG * 16 - 1) / (NRG * 16);
   const float scale = 1.0f / sqrtf((float)HD);
-  hipLaunchKernelGGL((tree_attn_mfma_kernel<HD, NRG>), dim3(n_splits, n_heads * n_chunks, B), dim3(AW * 64), 0, s, q, q_stride, rd, kv, layer,
-                     R, n_heads, n_chunks, scale, partial, n_splits, counters, (bf16_t*)out);
+  // aim at one workgroup per compute unit: more splits cost more in the exchange than they gain (measured at 2048 keys)
+  static const int n_cus = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    return cus > 0 ? cus : 256;
+  }();
+  const int items = n_heads * n_chunks * B;
+  const int want = items >= n_cus ? 1 : (n_cus + items - 1) / items;
+  const int gx = n_splits < want ? n_splits : want;
+  hipLaunchKernelGGL((tree_attn_mfma_kernel<HD, NRG>), dim3(gx, n_heads * n_chunks, B), dim3(AW * 64), 0, s, q, q_stride, rd, kv, layer,
+                     R, n_heads, n_chunks, scale, partial, n_splits, counters, (bf16_t*)out, want);
   return hipGetLastError();
 }
 

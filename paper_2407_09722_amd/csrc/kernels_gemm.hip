@@ -21,6 +21,8 @@
 #include "gemm.h"
 #include "gemm_device.h"
 
+#include <stdlib.h>
+
 namespace mtad {
 
 // ---- packing ------------------------------------------------------------------------------------------
@@ -142,6 +144,78 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
   if (wave < NG) gemm_finish_group<NG, EPI>(a, nt, wave, red, inv_s, rows_here, lane);
 }
 
+// Several strips per workgroup, for passes of more than 8 rows.  With NG row groups a weight tile needs NG activation
+// fragments of its own size from L2; a workgroup that works on S strips at once loads the fragments of a k tile
+// once and uses them for S weight tiles, so the L2 -> compute-unit traffic per weight byte drops from 1 + NG to
+// 1 + NG/S.  Same wave layout as above with one k tile per batch and wave; the S strips are reduced and finished one
+// after the other through the same LDS buffer.  S * NG <= 12 keeps the accumulators in 48 registers.
+template <int NG, int EPI>
+__global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, int S) {
+  constexpr int SM = 12 / NG;  // most strips per workgroup
+  __shared__ floatx4 red[GW * NG * 64];
+  __shared__ float inv_s[NG * 8];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int K = a.K, KT = K >> 5, NT = a.N >> 4;
+  const int R = a.R, row0 = a.row0;
+  const int rows_here = min(NG * 8, R - row0);
+  const int c = lane & 15, kg = lane >> 4;
+  const int nt0 = blockIdx.x * S, ns = min(S, NT - nt0);
+
+  const char* strip0 = (const char*)a.W + (((size_t)nt0 * KT) << 10);
+  const size_t strip_bytes = (size_t)KT << 10;
+  const unsigned voff = (unsigned)lane * 16u;
+  const char* X = (const char*)a.X + (size_t)row0 * K * 2;
+  const unsigned xoff = (unsigned)((((size_t)(c >> 3) * R + (c & 7)) * K + kg * 8) * 2);
+
+  Frag w[2][SM], b[2][1][NG];
+  auto load_w = [&](Frag (&ws)[SM], int kt) {
+#pragma unroll
+    for (int s2 = 0; s2 < SM; ++s2)
+      if (s2 < ns && kt < KT) ws[s2].n = __builtin_nontemporal_load((const uintx4*)(strip0 + s2 * strip_bytes + ((size_t)kt << 10) + voff));
+  };
+  gemm_load_b<NG, 1>(b[0], X, xoff, K, KT, wave, rows_here, c);
+  load_w(w[0], wave);
+  gemm_load_b<NG, 1>(b[1], X, xoff, K, KT, wave + GW, rows_here, c);
+  load_w(w[1], wave + GW);
+
+  floatx4 acc[SM][NG];
+#pragma unroll
+  for (int s2 = 0; s2 < SM; ++s2)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) acc[s2][g] = floatx4{0.f, 0.f, 0.f, 0.f};
+  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
+
+  for (int kt = wave; kt < KT; kt += 2 * GW) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k0 = kt + h * GW;
+      if (k0 < KT) {
+#pragma unroll
+        for (int s2 = 0; s2 < SM; ++s2)
+          if (s2 < ns) {
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[s2][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[h][s2].v, b[h][0][g].v, acc[s2][g], 0, 0, 0);
+          }
+      }
+      if (k0 + 2 * GW < KT) {
+        gemm_load_b<NG, 1>(b[h], X, xoff, K, KT, k0 + 2 * GW, rows_here, c);
+        load_w(w[h], k0 + 2 * GW);
+      }
+    }
+  }
+#pragma unroll
+  for (int s2 = 0; s2 < SM; ++s2) {
+    if (s2 < ns) {  // uniform over the workgroup
+      if (s2 > 0) __syncthreads();  // the previous strip's sums have been read
+#pragma unroll
+      for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[s2][g];
+      __syncthreads();
+      if (wave < NG) gemm_finish_group<NG, EPI>(a, nt0 + s2, wave, red, inv_s, rows_here, lane);
+    }
+  }
+}
+
 template <int RB>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ W, const float* __restrict__ X,
                                                        float* __restrict__ Y, int R, int N, int K, int ldy,
@@ -204,6 +278,34 @@ static hipError_t run_tag(const GemmArgs& a, int tag, hipStream_t s) {
   return run_one<NG, EPI, 0>(a, s);
 }
 
+template <int NG, int EPI>
+static hipError_t run_multi(const GemmArgs& a, int S, hipStream_t s) {
+  const int NT = a.N / 16;
+  hipLaunchKernelGGL((gemm_bf16_multi_kernel<NG, EPI>), dim3((NT + S - 1) / S), dim3(GW * 64), 0, s, a, S);
+  return hipGetLastError();
+}
+
+// Strips per workgroup for a product with NT strips and NG row groups: the S <= 12/NG that needs the fewest
+// rounds of workgroups times strips per round (one workgroup per compute unit at a time), larger S on ties.
+static int strips_per_group(int NT, int NG) {
+  static const int n_cus = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    return cus > 0 ? cus : 256;
+  }();
+  if (NG < 2 || NG > 6) return 1;
+  int best = 1, best_cost = ((NT + n_cus - 1) / n_cus);
+  for (int S = 2; S <= 12 / NG; ++S) {
+    const int groups = (NT + S - 1) / S;
+    const int cost = ((groups + n_cus - 1) / n_cus) * S;
+    if (cost <= best_cost) {
+      best = S;
+      best_cost = cost;
+    }
+  }
+  return best;
+}
+
 template <int EPI>
 static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
   // at most 64 rows per launch (8 row groups); more rows re-stream the weights per 64-row slab
@@ -211,6 +313,15 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
     a.row0 = r0;
     const int ng = ((a.R - r0 < 64 ? a.R - r0 : 64) + 7) / 8;
     hipError_t e;
+    const int S = strips_per_group(a.N / 16, ng <= 4 ? ng : (ng <= 6 ? 6 : 8));
+    if (S > 1) {
+      if (ng <= 2) e = run_multi<2, EPI>(a, S, s);
+      else if (ng <= 3) e = run_multi<3, EPI>(a, S, s);
+      else if (ng <= 4) e = run_multi<4, EPI>(a, S, s);
+      else e = run_multi<6, EPI>(a, S, s);
+      if (e != hipSuccess) return e;
+      continue;
+    }
     if (ng <= 1) e = run_tag<1, EPI>(a, tag, s);
     else if (ng <= 2) e = run_tag<2, EPI>(a, tag, s);
     else if (ng <= 3) e = run_tag<3, EPI>(a, tag, s);
