@@ -49,7 +49,9 @@ def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None):
 
 @pytest.mark.parametrize("R,N,K", [(1, 16, 32), (5, 48, 1376), (5, 2304, 768), (16, 64, 4096), (17, 4096, 4096),
                                    (5, 12288, 4096), (5, 4096, 11008), (33, 80, 96), (41, 512, 2048), (100, 96, 160),
-                                   (164, 640, 5120), (200, 32, 64), (256, 1024, 1376)])
+                                   (164, 640, 5120), (200, 32, 64), (256, 1024, 1376),
+                                   # more than 8 rows and more strips than compute units: several strips per workgroup
+                                   (17, 12288, 4096), (9, 22016, 256), (30, 12304, 128), (41, 8192, 96), (24, 4112, 64)])
 def test_gemm_bf16_matches_float64(R, N, K):
     mb = _mb()
     print(f"gemm bf16 R={R} N={N} K={K}", flush=True)
