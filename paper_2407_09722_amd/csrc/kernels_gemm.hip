@@ -148,10 +148,10 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
 // fragments of its own size from L2; a workgroup that works on S strips at once loads the fragments of a k tile
 // once and uses them for S weight tiles, so the L2 -> compute-unit traffic per weight byte drops from 1 + NG to
 // 1 + NG/S.  Same wave layout as above with one k tile per batch and wave; the S strips are reduced and finished one
-// after the other through the same LDS buffer.  S * NG <= 12 keeps the accumulators in 48 registers.
+// after the other through the same LDS buffer.  S * NG <= 12 (16 for 48 and 64 rows) bounds the accumulator registers.
 template <int NG, int EPI>
 __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, int S) {
-  constexpr int SM = 12 / NG;  // most strips per workgroup
+  constexpr int SM = NG <= 4 ? 12 / NG : 2;  // most strips per workgroup
   __shared__ floatx4 red[GW * NG * 64];
   __shared__ float inv_s[NG * 8];
   const int lane = threadIdx.x & 63;
@@ -285,19 +285,21 @@ static hipError_t run_multi(const GemmArgs& a, int S, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Strips per workgroup for a product with NT strips and NG row groups: the S <= 12/NG that needs the fewest
-// rounds of workgroups times strips per round (one workgroup per compute unit at a time), larger S on ties.
+// Strips per workgroup for a product with NT strips and NG row groups.  Cost model (fits the measured times at 17, 41
+// and 64 rows): the busiest compute unit works on rounds * S strips, and a strip costs in proportion to the bytes
+// that reach the compute unit per weight byte, 1 + NG/S; so minimise rounds * (S + NG), larger S on ties.
 static int strips_per_group(int NT, int NG) {
   static const int n_cus = [] {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
     return cus > 0 ? cus : 256;
   }();
-  if (NG < 2 || NG > 6) return 1;
-  int best = 1, best_cost = ((NT + n_cus - 1) / n_cus);
-  for (int S = 2; S <= 12 / NG; ++S) {
+  if (NG < 2) return 1;
+  const int smax = NG <= 4 ? 12 / NG : 2;
+  int best = 1, best_cost = 0x7fffffff;
+  for (int S = 1; S <= smax; ++S) {
     const int groups = (NT + S - 1) / S;
-    const int cost = ((groups + n_cus - 1) / n_cus) * S;
+    const int cost = ((groups + n_cus - 1) / n_cus) * (S + NG);
     if (cost <= best_cost) {
       best = S;
       best_cost = cost;
@@ -318,7 +320,8 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
       if (ng <= 2) e = run_multi<2, EPI>(a, S, s);
       else if (ng <= 3) e = run_multi<3, EPI>(a, S, s);
       else if (ng <= 4) e = run_multi<4, EPI>(a, S, s);
-      else e = run_multi<6, EPI>(a, S, s);
+      else if (ng <= 6) e = run_multi<6, EPI>(a, S, s);
+      else e = run_multi<8, EPI>(a, S, s);
       if (e != hipSuccess) return e;
       continue;
     }
