@@ -191,7 +191,7 @@ __device__ __forceinline__ void list_pop(TopList& L) {
   L.idx[MAXB - 1] = 0x7FFFFFFF;
 }
 
-// block-wide argmax of (key, idx) over 256 threads, ties to the lowest idx; result to every thread
+// block-wide argmax of (key, idx) over up to 1024 threads (shk, shi: 16 entries), ties to the lowest idx; result to every thread
 __device__ __forceinline__ void block_best(float& k, int& i, float* shk, int* shi) {
   for (int off = 32; off > 0; off >>= 1) {
     const float ok = __shfl_xor(k, off, 64);
@@ -202,7 +202,8 @@ __device__ __forceinline__ void block_best(float& k, int& i, float* shk, int* sh
   if ((threadIdx.x & 63) == 0) { shk[threadIdx.x >> 6] = k; shi[threadIdx.x >> 6] = i; }
   __syncthreads();
   k = shk[0]; i = shi[0];
-  for (int w = 1; w < 4; ++w)
+  const int nw = (int)blockDim.x >> 6;
+  for (int w = 1; w < nw; ++w)
     if (better(shk[w], shi[w], k, i)) { k = shk[w]; i = shi[w]; }
 }
 
@@ -386,13 +387,13 @@ hipError_t launch_gather_logp(const float* logits, const float* lse, TreeView tr
 
 // ---- joint-likelihood acceptance and bonus token -----------------------------------------------------------
 
-__global__ __launch_bounds__(256) void accept_kernel(TreeView tree, const float* __restrict__ logp_cond, const float* __restrict__ logits,
+__global__ __launch_bounds__(1024) void accept_kernel(TreeView tree, const float* __restrict__ logp_cond, const float* __restrict__ logits,
                                                      int V, const int32_t* __restrict__ len, float log_tau, int mode, int gamma,
                                                      int sample, uint64_t seed, AcceptView out) {
   __shared__ float joint[MTAD_MAX_ROWS];
   __shared__ int sel[2];  // eta, node
-  __shared__ float shk[4];
-  __shared__ int shi[4];
+  __shared__ float shk[16];
+  __shared__ int shi[16];
   const int s = blockIdx.x, M = tree.M;
   const int32_t* par = tree.parent + (int64_t)s * M;
   const int32_t* dep = tree.depth + (int64_t)s * M;
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(256) void accept_kernel(TreeView tree, const float*
   const uint64_t nk = noise_key(seed, s * STREAMS_PER_SEQ + STREAM_BONUS, len[s] + 1 + eta);
   float bk = -INFINITY;
   int bi = 0x7FFFFFFF;
-  for (int v = threadIdx.x; v < V; v += 256) {
+  for (int v = threadIdx.x; v < V; v += (int)blockDim.x) {
     float k = row[v];
     if (sample) k += gumbel(nk, (uint64_t)v);
     if (better(k, v, bk, bi)) { bk = k; bi = v; }
@@ -449,7 +450,7 @@ __global__ __launch_bounds__(256) void accept_kernel(TreeView tree, const float*
 
 hipError_t launch_accept(TreeView tree, const float* logp_cond, const float* logits, int V, const int32_t* len, float log_tau, int mode,
                          int B, int gamma, int sample, uint64_t seed, AcceptView out, hipStream_t s) {
-  hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(256), 0, s, tree, logp_cond, logits, V, len, log_tau, mode, gamma, sample, seed, out);
+  hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(1024), 0, s, tree, logp_cond, logits, V, len, log_tau, mode, gamma, sample, seed, out);
   return hipGetLastError();
 }
 

@@ -46,14 +46,29 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
   const T* e = E + (int64_t)t * d;
   const int64_t lo_plane = (int64_t)gridDim.x * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    float v;
-    if constexpr (sizeof(T) == 2) v = bf16_to_f32(e[i]);
-    else v = e[i];
-    h[(int64_t)row * d + i] = v;
+  for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {  // d is a multiple of 4 (checked at create)
+    float v[4];
+    if constexpr (sizeof(T) == 2) {
+      const ushort4 b = *(const ushort4*)(e + i);
+      v[0] = bf16_to_f32(b.x); v[1] = bf16_to_f32(b.y); v[2] = bf16_to_f32(b.z); v[3] = bf16_to_f32(b.w);
+    } else {
+      const float4 f = *(const float4*)(e + i);
+      v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+    }
+    *(float4*)(h + (int64_t)row * d + i) = make_float4(v[0], v[1], v[2], v[3]);
     if (planes) {
-      ss += v * v;
-      split_bf16(v * g0[i], planes[(int64_t)row * d + i], planes[lo_plane + (int64_t)row * d + i]);
+      const float4 g = *(const float4*)(g0 + i);
+      ushort4 hi, lo;
+      split_bf16(v[0] * g.x, hi.x, lo.x);
+      split_bf16(v[1] * g.y, hi.y, lo.y);
+      split_bf16(v[2] * g.z, hi.z, lo.z);
+      split_bf16(v[3] * g.w, hi.w, lo.w);
+      ss += v[0] * v[0];
+      ss += v[1] * v[1];
+      ss += v[2] * v[2];
+      ss += v[3] * v[3];
+      *(ushort4*)(planes + (int64_t)row * d + i) = hi;
+      *(ushort4*)(planes + lo_plane + (int64_t)row * d + i) = lo;
     }
   }
   if (planes) {
