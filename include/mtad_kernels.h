@@ -18,9 +18,8 @@ extern "C" {
  * MTAD_PACK_PLAIN); X two bfloat16 planes [2][R][K]
  * (hi, lo) whose sum is the activation; float32 accumulation (N % 16 == 0, K % 32 == 0, R <= 256);
  * dtype 0: W, X float32 (K % 4 == 0).  Y float32 [R][ldy], ldy >= N, ldy % 4 == 0.
- * accumulate != 0 adds to Y (the residual connection).  ctx may be NULL; with a context whose bound workspace is
- * large enough for the shape (it is for the context's own model shapes) the reduction dimension is also split
- * over workgroups, as in the passes. */
+ * accumulate != 0 adds to Y (the residual connection).  ctx may be NULL (the kernel needs no workspace); this is the
+ * product kernel of the passes with its plain store epilogue. */
 int mtad_k_gemm(mtad_ctx *ctx, int32_t dtype, const void *W, const void *X, float *Y, int32_t R, int32_t N, int32_t K, int32_t ldy,
                 int32_t accumulate, void *stream);
 

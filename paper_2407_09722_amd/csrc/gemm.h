@@ -12,8 +12,6 @@ struct GemmArgs {
   const bf16_t* X;   // two bf16 planes [2][R][K]: activation = hi + lo
   int R, N, K;
   int row0;          // first row handled by this launch (set by the launcher; 64 rows per launch)
-  float* part;       // split-k partial sums (gemm_part_floats), or null = no k split
-  int* counters;     // zeroed ints, one per 16-strip group; left zeroed
   // rows are multiplied by 1/sqrt(sum_p ssq[m][p] / K + eps) when ssq != null (fused RMSNorm of the input)
   const float* ssq;
   int NP;
@@ -40,8 +38,6 @@ struct GemmArgs {
 };
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s);
-size_t gemm_part_floats(int N, int K);   // floats of split-k workspace one product needs
-inline int gemm_groups(int N) { return (N / 16 + 3) / 4; }  // counters needed (smallest workgroup shape)
 hipError_t launch_gemm_f32(const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate, hipStream_t s);
 hipError_t launch_pack_matrix(const void* src, void* dst, int N, int K, int kind, int head_dim, hipStream_t s);
 

@@ -261,8 +261,6 @@ hipError_t launch_gemm_f32(const void* W, const void* X, float* Y, int R, int N,
   return hipGetLastError();
 }
 
-size_t gemm_part_floats(int, int) { return 0; }  // no cross-workgroup reduction in this kernel
-
 template <int NG, int EPI, int TAG>
 static hipError_t run_one(const GemmArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((gemm_bf16_kernel<NG, EPI, TAG>), dim3(a.N / 16), dim3(GW * 64), 0, s, a);

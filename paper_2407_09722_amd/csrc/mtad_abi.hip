@@ -25,18 +25,15 @@ struct mtad_ctx {
   // workspace carve-up
   float *h, *qkv, *gu, *dlogits, *lse, *partial, *part_key, *ssq, *lse_part;
   void *xn, *xg;  // xn: attention output / FFN activation; xg: h*gain planes feeding the next normalised product
-  int *attn_cnt, *gemm_cnt;
+  int* attn_cnt;
   size_t attn_cnt_n;
-  float* gemm_part;
   float2* rope;
   int* part_idx;
   RowDesc rd;
   uint32_t* status;
-  int gemm_groups;
   unsigned long long* bar;  // grid barrier counter + abort flag of the persistent pass kernel
   int n_cus;                // compute units of the device (workgroups of the persistent kernel)
   int persistent;           // use the persistent pass kernel where it applies
-  size_t gemm_part_cap;
   // persistent pass: device copies of the step lists of (up to) two models, the host copies they were made from,
   // and the device copy of the arguments of the pass being launched
   PassStep* steps_dev[2];
@@ -108,22 +105,6 @@ void carve(mtad_ctx* c, char* base) {
   c->lse_part = k.take<float>(rows * (size_t)(imax(t.vocab, d.vocab) / 16 + 1) * 2);
   c->attn_cnt_n = (size_t)c->cfg.batch * imax(t.n_heads, d.n_heads) * (size_t)((c->Rmax + 7) / 8);
   c->attn_cnt = k.take<int>(c->attn_cnt_n);
-  size_t pf = 0;
-  int groups = 0;
-  for (const mtad_model* m : {&t, &d}) {
-    const int hh = m->n_heads * m->head_dim, qk = (m->n_heads + 2 * m->n_kv_heads) * m->head_dim;
-    const int shapes[5][2] = {{qk, m->d_model}, {m->d_model, hh}, {2 * m->d_ffn, m->d_model}, {m->d_model, m->d_ffn}, {m->vocab, m->d_model}};
-    for (auto& sh : shapes) {
-      if (m->dtype != 1) continue;
-      const size_t need = gemm_part_floats(sh[0], sh[1]);
-      if (need > pf) pf = need;
-      if (gemm_groups(sh[0]) > groups) groups = gemm_groups(sh[0]);
-    }
-  }
-  c->gemm_part = k.take<float>(pf + 64);
-  c->gemm_part_cap = pf;
-  c->gemm_groups = groups + 1;
-  c->gemm_cnt = k.take<int>((size_t)c->gemm_groups);
   c->bar = k.take<unsigned long long>(32);
   for (int i = 0; i < 2; ++i) c->steps_dev[i] = k.take<PassStep>(pass_steps(PASS_MAX_LAYERS, true));
   c->pass_args = k.take<PassArgs>(1);
@@ -277,8 +258,6 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     memset(&a, 0, sizeof(a));
     a.R = rows;
     a.eps = m->rms_eps;
-    a.part = c->gemm_part;
-    a.counters = c->gemm_cnt;
     // qkv
     a.W = (const bf16_t*)L[1]; a.X = (const bf16_t*)c->xg; a.N = qkvw; a.K = d;
     a.ssq = c->ssq; a.NP = np;
@@ -323,7 +302,6 @@ int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* ls
     a.W = (const bf16_t*)W[tail + 1]; a.X = (const bf16_t*)c->xg; a.R = rows; a.N = m->vocab; a.K = m->d_model;
     a.ssq = c->ssq; a.NP = m->d_model / 16; a.eps = m->rms_eps;
     a.Y = logits; a.ldy = m->vocab; a.lse_part = c->lse_part;
-    a.part = c->gemm_part; a.counters = c->gemm_cnt;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_STORE, same_shape(m, &c->tshape) ? 1 : 0, s));
     HIP_TRY(c, launch_lse_finish(c->lse_part, lse, rows, m->vocab / 16, s));
     return MTAD_OK;
@@ -408,7 +386,6 @@ int mtad_bind_workspace(mtad_ctx* c, void* buf, size_t bytes) {
     c->n_cus = cus;
   }
   hipError_t e = hipMemset(c->status, 0, 256);
-  if (e == hipSuccess) e = hipMemset(c->gemm_cnt, 0, sizeof(int) * (size_t)c->gemm_groups);
   if (e == hipSuccess) e = hipMemset(c->attn_cnt, 0, sizeof(int) * c->attn_cnt_n);
   if (e != hipSuccess) {
     c->last_hip = (int)e;
@@ -557,10 +534,7 @@ int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float*
   memset(&a, 0, sizeof(a));
   a.W = (const bf16_t*)W; a.X = (const bf16_t*)X; a.R = R; a.N = N; a.K = K;
   a.Y = Y; a.ldy = ldy; a.accumulate = accumulate != 0;
-  if (c && c->ws && gemm_part_floats(N, K) <= c->gemm_part_cap && gemm_groups(N) <= c->gemm_groups) {  // k split needs the workspace
-    a.part = c->gemm_part;
-    a.counters = c->gemm_cnt;
-  }
+  (void)c;  // no workspace needed by the current kernels
   return launch_gemm_bf16(a, EPI_STORE, 2, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
 }
 
