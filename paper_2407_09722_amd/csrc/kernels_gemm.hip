@@ -120,7 +120,6 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
   floatx4 acc[NG];
 #pragma unroll
   for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
 
   for (int kt = wave; kt < KT; kt += 2 * span) {
 #pragma unroll
@@ -140,6 +139,7 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
   }
 #pragma unroll
   for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[g];
+  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);  // after the stream: its loads are L2 hits by now for most workgroups
   __syncthreads();
   if (wave < NG) gemm_finish_group<NG, EPI>(a, nt, wave, red, inv_s, rows_here, lane);
 }
@@ -184,7 +184,6 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
   for (int s2 = 0; s2 < SM; ++s2)
 #pragma unroll
     for (int g = 0; g < NG; ++g) acc[s2][g] = floatx4{0.f, 0.f, 0.f, 0.f};
-  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
 
   for (int kt = wave; kt < KT; kt += 2 * GW) {
 #pragma unroll
@@ -204,6 +203,7 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
       }
     }
   }
+  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);  // after the stream (see the single-strip kernel)
 #pragma unroll
   for (int s2 = 0; s2 < SM; ++s2) {
     if (s2 < ns) {  // uniform over the workgroup
