@@ -1,12 +1,13 @@
 // Tree-masked paged attention for bf16 models (half-precision K/V cache), few query rows per sequence
 // (Section 3.3: tree attention gives every tree token its conditional likelihood in one pass).
 //
-// Work item = (key split, head, chunk of 16 or 32 query rows, sequence) = one workgroup of 4 waves.  The keys of the
-// item are cut into 32-key tiles dealt round-robin to the waves; every wave runs its own online softmax over its
-// tiles and the 4 waves merge through LDS at the end.  A context of up to 128 keys is one workgroup, which writes the
-// attention output itself; longer contexts are cut into as many splits as fill the machine once (never below 128 keys
-// each) and the workgroup that arrives last merges the splits in split order (same partial layout and protocol as
-// the generic kernel).
+// Work item = (key split, head, chunk of 16 or 32 query rows, sequence) = one workgroup of 8 (16-row items) or 4
+// (32-row items) waves.  The keys of the item are cut into 32-key tiles dealt round-robin to the waves; every wave
+// runs its own online softmax over its tiles, with the K and V of two tiles in flight, and the waves merge through
+// LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup, which writes the attention output
+// itself: no exchange through global memory.  Longer contexts are cut into splits (at least one tile per wave each, at
+// most as many as fill the machine once) and the workgroup that arrives last merges the splits in split order (same
+// partial layout and protocol as the generic kernel).
 //
 // Both products run on the matrix cores, transposed, so that every operand is cheap to fetch:
 //   S^T = K Q^T   A operand = 8 consecutive dims of one key per lane = 16 contiguous bytes of a cache row, loaded from
@@ -23,9 +24,7 @@ namespace mtad {
 
 namespace {
 
-constexpr int AW = 4;                // waves per workgroup
 constexpr int ATK = 32;              // keys per tile
-constexpr int MIN_KEYS_PER_SPLIT = 128;  // a split is worth its exchange only with at least one 32-key tile per wave
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -35,7 +34,7 @@ union KFrag {
   half8 h;
 };
 
-template <int HD, int NRG>
+template <int HD, int NRG, int AW>
 struct MfmaAttnSmem {
   static constexpr int VS = HD + 8;  // padded row of halves: 16-byte aligned, keys 4 apart land 16 banks apart
   union {
@@ -59,8 +58,8 @@ __device__ __forceinline__ int token_index(const KvView& kv, int seq, int pos) {
   return page * kv.page_size + pos % kv.page_size;
 }
 
-template <int HD, int NRG>
-__global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 1 ? 3 : 2))) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
+template <int HD, int NRG, int AW>
+__global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(HD == 128 && NRG == 2 ? 1 : 2))) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
                                                                int R, int n_heads, int n_chunks, float scale, float* __restrict__ partial,
                                                                int n_splits, int* __restrict__ counters, bf16_t* __restrict__ out, int want_splits) {
   constexpr int KS = HD / 32;    // k-steps of the score product
@@ -69,10 +68,11 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
   constexpr int KPL = 64 / CH;   // keys one V load instruction covers
   constexpr int NV = ATK / KPL;  // V load instructions per tile
   constexpr int RBK = NRG * 16;  // query rows per work item
-  constexpr int DPT = HD / 16;   // output dims per thread in the merge (16 threads per row)
-  using Smem = MfmaAttnSmem<HD, NRG>;
-  constexpr int VS = Smem::VS;
-  __shared__ Smem sm;
+  constexpr int TPR = AW * 4;    // threads per query row in the merge (16 rows per pass)
+  constexpr int DPT = HD / TPR;  // output dims per thread in the merge
+  using Smem = MfmaAttnSmem<HD, NRG, AW>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];  // dynamic: the 8-wave variant needs more than 64 KiB
+  Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -84,9 +84,9 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
   const int nspec = max(0, min(rd.nspec[seq], 64));
   const int ktot = min(len + nspec, kv_capacity(kv));
 
-  // splits actually used for this sequence (all workgroups agree on this): as many as fill the machine once, but
-  // short contexts are not cut below MIN_KEYS_PER_SPLIT keys
-  const int eff = max(1, min(min(n_splits, want_splits), (ktot + MIN_KEYS_PER_SPLIT - 1) / MIN_KEYS_PER_SPLIT));
+  // splits actually used for this sequence (all workgroups agree on this): as many as fill the machine once, but a
+  // split is worth its exchange only if it gives every wave a tile (measured at 512 and 2048 keys)
+  const int eff = max(1, min(min(n_splits, want_splits), ktot / (AW * ATK)));
   if (split >= eff) return;
   int per = (ktot + eff - 1) / eff;
   per = ((per + ATK - 1) / ATK) * ATK;
@@ -107,27 +107,30 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
   const kv16_t* kbase = (const kv16_t*)kv.k + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
   const kv16_t* vbase = (const kv16_t*)kv.v + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
 
-  // first tile's K and V are requested before the queries are staged
-  int tok_cur = lookup(wave);
-  KFrag kf[2][KS], vf[NV];
-  auto load_kv = [&](int tok32) {
+  // K and V of the wave's first two tiles are requested before the queries are staged
+  KFrag kf[2][2][KS], vf[2][NV];
+  auto load_kv = [&](KFrag (&kfs)[2][KS], KFrag (&vfs)[NV], int tok32) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
       const int tk = __shfl(tok32, blk * 16 + srow, 64);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        kf[blk][ks].u = make_uint4(0, 0, 0, 0);
-        if (tk >= 0) kf[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
+        kfs[blk][ks].u = make_uint4(0, 0, 0, 0);
+        if (tk >= 0) kfs[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
       }
     }
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int tk = __shfl(tok32, j * KPL + lane / CH, 64);
-      vf[j].u = make_uint4(0, 0, 0, 0);  // keys past the end contribute exact zeros
-      if (tk >= 0) vf[j].u = *(const uint4*)(vbase + (int64_t)tk * tok_stride + (lane % CH) * 8);
+      vfs[j].u = make_uint4(0, 0, 0, 0);  // keys past the end contribute exact zeros
+      if (tk >= 0) vfs[j].u = *(const uint4*)(vbase + (int64_t)tk * tok_stride + (lane % CH) * 8);
     }
   };
-  if (wave < n_tiles) load_kv(tok_cur);
+  {
+    const int tok0 = lookup(wave), tok1 = lookup(wave + AW);
+    if (wave < n_tiles) load_kv(kf[0], vf[0], tok0);
+    if (wave + AW < n_tiles) load_kv(kf[1], vf[1], tok1);
+  }
 
   // queries of the item as half hi / lo terms in LDS (rows beyond the item are zero)
   for (int i = t; i < RBK * (HD / 4); i += AW * 64) {
@@ -154,10 +157,10 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
     for (int db = 0; db < DB; ++db) acc[rg][db] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  for (int ti = wave; ti < n_tiles; ti += AW) {
+  auto process = [&](const KFrag (&kfs)[2][KS], const KFrag (&vfs)[NV], int ti) {
     // V tile -> wave-private LDS copy
 #pragma unroll
-    for (int j = 0; j < NV; ++j) *(uint4*)&sm.a.v[wave][j * KPL + lane / CH][(lane % CH) * 8] = vf[j].u;
+    for (int j = 0; j < NV; ++j) *(uint4*)&sm.a.v[wave][j * KPL + lane / CH][(lane % CH) * 8] = vfs[j].u;
 
     // S^T = K Q^T: lane (sg4, srow) gets keys blk*16 + sg4*4 + i of row rg*16 + srow
     floatx4 s2[NRG][2];
@@ -173,20 +176,13 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
         const half8 ql = *(const half8*)&sm.a.q[1][rg * 16 + srow][ks * 32 + sg4 * 8];
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, qh, s2[rg][blk], 0, 0, 0);
-          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, ql, s2[rg][blk], 0, 0, 0);
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfs[blk][ks].h, qh, s2[rg][blk], 0, 0, 0);
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfs[blk][ks].h, ql, s2[rg][blk], 0, 0, 0);
         }
       }
-    // the next tile's K and V can go now: their registers are free
-    const bool more = ti + AW < n_tiles;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the V tile is in LDS (the wave reads what other lanes wrote)
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    int tok_next = -1;
-    if (more) {
-      tok_next = lookup(ti + AW);
-      load_kv(tok_next);
-    }
 
     // visibility, scale, running softmax per row; probabilities become the B operand of the second product
     half8 ph[NRG], pl[NRG];
@@ -241,11 +237,19 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the V tile has been read before the next one overwrites it
-    tok_cur = tok_next;
+  };
+  // two register sets: while a tile is worked on, the other tile's loads (and then this set's reload) are in flight
+  for (int ti = wave; ti < n_tiles; ti += 2 * AW) {
+    process(kf[0], vf[0], ti);
+    if (ti + 2 * AW < n_tiles) load_kv(kf[0], vf[0], lookup(ti + 2 * AW));
+    if (ti + AW < n_tiles) {
+      process(kf[1], vf[1], ti + AW);
+      if (ti + 3 * AW < n_tiles) load_kv(kf[1], vf[1], lookup(ti + 3 * AW));
+    }
   }
 
-  // ---- the 4 waves meet in LDS, one row group at a time (the buffer aliases the V tiles and the queries)
-  const int mrow = t >> 4, md = (t & 15) * DPT;  // merge role: row within the group, first of DPT dims
+  // ---- the waves meet in LDS, one row group at a time (the buffer aliases the V tiles and the queries)
+  const int mrow = t / TPR, md = (t % TPR) * DPT;  // merge role: row within the group, first of DPT dims
   const int64_t lo_plane = (int64_t)B * R * n_heads * HD;
 #pragma unroll
   for (int rg = 0; rg < NRG; ++rg) {
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
         float* p = partial + ((((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits + split) * (HD + 2);
 #pragma unroll
         for (int x = 0; x < DPT; ++x) __hip_atomic_store(p + 2 + md + x, o[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((t & 15) == 0) {
+        if (t % TPR == 0) {
           __hip_atomic_store(p, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           __hip_atomic_store(p + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
@@ -352,11 +356,16 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(NRG == 
   }
 }
 
-template <int HD, int NRG>
+template <int HD, int NRG, int AW>
 hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvView& kv, int layer, int B, int R, int n_heads, float* partial,
                     int n_splits, int* counters, void* out, hipStream_t s) {
   const int n_chunks = (R + NRG * 16 - 1) / (NRG * 16);
   const float scale = 1.0f / sqrtf((float)HD);
+  auto kern = tree_attn_mfma_kernel<HD, NRG, AW>;
+  constexpr size_t lds = sizeof(MfmaAttnSmem<HD, NRG, AW>);
+  static const hipError_t attr = lds > 64 * 1024 ? hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                                                 : hipSuccess;
+  if (attr != hipSuccess) return attr;
   // aim at one workgroup per compute unit: more splits cost more in the exchange than they gain (measured at 2048 keys)
   static const int n_cus = [] {
     int dev = 0, cus = 0;
@@ -366,22 +375,23 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
   const int items = n_heads * n_chunks * B;
   const int want = items >= n_cus ? 1 : (n_cus + items - 1) / items;
   const int gx = n_splits < want ? n_splits : want;
-  hipLaunchKernelGGL((tree_attn_mfma_kernel<HD, NRG>), dim3(gx, n_heads * n_chunks, B), dim3(AW * 64), 0, s, q, q_stride, rd, kv, layer,
-                     R, n_heads, n_chunks, scale, partial, n_splits, counters, (bf16_t*)out, want);
+  hipLaunchKernelGGL(kern, dim3(gx, n_heads * n_chunks, B), dim3(AW * 64), lds, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale,
+                     partial, n_splits, counters, (bf16_t*)out, want);
   return hipGetLastError();
 }
 
 }  // namespace
 
 // bf16 models: q float32 [B*R][q_stride], half-precision cache, output = bf16 hi / lo planes [2][B*R][n_heads*hd].
-// Passes of up to 16 rows per sequence use 16-row work items, larger ones 32-row items (K and V are read once per item).
+// Passes of up to 16 rows per sequence use 16-row work items of 8 waves, larger ones 32-row items of 4 waves (K and V
+// are read once per item).
 hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
                                  float* partial, int n_splits, int* counters, void* out, hipStream_t s) {
   const int hd = kv.head_dim;
-  if (hd == 128 && R <= 16) return run_mfma<128, 1>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
-  if (hd == 128) return run_mfma<128, 2>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
-  if (hd == 64 && R <= 16) return run_mfma<64, 1>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
-  if (hd == 64) return run_mfma<64, 2>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 128 && R <= 16) return run_mfma<128, 1, 8>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 128) return run_mfma<128, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 64 && R <= 16) return run_mfma<64, 1, 8>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 64) return run_mfma<64, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   return hipErrorInvalidValue;
 }
 
