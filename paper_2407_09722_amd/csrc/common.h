@@ -88,14 +88,12 @@ struct RowDesc {
 };
 
 // ---- launchers (kernels_*.hip) ----------------------------------------------------------------
-// h = E[tok]; bf16 models also get the first RMSNorm's input: planes [2][rows][d] of h*g0 and ssq[rows] = sum h^2
+// h = E[tok]; bf16 models also get the first RMSNorm's input: planes [2][rows][d] of h*g0 and ssq[rows] = sum h^2;
+// and the rotary table of the rows' positions, table[rows][head_dim/2] = (cos, sin)
 hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, const float* g0,
-                        void* planes, float* ssq, hipStream_t s);
+                        void* planes, float* ssq, const int32_t* pos, float2* table, int head_dim, float theta, hipStream_t s);
 // out = rmsnorm(h) * g, written as hi/lo bf16 planes [2][rows][d] (dtype 1) or f32 [rows][d] (dtype 0)
 hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s);
-// also zeroes the two words at `zero2` when given (the persistent pass kernel's barrier counter and abort flag)
-hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s,
-                             unsigned long long* zero2);
 // rotate q (in place in qkv, float32), rotate k and write k, v to the cache in its storage type
 hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
                           int n_heads, uint32_t* status, hipStream_t s);
@@ -109,6 +107,9 @@ hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd
                                  float* partial, int n_splits, int* counters, void* out, hipStream_t s);
 // lse[row] from per-strip (max, sum exp) partials [rows][NP]
 hipError_t launch_lse_finish(const float* lse_part, float* lse, int rows, int NP, hipStream_t s);
+// lse as above for B*M rows, plus logp_cond[s][c] = logits[s][parent(c)][tok(c)] - lse[s][parent(c)] (0 for c = 0)
+hipError_t launch_lse_gather(const float* lse_part, float* lse, int B, int M, int NP, const float* logits, int V, const int32_t* parent,
+                             const int32_t* tok, float* logp_cond, hipStream_t s);
 hipError_t launch_silu_mul(int dtype, const float* gu, void* act, int rows, int f, hipStream_t s);
 hipError_t launch_copy(const void* src, void* dst, int64_t bytes, hipStream_t s);
 hipError_t launch_row_lse(const float* logits, float* lse, int rows, int vocab, hipStream_t s);

@@ -34,13 +34,23 @@ __device__ __forceinline__ float block_max(float v, float* sh) {
   return t;
 }
 
-// h[row] = E[tok[row]]; bf16 models: also planes of h*g0 (input of the first fused RMSNorm) and ssq[row] = sum h^2
+// The inputs of a pass, one workgroup per row: h[row] = E[tok[row]]; bf16 models: also planes of h*g0 (input of the
+// first fused RMSNorm) and ssq[row] = sum h^2; and the row's rotary table, table[row][i] = (cos, sin)(pos[row] *
+// theta^(-2i/head_dim)), evaluated in double so that positions in the thousands keep float32-exact angles.
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ h, int d,
                                                     int vocab, const float* __restrict__ g0, bf16_t* __restrict__ planes,
-                                                    float* __restrict__ ssq) {
+                                                    float* __restrict__ ssq, const int32_t* __restrict__ pos, float2* __restrict__ table,
+                                                    int half, float theta) {
   __shared__ float sh[4];
   const int row = blockIdx.x;
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    const double inv_freq = pow((double)theta, -(double)i / (double)half);
+    const double ang = (double)pos[row] * inv_freq;
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    table[(int64_t)row * half + i] = make_float2((float)cs, (float)sn);
+  }
   int t = tok[row];
   if (t < 0 || t >= vocab) t = 0;  // inactive rows carry no meaningful token
   const T* e = E + (int64_t)t * d;
@@ -78,12 +88,14 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
 }
 
 hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, const float* g0,
-                        void* planes, float* ssq, hipStream_t s) {
+                        void* planes, float* ssq, const int32_t* pos, float2* table, int head_dim, float theta, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (dtype == 1)
-    hipLaunchKernelGGL((embed_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t*)E, tok, h, d, vocab, g0, (bf16_t*)planes, ssq);
+    hipLaunchKernelGGL((embed_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t*)E, tok, h, d, vocab, g0, (bf16_t*)planes, ssq, pos,
+                       table, head_dim / 2, theta);
   else
-    hipLaunchKernelGGL((embed_kernel<float>), dim3(rows), dim3(256), 0, s, (const float*)E, tok, h, d, vocab, nullptr, nullptr, nullptr);
+    hipLaunchKernelGGL((embed_kernel<float>), dim3(rows), dim3(256), 0, s, (const float*)E, tok, h, d, vocab, nullptr, nullptr, nullptr, pos,
+                       table, head_dim / 2, theta);
   return hipGetLastError();
 }
 
@@ -125,29 +137,6 @@ hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, 
   if (d % 4) return hipErrorInvalidValue;
   if (dtype == 1) hipLaunchKernelGGL((rmsnorm_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, h, g, (bf16_t*)out, d, eps);
   else hipLaunchKernelGGL((rmsnorm_kernel<float>), dim3(rows), dim3(256), 0, s, h, g, (float*)out, d, eps);
-  return hipGetLastError();
-}
-
-// table[row][i] = (cos, sin)(pos[row] * theta^(-2i/head_dim)), evaluated in double so that positions in
-// the thousands keep float32-exact angles
-__global__ void rope_table_kernel(const int32_t* __restrict__ pos, float2* __restrict__ table, int rows, int half, float theta,
-                                  unsigned long long* zero2) {
-  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (zero2 && idx < 2) zero2[idx] = 0ull;
-  if (idx >= rows * half) return;
-  const int row = idx / half, i = idx % half;
-  const double inv_freq = pow((double)theta, -(double)i / (double)half);
-  const double ang = (double)pos[row] * inv_freq;
-  double sn, cs;
-  sincos(ang, &sn, &cs);
-  table[idx] = make_float2((float)cs, (float)sn);
-}
-
-hipError_t launch_rope_table(const int32_t* pos, float2* table, int rows, int head_dim, float theta, hipStream_t s,
-                             unsigned long long* zero2) {
-  if (rows <= 0) return hipSuccess;
-  const int half = head_dim / 2, n = rows * half;
-  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, s, pos, table, rows, half, theta, zero2);
   return hipGetLastError();
 }
 
@@ -245,6 +234,45 @@ __global__ __launch_bounds__(256) void lse_finish_kernel(const float2* __restric
   for (int i = threadIdx.x; i < NP; i += 256) sum += p[i].y * expf(p[i].x - m);
   sum = block_sum(sum, sh);
   if (threadIdx.x == 0) lse[blockIdx.x] = m + logf(sum);
+}
+
+// The same, fused with the gather of the tree nodes' conditional log-likelihoods: workgroup (sequence s, row c) writes
+// lse[s][c] and, for c > 0, logp_cond[s][c] = logits[s][parent(c)][tok(c)] - lse[s][parent(c)], reducing the
+// parent row's partials itself (same code, same order: the value equals the one the parent's workgroup writes).
+__device__ __forceinline__ float lse_of_row(const float2* __restrict__ p, int NP, float* sh) {
+  float m = -INFINITY;
+  for (int i = threadIdx.x; i < NP; i += 256) m = fmaxf(m, p[i].x);
+  m = block_max(m, sh);
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < NP; i += 256) sum += p[i].y * expf(p[i].x - m);
+  sum = block_sum(sum, sh);
+  return m + logf(sum);
+}
+
+__global__ __launch_bounds__(256) void lse_gather_kernel(const float2* __restrict__ part, float* __restrict__ lse, int NP,
+                                                         const float* __restrict__ logits, int M, int V, const int32_t* __restrict__ parent,
+                                                         const int32_t* __restrict__ tok, float* __restrict__ logp_cond) {
+  __shared__ float sh[4];
+  const int idx = blockIdx.x, s = idx / M, c = idx % M;
+  const float own = lse_of_row(part + (int64_t)idx * NP, NP, sh);
+  if (threadIdx.x == 0) lse[idx] = own;
+  float out = 0.f;
+  if (c > 0) {  // uniform over the workgroup
+    const int p = parent[idx], t = tok[idx];
+    if (p >= 0 && p < M && t >= 0 && t < V) {
+      __syncthreads();  // sh is reused
+      const float lp = lse_of_row(part + ((int64_t)s * M + p) * NP, NP, sh);
+      out = logits[((int64_t)s * M + p) * V + t] - lp;
+    }
+  }
+  if (threadIdx.x == 0) logp_cond[idx] = out;
+}
+
+hipError_t launch_lse_gather(const float* lse_part, float* lse, int B, int M, int NP, const float* logits, int V, const int32_t* parent,
+                             const int32_t* tok, float* logp_cond, hipStream_t s) {
+  if (B * M <= 0) return hipSuccess;
+  hipLaunchKernelGGL(lse_gather_kernel, dim3(B * M), dim3(256), 0, s, (const float2*)lse_part, lse, NP, logits, M, V, parent, tok, logp_cond);
+  return hipGetLastError();
 }
 
 hipError_t launch_lse_finish(const float* lse_part, float* lse, int rows, int NP, hipStream_t s) {

@@ -40,6 +40,9 @@ struct mtad_ctx {
   PassStep steps_host[2][pass_steps(PASS_MAX_LAYERS, true)];
   int steps_n[2];
   int steps_evict;
+  // set by mtad_verify_tree around its pass: the logsumexp kernel of a bf16 pass then also gathers logp_cond
+  const mtad_tree* gather_tree;
+  float* gather_out;
   PassArgs* pass_args;
   bf16_t* pass_act;  // per-layer activation planes of the persistent pass
   int pass_rows;     // rows those planes are sized for
@@ -174,6 +177,19 @@ int same_shape(const mtad_model* a, const mtad_model* b) {
 
 int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* lse, hipStream_t s);
 
+// Row logsumexp from the per-strip partials the lm_head product left; inside mtad_verify_tree the same kernel also
+// gathers the tree nodes' conditional log-likelihoods.
+int finish_lse(mtad_ctx* c, const mtad_model* m, int rows, const float* logits, float* lse, hipStream_t s) {
+  if (c->gather_out && c->gather_tree) {
+    const mtad_tree* t = c->gather_tree;
+    HIP_TRY(c, launch_lse_gather(c->lse_part, lse, rows / t->M, t->M, m->vocab / 16, logits, m->vocab, t->parent, t->tok, c->gather_out, s));
+    c->gather_out = nullptr;  // done: the caller skips its separate gather
+    return MTAD_OK;
+  }
+  HIP_TRY(c, launch_lse_finish(c->lse_part, lse, rows, m->vocab / 16, s));
+  return MTAD_OK;
+}
+
 // The decoder pass over B*R rows described by ctx->rd.  float32 models: hidden states end in ctx->h.
 // bf16 models: additionally ctx->xg holds the planes of h*g_final and ctx->ssq the per-strip sums of squares,
 // ready for the lm_head product.
@@ -184,8 +200,7 @@ int decoder_pass_f32(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R,
   const KvView kvv = view_of(kv, m);
   const int n_splits = splits_for(c, m, R);
   const void* const* W = m->weights;
-  HIP_TRY(c, launch_embed(0, W[0], c->rd.tok, c->h, rows, d, m->vocab, nullptr, nullptr, nullptr, s));
-  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s, nullptr));
+  HIP_TRY(c, launch_embed(0, W[0], c->rd.tok, c->h, rows, d, m->vocab, nullptr, nullptr, nullptr, c->rd.pos, c->rope, hd, m->rope_theta, s));
   for (int l = 0; l < m->n_layers; ++l) {
     const void* const* L = W + 1 + 6 * l;
     HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)L[0], c->xn, rows, d, m->rms_eps, s));
@@ -217,8 +232,8 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
   const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
-  HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, s));
-  HIP_TRY(c, launch_rope_table(c->rd.pos, c->rope, rows, hd, m->rope_theta, s, nullptr));
+  HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, c->rd.pos, c->rope, hd, m->rope_theta,
+                          s));
   if (persistent) {  // every layer (and the lm_head) in one launch
     // step list of this model: built on the host, uploaded when it differs from both cached lists
     PassStep built[pass_steps(PASS_MAX_LAYERS, true)];
@@ -248,7 +263,7 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     p.prof = c->prof;
 #endif
     HIP_TRY(c, launch_pass(p, c->pass_args, c->n_cus, s));
-    if (logits) HIP_TRY(c, launch_lse_finish(c->lse_part, lse, rows, m->vocab / 16, s));
+    if (logits) return finish_lse(c, m, rows, logits, lse, s);
     return MTAD_OK;
   }
   int np = 1;  // partial sums of squares per row currently in ctx->ssq
@@ -303,8 +318,7 @@ int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* ls
     a.ssq = c->ssq; a.NP = m->d_model / 16; a.eps = m->rms_eps;
     a.Y = logits; a.ldy = m->vocab; a.lse_part = c->lse_part;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_STORE, same_shape(m, &c->tshape) ? 1 : 0, s));
-    HIP_TRY(c, launch_lse_finish(c->lse_part, lse, rows, m->vocab / 16, s));
-    return MTAD_OK;
+    return finish_lse(c, m, rows, logits, lse, s);
   }
   HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)W[tail], c->xn, rows, m->d_model, m->rms_eps, s));
   HIP_TRY(c, launch_gemm_f32(W[tail + 1], c->xn, logits, rows, m->vocab, m->d_model, m->vocab, false, s));
@@ -471,9 +485,14 @@ int mtad_verify_tree(mtad_ctx* c, const mtad_model* target, mtad_kv* tkv, const 
   hipStream_t s = (hipStream_t)stream;
   const int B = c->cfg.batch, M = tree->M;
   HIP_TRY(c, launch_verify_rows(c->rd, tkv->len, root_tok, tview(tree), B, tkv->page_size * tkv->max_pages, c->status, s));
+  c->gather_tree = tree;
+  c->gather_out = logp_cond;
   int rc = decoder_pass(c, target, tkv, M, s, logits, row_lse);
+  const bool gathered = c->gather_out == nullptr;
+  c->gather_tree = nullptr;
+  c->gather_out = nullptr;
   if (rc) return rc;
-  HIP_TRY(c, launch_gather_logp(logits, row_lse, tview(tree), B, target->vocab, logp_cond, s));
+  if (!gathered) HIP_TRY(c, launch_gather_logp(logits, row_lse, tview(tree), B, target->vocab, logp_cond, s));
   return MTAD_OK;
 }
 
