@@ -1,8 +1,8 @@
 // Tree-masked paged attention for bf16 models (half-precision K/V cache), few query rows per sequence
 // (Section 3.3: tree attention gives every tree token its conditional likelihood in one pass).
 //
-// Work item = (key split, head, chunk of 16 or 32 query rows, sequence) = one workgroup of 8 (16-row items) or 4
-// (32-row items) waves.  The keys of the item are cut into 32-key tiles dealt round-robin to the waves; every wave
+// Work item = (key split, head, chunk of 16 or 32 query rows, sequence) = one workgroup of AW waves (4 in both
+// configurations used; 8 measured no faster).  The keys of the item are cut into 32-key tiles dealt round-robin to the waves; every wave
 // runs its own online softmax over its tiles, with the K and V of two tiles in flight, and the waves merge through
 // LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup, which writes the attention output
 // itself: no exchange through global memory.  Longer contexts are cut into splits (at least one tile per wave each, at
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(HD == 1
   constexpr int TPR = AW * 4;    // threads per query row in the merge (16 rows per pass)
   constexpr int DPT = HD / TPR;  // output dims per thread in the merge
   using Smem = MfmaAttnSmem<HD, NRG, AW>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];  // dynamic: the 8-wave variant needs more than 64 KiB
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];  // dynamic: an 8-wave variant needs more than 64 KiB
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
 
   const int t = threadIdx.x, lane = t & 63;
@@ -383,14 +383,13 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
 }  // namespace
 
 // bf16 models: q float32 [B*R][q_stride], half-precision cache, output = bf16 hi / lo planes [2][B*R][n_heads*hd].
-// Passes of up to 16 rows per sequence use 16-row work items of 8 waves, larger ones 32-row items of 4 waves (K and V
-// are read once per item).
+// Passes of up to 16 rows per sequence use 16-row work items, larger ones 32-row items (K and V are read once per item).
 hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
                                  float* partial, int n_splits, int* counters, void* out, hipStream_t s) {
   const int hd = kv.head_dim;
-  if (hd == 128 && R <= 16) return run_mfma<128, 1, 8>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 128 && R <= 16) return run_mfma<128, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (hd == 128) return run_mfma<128, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
-  if (hd == 64 && R <= 16) return run_mfma<64, 1, 8>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 64 && R <= 16) return run_mfma<64, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (hd == 64) return run_mfma<64, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   return hipErrorInvalidValue;
 }
