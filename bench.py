@@ -154,15 +154,17 @@ def main():
     gemm_ms = ev[0].elapsed_time(ev[1]) / (reps * len(launches))
     bytes_per_launch = gemm_bytes / len(launches)
     achieved = bytes_per_launch / gemm_ms / 1e6
-    traffic = None
+    traffic, traffic_detail = None, None
     tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "c3_gemm_hbm_traffic.txt")
     if w.name == "C3" and os.path.exists(tfile):       # per-launch HBM bytes from the committed rocprofv3 counter runs
         kv = dict(l.strip().split("=", 1) for l in open(tfile) if "=" in l and not l.startswith("#"))
-        traffic = {"fetch_bytes_per_launch": int(float(kv["fetch_bytes_per_launch"])),
-                   "write_bytes_per_launch": int(float(kv["write_bytes_per_launch"])), "source": "profiles/c3_gemm_hbm_counters.md"}
+        traffic_detail = {"fetch_bytes_per_launch": int(float(kv["fetch_bytes_per_launch"])),
+                          "write_bytes_per_launch": int(float(kv["write_bytes_per_launch"])),
+                          "source": "profiles/c3_gemm_hbm_counters.md (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel)"}
+        traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]   # HBM bytes per launch
     roofline = {"kernel": "gemm_bf16_kernel (skinny weight-streaming GEMM, all target matrices)" if dt_id else "gemm_f32_kernel",
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_detail": traffic_detail,
                 "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(gemm_ms * 1e3, 3),
                 "launches_per_verify": len(launches)}
 
