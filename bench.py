@@ -105,6 +105,29 @@ def main():
     dt0, tokens0, _ = timed_region(0.0)                  # tau = 0 passes every prefix: gamma+1 tokens per iteration
     status |= mb.mtad_device_status(eng.ctx)
 
+    # --- the same K iterations replayed from a HIP graph of one iteration (extra figure; `value` stays the eager loop) ----
+    graph_info = None
+    try:
+        eng.prefill(prompt)
+        for _ in range(W):
+            eng.iteration(tau, seed=w.seed)
+        torch.cuda.synchronize()
+        g = eng.capture_iteration(tau, seed=w.seed)
+        g.replay()
+        torch.cuda.synchronize()
+        len0 = eng.tkv.len.clone()
+        t = time.perf_counter()
+        for _ in range(K):
+            g.replay()
+        torch.cuda.synchronize()
+        dtg = time.perf_counter() - t
+        tok_g = int((eng.tkv.len - len0).sum().item())
+        graph_info = {"ms_per_step": round(dtg / K * 1e3, 4), "tokens_per_s": round(tok_g / dtg, 2)}
+        del g
+    except Exception as e:                                  # reported, never fatal: the eager loop is the measurement
+        graph_info = {"error": str(e)[:200]}
+    status |= mb.mtad_device_status(eng.ctx)
+
     # --- verify step alone, HIP events on the launch stream --------------------------------------------------
     eng.prefill(prompt)
     eng.draft_phase(seed=w.seed)
@@ -231,7 +254,7 @@ def main():
                                "block-efficiency table): a labelled projection, not a measurement"},
         "tau0": {"tokens_per_s": round(tokens0 / dt0, 2), "tokens_per_iteration": round(tokens0 / K / w.batch, 3),
                  "ms_per_step": round(dt0 / K * 1e3, 4)},
-        "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
+        "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
         "device_status": status, "weights_setup_s": round(t_weights, 1),
     }
     print(json.dumps(out))

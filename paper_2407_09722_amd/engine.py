@@ -182,6 +182,20 @@ class Engine:
         self.accept_phase(tau, sample_bonus, seed, stream)
         self.commit_phase(stream)
 
+    def capture_iteration(self, tau, sample_beam=False, sample_bonus=True, seed=0):
+        """Records one iteration as a HIP graph and returns it (`graph.replay()` = one iteration on the current
+        stream).  Everything that changes from one iteration to the next (lengths, root and catch-up tokens,
+        beam history, the positions that key the random numbers) lives in device memory, and the calls allocate
+        nothing, synchronise nothing and record no memset, so the same graph serves every iteration.  tau, seed and
+        the two sampling switches are baked in.  Not for the persistent pass (its first launch uploads a step list)."""
+        side = torch.cuda.Stream(device=self.device)
+        side.wait_stream(torch.cuda.current_stream(self.device))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            self.iteration(tau, sample_beam, sample_bonus, seed, stream=side)
+        torch.cuda.current_stream(self.device).wait_stream(side)
+        return graph
+
     def emitted(self):
         """Host copy of the tokens the last iteration produced, per sequence."""
         cnt = self.out_cnt.cpu().numpy()

@@ -7,6 +7,7 @@ import synth_inputs as si
 from tests._parity import run_pair
 
 pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
 
 
 def _weights(shape, seed, role, boost=None):
@@ -95,3 +96,38 @@ def test_workload_c2_shape_short_run():
                   seed=w.seed)
     assert st["iters"] >= 5
     print(f"C2: {st['iters']} iterations, excused {st['excused']}, max logit err {st['max_logit_err']:.2e}")
+
+
+def test_graph_replay_matches_eager_iterations():
+    """One iteration captured as a HIP graph and replayed, with eager work and synchronisations between the replays, commits
+    the same tokens as the same iterations launched eagerly (all per-iteration state lives on the device)."""
+    import torch
+    from paper_2407_09722_amd.engine import DeviceModel, Engine
+    from paper_2407_09722_amd import binding as mb
+    ts, ds = si.ModelShape(2, 128, 4, 2, 64, 352, 1024, "bf16"), si.ModelShape(1, 64, 1, 1, 64, 160, 1024, "bf16")
+    wt, wd = si.make_weights(ts, 21, "target"), si.make_weights(ds, 21, "draft")
+    prompt = np.random.default_rng(3).integers(0, 1024, (2, 23)).astype(np.int32)
+    tm, dm = DeviceModel(ts, wt, DEV), DeviceModel(ds, wd, DEV)
+    n_iter = 7
+    for mode, tau in (("mtad", 0.0), ("mmtad", 0.3)):
+        print(f"graph replay {mode} tau={tau}", flush=True)
+        eager = Engine(tm, dm, batch=2, gamma=3, beam=3, mode=mode, max_context=128, device=DEV, persistent=False)
+        eager.prefill(prompt)
+        want = []
+        for _ in range(n_iter):
+            eager.iteration(tau, sample_beam=True, seed=9)
+            want.append((eager.emitted(), eager.tkv.len.cpu().tolist(), eager.dkv.len.cpu().tolist()))
+        rep = Engine(tm, dm, batch=2, gamma=3, beam=3, mode=mode, max_context=128, device=DEV, persistent=False)
+        rep.prefill(prompt)
+        torch.cuda.synchronize()
+        graph = rep.capture_iteration(tau, sample_beam=True, seed=9)
+        scratch = torch.zeros(1 << 16, device=DEV)
+        for i in range(n_iter):
+            graph.replay()
+            scratch.add_(1.0)                       # eager work between the replays
+            torch.cuda.synchronize()
+            got = (rep.emitted(), rep.tkv.len.cpu().tolist(), rep.dkv.len.cpu().tolist())
+            assert got == want[i], f"{mode}: replay {i} differs from the eager iteration"
+        assert mb.mtad_device_status(rep.ctx) == 0
+        eager.close()
+        rep.close()
