@@ -151,7 +151,7 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
 // after the other through the same LDS buffer.  S * NG <= 12 (16 for 48 and 64 rows) bounds the accumulator registers.
 template <int NG, int EPI>
 __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, int S) {
-  constexpr int SM = NG <= 4 ? 12 / NG : 2;  // most strips per workgroup
+  constexpr int SM = NG <= 4 ? 12 / NG : (NG <= 6 ? 3 : 4);  // most strips per workgroup
   __shared__ floatx4 red[GW * NG * 64];
   __shared__ float inv_s[NG * 8];
   const int lane = threadIdx.x & 63;
@@ -293,7 +293,7 @@ static int strips_per_group(int NT, int NG) {
     return cus > 0 ? cus : 256;
   }();
   if (NG < 2) return 1;
-  const int smax = NG <= 4 ? 12 / NG : 2;
+  const int smax = NG <= 4 ? 12 / NG : (NG <= 6 ? 3 : 4);
   int best = 1, best_cost = 0x7fffffff;
   for (int S = 1; S <= smax; ++S) {
     const int groups = (NT + S - 1) / S;
