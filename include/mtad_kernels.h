@@ -18,8 +18,10 @@ extern "C" {
  * MTAD_PACK_PLAIN); X two bfloat16 planes [2][R][K]
  * (hi, lo) whose sum is the activation; float32 accumulation (N % 16 == 0, K % 32 == 0, R <= 256);
  * dtype 0: W, X float32 (K % 4 == 0).  Y float32 [R][ldy], ldy >= N, ldy % 4 == 0.
- * accumulate != 0 adds to Y (the residual connection).  ctx may be NULL (the kernel needs no workspace); this is the
- * product kernel of the passes with its plain store epilogue. */
+ * accumulate != 0 adds to Y (the residual connection).  This is the product kernel of the passes with its plain store
+ * epilogue.  ctx may be NULL; with a context whose bound workspace covers the shape (it does for the context's own
+ * model shapes) products with few output strips and more than 8 rows also split the reduction dimension over
+ * workgroups, as in the passes. */
 int mtad_k_gemm(mtad_ctx *ctx, int32_t dtype, const void *W, const void *X, float *Y, int32_t R, int32_t N, int32_t K, int32_t ldy,
                 int32_t accumulate, void *stream);
 

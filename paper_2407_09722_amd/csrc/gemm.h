@@ -35,9 +35,16 @@ struct GemmArgs {
   KvView kv;
   int layer, Rseq, n_heads;
   uint32_t* status;
+  // k split across workgroups (products with few strips and more than 8 rows): partial sums [group][strip][row group][split]
+  // of 256 floats, and one zeroed counter per group (left zeroed); null = no split
+  float* part;
+  int* counters;
 };
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s);
+// workspace a context should offer for the k split of a product with N outputs (0 if it would never be split)
+size_t gemm_split_floats(int N);
+int gemm_split_counters(int N);
 hipError_t launch_gemm_f32(const void* W, const void* X, float* Y, int R, int N, int K, int ldy, bool accumulate, hipStream_t s);
 hipError_t launch_pack_matrix(const void* src, void* dst, int N, int K, int kind, int head_dim, hipStream_t s);
 

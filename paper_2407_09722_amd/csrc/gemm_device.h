@@ -133,17 +133,36 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int nt, floatx4
     }
 }
 
-// Sum of the NWAVES partial sums of row group g (in wave order), hi + lo fold, epilogue.  Called by wave g < NG after
-// the partial sums are in `red` ([wave][g][lane]) and a workgroup barrier.
-template <int NG, int EPI, bool COH = false, int NWAVES = GW>
-__device__ __forceinline__ void gemm_finish_group(const GemmArgs& a, int nt, int g, const floatx4* red, const float* inv_s,
-                                                  int rows_here, int lane) {
-  const int c = lane & 15, kg = lane >> 4;
+// Sum of the NWAVES partial sums of row group g (in wave order).  Called by wave g < NG after the partial sums are in
+// `red` ([wave][g][lane]) and a workgroup barrier.
+template <int NG, int NWAVES = GW>
+__device__ __forceinline__ floatx4 gemm_sum_waves(int g, const floatx4* red, int lane) {
   floatx4 s = red[g * 64 + lane];
   for (int w2 = 1; w2 < NWAVES; ++w2) {
     const floatx4 t2 = red[(w2 * NG + g) * 64 + lane];
     s[0] += t2[0]; s[1] += t2[1]; s[2] += t2[2]; s[3] += t2[3];
   }
+  return s;
+}
+
+// hi + lo fold of a row group's sums, then the epilogue.
+template <int EPI, bool COH = false>
+__device__ __forceinline__ void gemm_finish_sum(const GemmArgs& a, int nt, int g, floatx4 s, const float* inv_s, int rows_here, int lane) {
+  const int c = lane & 15, kg = lane >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) s[i] += __shfl_xor(s[i], 8, 64);  // columns c and c + 8 are the hi and lo terms of one row
+  const int mrel = g * 8 + (c & 7);
+  const bool live = c < 8 && mrel < rows_here;
+  const float inv = (a.ssq && live) ? inv_s[mrel] : 1.0f;
+  gemm_epilogue<EPI, COH>(a, nt, s, a.row0 + mrel, live, inv, kg);
+}
+
+// Both steps for a workgroup that holds a strip's whole reduction dimension.
+template <int NG, int EPI, bool COH = false, int NWAVES = GW>
+__device__ __forceinline__ void gemm_finish_group(const GemmArgs& a, int nt, int g, const floatx4* red, const float* inv_s,
+                                                  int rows_here, int lane) {
+  const int c = lane & 15, kg = lane >> 4;
+  floatx4 s = gemm_sum_waves<NG, NWAVES>(g, red, lane);
 #pragma unroll
   for (int i = 0; i < 4; ++i) s[i] += __shfl_xor(s[i], 8, 64);  // columns c and c + 8 are the hi and lo terms of one row
   const int mrel = g * 8 + (c & 7);

@@ -148,22 +148,30 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
 // fragments of its own size from L2; a workgroup that works on S strips at once loads the fragments of a k tile
 // once and uses them for S weight tiles, so the L2 -> compute-unit traffic per weight byte drops from 1 + NG to
 // 1 + NG/S.  Same wave layout as above with one k tile per batch and wave; the S strips are reduced and finished one
-// after the other through the same LDS buffer.  S * NG <= 12 (16 for 48 and 64 rows) bounds the accumulator registers.
+// after the other through the same LDS buffer.  A product with about one strip per compute unit or fewer would leave
+// most units idle at S > 1: its reduction dimension is then also cut into KS ranges (grid.y); every workgroup leaves
+// its sums in global memory (device-scope write-through stores) and the one that arrives last for a group of strips
+// adds the KS partial sums in range order and runs the epilogues (deterministic, same protocol as the attention splits).  S * NG <= 12 (16 for 48 and 64 rows) bounds the accumulator registers.
 template <int NG, int EPI>
 __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, int S) {
+  __shared__ int last_s;
   constexpr int SM = NG <= 4 ? 12 / NG : (NG <= 6 ? 3 : 4);  // most strips per workgroup
   __shared__ floatx4 red[GW * NG * 64];
   __shared__ float inv_s[NG * 8];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int K = a.K, KT = K >> 5, NT = a.N >> 4;
+  const int K = a.K, KT_all = K >> 5, NT = a.N >> 4;
   const int R = a.R, row0 = a.row0;
   const int rows_here = min(NG * 8, R - row0);
   const int c = lane & 15, kg = lane >> 4;
   const int nt0 = blockIdx.x * S, ns = min(S, NT - nt0);
+  // this workgroup's range of k tiles [k_lo, KT)
+  const int KS = gridDim.y, ks = blockIdx.y;
+  const int per = (KT_all + KS - 1) / KS;
+  const int k_lo = ks * per, KT = min(KT_all, k_lo + per);
 
-  const char* strip0 = (const char*)a.W + (((size_t)nt0 * KT) << 10);
-  const size_t strip_bytes = (size_t)KT << 10;
+  const char* strip0 = (const char*)a.W + (((size_t)nt0 * KT_all) << 10);
+  const size_t strip_bytes = (size_t)KT_all << 10;
   const unsigned voff = (unsigned)lane * 16u;
   const char* X = (const char*)a.X + (size_t)row0 * K * 2;
   const unsigned xoff = (unsigned)((((size_t)(c >> 3) * R + (c & 7)) * K + kg * 8) * 2);
@@ -174,10 +182,10 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
     for (int s2 = 0; s2 < SM; ++s2)
       if (s2 < ns && kt < KT) ws[s2].n = __builtin_nontemporal_load((const uintx4*)(strip0 + s2 * strip_bytes + ((size_t)kt << 10) + voff));
   };
-  gemm_load_b<NG, 1>(b[0], X, xoff, K, KT, wave, rows_here, c);
-  load_w(w[0], wave);
-  gemm_load_b<NG, 1>(b[1], X, xoff, K, KT, wave + GW, rows_here, c);
-  load_w(w[1], wave + GW);
+  gemm_load_b<NG, 1>(b[0], X, xoff, K, KT, k_lo + wave, rows_here, c);
+  load_w(w[0], k_lo + wave);
+  gemm_load_b<NG, 1>(b[1], X, xoff, K, KT, k_lo + wave + GW, rows_here, c);
+  load_w(w[1], k_lo + wave + GW);
 
   floatx4 acc[SM][NG];
 #pragma unroll
@@ -185,7 +193,7 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
 #pragma unroll
     for (int g = 0; g < NG; ++g) acc[s2][g] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  for (int kt = wave; kt < KT; kt += 2 * GW) {
+  for (int kt = k_lo + wave; kt < KT; kt += 2 * GW) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int k0 = kt + h * GW;
@@ -204,6 +212,8 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
     }
   }
   gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);  // after the stream (see the single-strip kernel)
+  // partial sums of (group, strip s2, row group g, range ks): 64 lanes x 4 floats
+  float* const mypart = a.part ? a.part + ((((size_t)blockIdx.x * SM) * NG) * KS) * 256 : nullptr;
 #pragma unroll
   for (int s2 = 0; s2 < SM; ++s2) {
     if (s2 < ns) {  // uniform over the workgroup
@@ -211,7 +221,39 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
 #pragma unroll
       for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[s2][g];
       __syncthreads();
-      if (wave < NG) gemm_finish_group<NG, EPI>(a, nt0 + s2, wave, red, inv_s, rows_here, lane);
+      if (wave < NG) {
+        const floatx4 sum = gemm_sum_waves<NG>(wave, red, lane);
+        if (KS == 1) {
+          gemm_finish_sum<EPI>(a, nt0 + s2, wave, sum, inv_s, rows_here, lane);
+        } else {
+          float* p = mypart + ((((size_t)s2 * NG + wave) * KS + ks) * 64 + lane) * 4;
+          st8<true>(p, make_uint2(__float_as_uint(sum[0]), __float_as_uint(sum[1])));
+          st8<true>(p + 2, make_uint2(__float_as_uint(sum[2]), __float_as_uint(sum[3])));
+        }
+      }
+    }
+  }
+  if (KS == 1) return;
+  // the workgroup that arrives last for this group of strips adds the ranges in order and finishes
+  __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int prev = __hip_atomic_fetch_add(a.counters + blockIdx.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last_s = (prev == KS - 1);
+    if (last_s) __hip_atomic_store(a.counters + blockIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
+  }
+  __syncthreads();
+  if (!last_s || wave >= NG) return;
+#pragma unroll
+  for (int s2 = 0; s2 < SM; ++s2) {
+    if (s2 < ns) {
+      const float* p = mypart + ((((size_t)s2 * NG + wave) * KS) * 64 + lane) * 4;
+      floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+      for (int k2 = 0; k2 < KS; ++k2) {
+        const uint4 v = ld16<true>(p + (size_t)k2 * 256);
+        sum[0] += __uint_as_float(v.x); sum[1] += __uint_as_float(v.y); sum[2] += __uint_as_float(v.z); sum[3] += __uint_as_float(v.w);
+      }
+      gemm_finish_sum<EPI>(a, nt0 + s2, wave, sum, inv_s, rows_here, lane);
     }
   }
 }
@@ -277,21 +319,36 @@ static hipError_t run_tag(const GemmArgs& a, int tag, hipStream_t s) {
 }
 
 template <int NG, int EPI>
-static hipError_t run_multi(const GemmArgs& a, int S, hipStream_t s) {
+static hipError_t run_multi(const GemmArgs& a, int S, int KS, hipStream_t s) {
   const int NT = a.N / 16;
-  hipLaunchKernelGGL((gemm_bf16_multi_kernel<NG, EPI>), dim3((NT + S - 1) / S), dim3(GW * 64), 0, s, a, S);
+  hipLaunchKernelGGL((gemm_bf16_multi_kernel<NG, EPI>), dim3((NT + S - 1) / S, KS), dim3(GW * 64), 0, s, a, S);
   return hipGetLastError();
 }
 
-// Strips per workgroup for a product with NT strips and NG row groups.  Cost model (fits the measured times at 17, 41
-// and 64 rows): the busiest compute unit works on rounds * S strips, and a strip costs in proportion to the bytes
-// that reach the compute unit per weight byte, 1 + NG/S; so minimise rounds * (S + NG), larger S on ties.
-static int strips_per_group(int NT, int NG) {
+static int device_cus() {
   static const int n_cus = [] {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
     return cus > 0 ? cus : 256;
   }();
+  return n_cus;
+}
+
+// Products with at most SPLIT_MAX_STRIPS strips (about one per compute unit) take 4 strips per workgroup and cut the
+// reduction dimension 4 ways when a workspace is offered; the workspace is sized for that.
+constexpr int SPLIT_MAX_STRIPS = 384, SPLIT_S = 4, SPLIT_KS = 4, SPLIT_NG_MAX = 8;
+size_t gemm_split_floats(int N) {
+  const int NT = N / 16;
+  if (NT > SPLIT_MAX_STRIPS) return 0;
+  return (size_t)((NT + SPLIT_S - 1) / SPLIT_S) * SPLIT_S * SPLIT_NG_MAX * SPLIT_KS * 256;
+}
+int gemm_split_counters(int N) { return N / 16 > SPLIT_MAX_STRIPS ? 0 : (N / 16 + 1) / 2; }  // groups of at least 2 strips
+
+// Strips per workgroup for a product with NT strips and NG row groups.  Cost model (fits the measured times at 17, 41
+// and 64 rows): the busiest compute unit works on rounds * S strips, and a strip costs in proportion to the bytes
+// that reach the compute unit per weight byte, 1 + NG/S; so minimise rounds * (S + NG), larger S on ties.
+static int strips_per_group(int NT, int NG) {
+  const int n_cus = device_cus();
   if (NG < 2) return 1;
   const int smax = NG <= 4 ? 12 / NG : (NG <= 6 ? 3 : 4);
   int best = 1, best_cost = 0x7fffffff;
@@ -313,13 +370,20 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
     a.row0 = r0;
     const int ng = ((a.R - r0 < 64 ? a.R - r0 : 64) + 7) / 8;
     hipError_t e;
-    const int S = strips_per_group(a.N / 16, ng <= 4 ? ng : (ng <= 6 ? 6 : 8));
+    const int ngt = ng <= 4 ? ng : (ng <= 6 ? 6 : 8);
+    int S = strips_per_group(a.N / 16, ngt), KS = 1;
+    const int smax = ngt <= 4 ? 12 / ngt : (ngt <= 6 ? 3 : 4);
+    // worth its exchange when every wave keeps at least 8 k tiles, or with 64 rows (measured at 17, 41 and 64 rows)
+    if (ng >= 2 && a.part && a.counters && a.N / 16 <= SPLIT_MAX_STRIPS && ((a.K >> 5) >= SPLIT_KS * GW * 8 || (ng >= 7 && (a.K >> 5) >= SPLIT_KS * GW * 2))) {
+      S = smax < SPLIT_S ? smax : SPLIT_S;  // share the fragments between strips, keep every compute unit busy by cutting k
+      KS = SPLIT_KS;
+    }
     if (S > 1) {
-      if (ng <= 2) e = run_multi<2, EPI>(a, S, s);
-      else if (ng <= 3) e = run_multi<3, EPI>(a, S, s);
-      else if (ng <= 4) e = run_multi<4, EPI>(a, S, s);
-      else if (ng <= 6) e = run_multi<6, EPI>(a, S, s);
-      else e = run_multi<8, EPI>(a, S, s);
+      if (ng <= 2) e = run_multi<2, EPI>(a, S, KS, s);
+      else if (ng <= 3) e = run_multi<3, EPI>(a, S, KS, s);
+      else if (ng <= 4) e = run_multi<4, EPI>(a, S, KS, s);
+      else if (ng <= 6) e = run_multi<6, EPI>(a, S, KS, s);
+      else e = run_multi<8, EPI>(a, S, KS, s);
       if (e != hipSuccess) return e;
       continue;
     }

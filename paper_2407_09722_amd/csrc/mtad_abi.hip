@@ -26,6 +26,9 @@ struct mtad_ctx {
   float *h, *qkv, *gu, *dlogits, *lse, *partial, *part_key, *ssq, *lse_part;
   void *xn, *xg;  // xn: attention output / FFN activation; xg: h*gain planes feeding the next normalised product
   int* attn_cnt;
+  float* gemm_part;  // k-split partial sums of the product kernel (products with few strips, more than 8 rows)
+  int* gemm_cnt;
+  int gemm_cnt_n;
   size_t attn_cnt_n;
   float2* rope;
   int* part_idx;
@@ -108,6 +111,21 @@ void carve(mtad_ctx* c, char* base) {
   c->lse_part = k.take<float>(rows * (size_t)(imax(t.vocab, d.vocab) / 16 + 1) * 2);
   c->attn_cnt_n = (size_t)c->cfg.batch * imax(t.n_heads, d.n_heads) * (size_t)((c->Rmax + 7) / 8);
   c->attn_cnt = k.take<int>(c->attn_cnt_n);
+  {
+    size_t pf = 0;
+    int pc = 0;
+    for (const mtad_model* m : {&t, &d}) {
+      if (m->dtype != 1) continue;
+      const int hh = m->n_heads * m->head_dim, qk = (m->n_heads + 2 * m->n_kv_heads) * m->head_dim;
+      for (int N : {qk, m->d_model, 2 * m->d_ffn, m->vocab, hh}) {
+        if (gemm_split_floats(N) > pf) pf = gemm_split_floats(N);
+        if (gemm_split_counters(N) > pc) pc = gemm_split_counters(N);
+      }
+    }
+    c->gemm_part = k.take<float>(pf + 64);
+    c->gemm_cnt_n = pc + 1;
+    c->gemm_cnt = k.take<int>((size_t)c->gemm_cnt_n);
+  }
   c->bar = k.take<unsigned long long>(32);
   for (int i = 0; i < 2; ++i) c->steps_dev[i] = k.take<PassStep>(pass_steps(PASS_MAX_LAYERS, true));
   c->pass_args = k.take<PassArgs>(1);
@@ -273,6 +291,8 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     memset(&a, 0, sizeof(a));
     a.R = rows;
     a.eps = m->rms_eps;
+    a.part = c->gemm_part;
+    a.counters = c->gemm_cnt;
     // qkv
     a.W = (const bf16_t*)L[1]; a.X = (const bf16_t*)c->xg; a.N = qkvw; a.K = d;
     a.ssq = c->ssq; a.NP = np;
@@ -317,6 +337,7 @@ int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* ls
     a.W = (const bf16_t*)W[tail + 1]; a.X = (const bf16_t*)c->xg; a.R = rows; a.N = m->vocab; a.K = m->d_model;
     a.ssq = c->ssq; a.NP = m->d_model / 16; a.eps = m->rms_eps;
     a.Y = logits; a.ldy = m->vocab; a.lse_part = c->lse_part;
+    a.part = c->gemm_part; a.counters = c->gemm_cnt;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_STORE, same_shape(m, &c->tshape) ? 1 : 0, s));
     return finish_lse(c, m, rows, logits, lse, s);
   }
@@ -401,6 +422,7 @@ int mtad_bind_workspace(mtad_ctx* c, void* buf, size_t bytes) {
   }
   hipError_t e = hipMemset(c->status, 0, 256);
   if (e == hipSuccess) e = hipMemset(c->attn_cnt, 0, sizeof(int) * c->attn_cnt_n);
+  if (e == hipSuccess) e = hipMemset(c->gemm_cnt, 0, sizeof(int) * (size_t)c->gemm_cnt_n);
   if (e != hipSuccess) {
     c->last_hip = (int)e;
     return MTAD_EHIP;
@@ -542,6 +564,16 @@ int mtad_set_persistent(mtad_ctx* c, int32_t on) {
   return MTAD_OK;
 }
 
+static size_t gemm_split_floats_cap(const mtad_ctx* c) {
+  size_t pf = 0;
+  for (const mtad_model* m : {&c->tshape, &c->dshape}) {
+    if (m->dtype != 1) continue;
+    for (int N : {(m->n_heads + 2 * m->n_kv_heads) * m->head_dim, m->d_model, 2 * m->d_ffn, m->vocab, m->n_heads * m->head_dim})
+      if (gemm_split_floats(N) > pf) pf = gemm_split_floats(N);
+  }
+  return pf;
+}
+
 int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float* Y, int32_t R, int32_t N, int32_t K, int32_t ldy, int32_t accumulate,
                 void* stream) {
   if (!W || !X || !Y || R < 1 || N < 1 || K < 1 || ldy < N) return MTAD_EINVAL;
@@ -553,7 +585,10 @@ int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float*
   memset(&a, 0, sizeof(a));
   a.W = (const bf16_t*)W; a.X = (const bf16_t*)X; a.R = R; a.N = N; a.K = K;
   a.Y = Y; a.ldy = ldy; a.accumulate = accumulate != 0;
-  (void)c;  // no workspace needed by the current kernels
+  if (c && c->ws && gemm_split_floats(N) > 0 && gemm_split_floats(N) <= gemm_split_floats_cap(c)) {  // k split needs the workspace
+    a.part = c->gemm_part;
+    a.counters = c->gemm_cnt;
+  }
   return launch_gemm_bf16(a, EPI_STORE, 2, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
 }
 

@@ -19,7 +19,7 @@ def _bits(x):
     return torch.from_numpy(si.f32_to_bf16_bits(x).view(np.int16)).to(DEV)
 
 
-def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None):
+def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None, ctx=None):
     g = np.random.default_rng(seed)
     W = (g.standard_normal((N, K)) * 0.05).astype(np.float32)
     X = g.standard_normal((R, K)).astype(np.float32)
@@ -35,7 +35,7 @@ def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None):
     else:
         Wd, Xd = torch.from_numpy(W).to(DEV), torch.from_numpy(X).to(DEV)
     Yd = torch.from_numpy(Y0).to(DEV)
-    mb.mtad_k_gemm(dtype, Wd, Xd, Yd, R, N, K, ldy, accumulate)
+    mb.mtad_k_gemm(dtype, Wd, Xd, Yd, R, N, K, ldy, accumulate, ctx=ctx)
     torch.cuda.synchronize()
     got = Yd.cpu().numpy().astype(np.float64)
     want = Y0.astype(np.float64)
@@ -56,6 +56,23 @@ def test_gemm_bf16_matches_float64(R, N, K):
     mb = _mb()
     print(f"gemm bf16 R={R} N={N} K={K}", flush=True)
     _gemm_case(mb, R, N, K, 1, seed=R * 7 + N)
+
+
+@pytest.mark.parametrize("R,N,K", [(17, 4096, 4096), (17, 4096, 11008), (64, 4096, 4096), (41, 5120, 5120), (9, 2064, 2048), (30, 4112, 2080)])
+def test_gemm_bf16_reduction_split_over_workgroups(R, N, K):
+    """Few output strips and more than 8 rows: with a context's workspace the reduction dimension is cut over workgroups
+    and the last one to arrive adds the ranges; twice in a row, so that the arrival counters are seen to return to zero."""
+    mb = _mb()
+    shape = si.ModelShape(1, 4096, 32, 32, 128, 11008, 32000, "bf16")
+    draft = si.ModelShape(1, 5120, 40, 40, 128, 1024, 32000, "bf16")
+    desc = lambda s: mb.mtad_model(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 1, s.rms_eps, s.rope_theta, None)
+    ctx = mb.mtad_create(mb.mtad_config(1, 4, 4, 1, 64, 256), desc(shape), desc(draft))
+    ws = torch.empty(mb.mtad_workspace_bytes(ctx), dtype=torch.uint8, device=DEV)
+    mb.mtad_bind_workspace(ctx, ws)
+    for rep in range(2):
+        print(f"gemm bf16 k-split R={R} N={N} K={K} rep {rep}", flush=True)
+        _gemm_case(mb, R, N, K, 1, seed=R + N + rep, ctx=ctx)
+    mb.mtad_destroy(ctx)
 
 
 def test_gemm_accumulate_and_padded_rows():
