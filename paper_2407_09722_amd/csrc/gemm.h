@@ -42,6 +42,11 @@ struct GemmArgs {
 };
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s);
+// the same product for passes of many rows, activations staged through LDS (kernels_gemm_tiled.hip); chosen by launch_gemm_bf16
+hipError_t launch_gemm_bf16_tiled(const GemmArgs& a, int epi, hipStream_t s);
+bool gemm_tiled_wide(int N);  // enough strips for workgroups of 8
+size_t gemm_tiled_split_floats(int N);
+int gemm_tiled_split_counters(int N);
 // workspace a context should offer for the k split of a product with N outputs (0 if it would never be split)
 size_t gemm_split_floats(int N);
 int gemm_split_counters(int N);

@@ -59,7 +59,7 @@ __device__ __forceinline__ int token_index(const KvView& kv, int seq, int pos) {
 }
 
 template <int HD, int NRG, int AW>
-__global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(HD == 128 && NRG == 2 ? 1 : 2))) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
+__global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
                                                                int R, int n_heads, int n_chunks, float scale, float* __restrict__ partial,
                                                                int n_splits, int* __restrict__ counters, bf16_t* __restrict__ out, int want_splits) {
   constexpr int KS = HD / 32;    // k-steps of the score product

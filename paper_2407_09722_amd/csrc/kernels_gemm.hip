@@ -339,10 +339,15 @@ static int device_cus() {
 constexpr int SPLIT_MAX_STRIPS = 384, SPLIT_S = 4, SPLIT_KS = 4, SPLIT_NG_MAX = 8;
 size_t gemm_split_floats(int N) {
   const int NT = N / 16;
-  if (NT > SPLIT_MAX_STRIPS) return 0;
-  return (size_t)((NT + SPLIT_S - 1) / SPLIT_S) * SPLIT_S * SPLIT_NG_MAX * SPLIT_KS * 256;
+  const size_t skinny = NT > SPLIT_MAX_STRIPS ? 0 : (size_t)((NT + SPLIT_S - 1) / SPLIT_S) * SPLIT_S * SPLIT_NG_MAX * SPLIT_KS * 256;
+  const size_t tiled = gemm_tiled_split_floats(N);
+  return skinny > tiled ? skinny : tiled;
 }
-int gemm_split_counters(int N) { return N / 16 > SPLIT_MAX_STRIPS ? 0 : (N / 16 + 1) / 2; }  // groups of at least 2 strips
+int gemm_split_counters(int N) {
+  const int skinny = N / 16 > SPLIT_MAX_STRIPS ? 0 : (N / 16 + 1) / 2;  // groups of at least 2 strips
+  const int tiled = gemm_tiled_split_counters(N);
+  return skinny > tiled ? skinny : tiled;
+}
 
 // Strips per workgroup for a product with NT strips and NG row groups.  Cost model (fits the measured times at 17, 41
 // and 64 rows): the busiest compute unit works on rounds * S strips, and a strip costs in proportion to the bytes
@@ -398,9 +403,15 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
   return hipSuccess;
 }
 
+// Passes of many rows stage both operands through LDS (kernels_gemm_tiled.hip).  Measured against the kernels above at
+// the 7B- and 13B-shaped products: it wins from 65 rows up everywhere, and from 25 rows up for products wide enough
+// to give every compute unit a workgroup of 8 strips.
+static bool use_tiled(const GemmArgs& a) { return a.R >= 65 || (a.R >= 25 && gemm_tiled_wide(a.N)); }
+
 hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s) {
   if (a.R <= 0) return hipSuccess;
   if ((a.N % 16) || (a.K % 32) || a.R > 256) return hipErrorInvalidValue;
+  if (use_tiled(a) && (epi != EPI_STORE || (a.ldy % 4) == 0)) return launch_gemm_bf16_tiled(a, epi, s);
   switch (epi) {
     case EPI_STORE: return (a.ldy % 4) ? hipErrorInvalidValue : run_epi<EPI_STORE>(a, tag, s);
     case EPI_RESID: return run_epi<EPI_RESID>(a, tag, s);

@@ -1,0 +1,320 @@
+// Matrix products Y[R][N] = X[R][K] * W[N][K]^T for passes of many rows (a batch of token trees, Section 3.3, or a
+// slab of prompt rows): the same operands, packing and epilogues as the skinny kernels (kernels_gemm.hip), but with
+// both operands staged through LDS, because with 100+ rows the activation fragments a weight tile needs are 20x its
+// own size and can no longer come from L2 per wave, and the product is as close to the matrix cores' bound as to the
+// memory bound.
+//
+// One workgroup (8 waves) owns TN = 4*WS strips of 16 output features and all NCG = WCQ*C column groups of the pass
+// (a column group = the hi and lo terms of 8 rows = the 16 columns of one MFMA).  The reduction dimension runs in
+// stages of SK k tiles.  A stage's weight tiles (TN x SK KiB) and activation fragments (SK x NCG KiB, in B-operand
+// order) are fetched by all waves together, every byte once, into registers and written to one of two LDS slabs
+// while the other slab is being consumed: one barrier per stage.  Registers, not LDS, are the prefetch buffer: the
+// weights (HBM latency) are requested DW = 4 stages ahead, the activations (L2) DX = 2 stages ahead, in rotating
+// register sets, so that about 48 KiB of weights per compute unit are in flight.  A wave is (ws, wc, wk): strips
+// ws*4 .. +3, column groups wc, wc + WCQ, ... (C of them: 4 x C accumulator tiles, every weight fragment read from
+// LDS feeds C MFMAs and every activation fragment 4), k tiles wk, wk + KP, ... of each stage.  The KP waves that share
+// an accumulator tile add their sums through LDS in wave order.
+// A product with few strips also cuts the reduction dimension over workgroups (grid.y): partial sums go to global
+// memory with device-scope write-through stores, and the workgroup that arrives last for a tile adds them in range
+// order and runs the epilogues (deterministic; the same protocol as the skinny kernels).
+#include "common.h"
+#include "gemm.h"
+#include "gemm_device.h"
+
+namespace mtad {
+
+namespace {
+
+constexpr int TW = 8;  // waves per workgroup
+
+template <int WS, int WCQ, int KP, int C, int SK>
+struct TiledShape {
+  static_assert(WS * WCQ * KP == TW, "eight waves");
+  static_assert(SK % KP == 0, "every wave takes the same number of k tiles per stage");
+  static constexpr int TN = 4 * WS;          // strips per workgroup
+  static constexpr int NCG = WCQ * C;        // column groups per pass
+  static constexpr int KW = SK / KP;         // k tiles per wave and stage
+  static constexpr int FR = SK * NCG;        // activation fragments per stage
+  static constexpr int FPW = FR / TW;        // staged per wave
+  static_assert(FR % TW == 0, "the waves share the staging evenly");
+  static constexpr int WF = TN * SK;         // weight tiles per stage
+  static constexpr int WPW = WF / TW;        // staged per wave
+  static_assert(WF % TW == 0, "the waves share the staging evenly");
+  static constexpr int SLAB = WF + FR;       // fragments (KiB) per slab: weight tiles, then activation fragments
+  static constexpr int OWN = TW / KP;        // waves that end up holding sums
+  static constexpr int SLAB_KIB = 2 * SLAB;
+  static constexpr int RED_KIB = KP > 1 ? OWN * 4 * C : 0;
+  static constexpr int LDS_BYTES = (SLAB_KIB > RED_KIB ? SLAB_KIB : RED_KIB) * 1024;
+};
+
+template <int WS, int WCQ, int KP, int C, int SK, int EPI>
+__global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
+  using Sh = TiledShape<WS, WCQ, KP, C, SK>;
+  constexpr int TN = Sh::TN, NCG = Sh::NCG, KW = Sh::KW, FR = Sh::FR, FPW = Sh::FPW, WF = Sh::WF, WPW = Sh::WPW, SLAB = Sh::SLAB, OWN = Sh::OWN;
+  constexpr int DW = 4, DX = 2;  // stages ahead the weights / the activations are requested = register sets of each
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  uint4* const slab = reinterpret_cast<uint4*>(lds_raw);  // [2][SLAB][64]
+  __shared__ float inv_s[NCG * 8];
+  __shared__ int last_s;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wk = wave % KP, wc = (wave / KP) % WCQ, ws = wave / (KP * WCQ);
+  const int K = a.K, KT_all = K >> 5, NT = a.N >> 4;
+  const int R = a.R, row0 = a.row0;
+  const int rows_here = min(NCG * 8, R - row0);
+  const int ncg_here = (rows_here + 7) >> 3;
+  const int tile = blockIdx.x, nt0 = tile * TN + ws * 4;
+  const int KS = gridDim.y, ks = blockIdx.y;
+  const int stages_all = (KT_all + SK - 1) / SK;
+  const int per = (stages_all + KS - 1) / KS;
+  const int st_lo = ks * per, n_st = max(0, min(stages_all, st_lo + per) - st_lo);
+
+  // staging roles.  Activation fragment f = i*TW + wave of a stage is (column group f / SK, k tile f % SK); weight tile
+  // g = i*TW + wave of a stage is (strip g / SK, k tile g % SK).  Both land in LDS in operand order.
+  unsigned xsrc[FPW];  // byte offset from the stage's first k element, or ~0u for a lane beyond the pass's rows
+#pragma unroll
+  for (int i = 0; i < FPW; ++i) {
+    const int f = i * TW + wave, cg = f / SK, kk = f % SK;
+    const int row = cg * 8 + (lane & 7), plane = (lane >> 3) & 1;
+    xsrc[i] = row < rows_here ? (unsigned)((((size_t)plane * R + row) * K + kk * 32 + (lane >> 4) * 8) * 2) : ~0u;
+  }
+  const char* const X = (const char*)a.X + (size_t)row0 * K * 2;
+  auto load_x = [&](uint4 (&xr)[FPW], int t) {  // stage t of this workgroup's range
+    const int st = st_lo + t;
+#pragma unroll
+    for (int i = 0; i < FPW; ++i) {
+      const int kk = (i * TW + wave) % SK;
+      xr[i] = make_uint4(0, 0, 0, 0);
+      if (t < n_st && xsrc[i] != ~0u && st * SK + kk < KT_all) xr[i] = *(const uint4*)(X + (size_t)st * (SK * 64) + xsrc[i]);
+    }
+  };
+  const char* const W = (const char*)a.W;
+  const unsigned voff = (unsigned)lane * 16u;
+  auto load_w = [&](Frag (&wr)[WPW], int t) {
+    const int st = st_lo + t;
+#pragma unroll
+    for (int i = 0; i < WPW; ++i) {
+      const int g = i * TW + wave, nt = tile * TN + g / SK, kt = st * SK + g % SK;
+      wr[i].u = make_uint4(0, 0, 0, 0);
+      if (t < n_st && nt < NT && kt < KT_all) wr[i].n = __builtin_nontemporal_load((const uintx4*)(W + ((((size_t)nt) * KT_all + kt) << 10) + voff));
+    }
+  };
+  auto store_stage = [&](const Frag (&wr)[WPW], const uint4 (&xr)[FPW], int buf) {
+#pragma unroll
+    for (int i = 0; i < WPW; ++i) slab[(buf * SLAB + i * TW + wave) * 64 + lane] = wr[i].u;
+#pragma unroll
+    for (int i = 0; i < FPW; ++i) slab[(buf * SLAB + WF + i * TW + wave) * 64 + lane] = xr[i];
+  };
+
+  floatx4 acc[4][C];
+#pragma unroll
+  for (int si = 0; si < 4; ++si)
+#pragma unroll
+    for (int j = 0; j < C; ++j) acc[si][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const int cv = max(0, min(C, (ncg_here - wc + WCQ - 1) / WCQ));  // column groups of this wave that hold rows
+  auto compute = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < KW; ++i) {
+      const int kk = wk + KP * i;
+      Frag w[4], b[C];
+#pragma unroll
+      for (int si = 0; si < 4; ++si) w[si].u = slab[(buf * SLAB + (ws * 4 + si) * SK + kk) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < C; ++j)
+        if (j < cv) b[j].u = slab[(buf * SLAB + WF + (j * WCQ + wc) * SK + kk) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < C; ++j)
+        if (j < cv) {
+#pragma unroll
+          for (int si = 0; si < 4; ++si) acc[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[si].v, b[j].v, acc[si][j], 0, 0, 0);
+        }
+    }
+  };
+
+  Frag wr[DW][WPW];
+  uint4 xr[DX][FPW];
+  // stage 0 goes to slab 0; the next stages' requests are issued, activations before weights within a stage (loads
+  // complete in issue order: a wait for stage t's activations must not include later weight requests)
+  load_x(xr[0], 0);
+  load_w(wr[0], 0);
+  load_x(xr[1], 1);
+#pragma unroll
+  for (int u = 1; u < DW; ++u) load_w(wr[u], u);
+  store_stage(wr[0], xr[0], 0);
+  __syncthreads();
+  for (int t0 = 0; t0 < n_st; t0 += DW) {
+#pragma unroll
+    for (int u = 0; u < DW; ++u) {
+      const int t = t0 + u;
+      if (t < n_st) {  // uniform over the workgroup
+        load_x(xr[u % DX], t + DX);  // these registers went to LDS during the previous stage
+        load_w(wr[u], t + DW);
+        compute(u & 1);
+        if (t + 1 < n_st) store_stage(wr[(u + 1) % DW], xr[(u + 1) % DX], (u + 1) & 1);
+        __syncthreads();  // the other slab is complete; this one has been consumed
+      }
+    }
+  }
+
+  gemm_row_factors(a, inv_s, rows_here, wave, lane, TW);
+  if constexpr (KP > 1) {  // the waves of one accumulator tile add their sums in wave order
+    floatx4* const red = reinterpret_cast<floatx4*>(lds_raw);  // [OWN][4*C][64], over the slabs (all consumed)
+    const int own = ws * WCQ + wc;
+#pragma unroll
+    for (int p = 1; p < KP; ++p) {
+      if (p > 1) __syncthreads();
+      if (wk == p) {
+#pragma unroll
+        for (int si = 0; si < 4; ++si)
+#pragma unroll
+          for (int j = 0; j < C; ++j) red[((own * 4 + si) * C + j) * 64 + lane] = acc[si][j];
+      }
+      __syncthreads();
+      if (wk == 0) {
+#pragma unroll
+        for (int si = 0; si < 4; ++si)
+#pragma unroll
+          for (int j = 0; j < C; ++j) {
+            const floatx4 t2 = red[((own * 4 + si) * C + j) * 64 + lane];
+            acc[si][j][0] += t2[0]; acc[si][j][1] += t2[1]; acc[si][j][2] += t2[2]; acc[si][j][3] += t2[3];
+          }
+      }
+    }
+  }
+  __syncthreads();  // the row factors are in place
+  const bool owner = wk == 0;
+  const int own = ws * WCQ + wc;
+  if (KS == 1) {
+    if (!owner) return;
+#pragma unroll
+    for (int si = 0; si < 4; ++si)
+      if (nt0 + si < NT) {
+#pragma unroll
+        for (int j = 0; j < C; ++j)
+          if (j < cv) gemm_finish_sum<EPI>(a, nt0 + si, j * WCQ + wc, acc[si][j], inv_s, rows_here, lane);
+      }
+    return;
+  }
+  // partial sums of (tile, range ks, owner wave, strip, column group): 64 lanes x 4 floats
+  float* const mine = a.part + ((((size_t)tile * KS) * OWN + own) * (4 * C)) * 256 + (size_t)lane * 4;
+  constexpr size_t range_stride = (size_t)OWN * 4 * C * 256;
+  if (owner) {
+#pragma unroll
+    for (int si = 0; si < 4; ++si)
+#pragma unroll
+      for (int j = 0; j < C; ++j)
+        if (j < cv) {
+          float* p = mine + (size_t)ks * range_stride + (size_t)(si * C + j) * 256;
+          st8<true>(p, make_uint2(__float_as_uint(acc[si][j][0]), __float_as_uint(acc[si][j][1])));
+          st8<true>(p + 2, make_uint2(__float_as_uint(acc[si][j][2]), __float_as_uint(acc[si][j][3])));
+        }
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int prev = __hip_atomic_fetch_add(a.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    last_s = (prev == KS - 1);
+    if (last_s) __hip_atomic_store(a.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
+  }
+  __syncthreads();
+  if (!last_s || !owner) return;
+#pragma unroll
+  for (int si = 0; si < 4; ++si)
+    if (nt0 + si < NT) {
+#pragma unroll
+      for (int j = 0; j < C; ++j)
+        if (j < cv) {
+          const float* p = mine + (size_t)(si * C + j) * 256;
+          floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+          for (int k2 = 0; k2 < KS; ++k2) {
+            const uint4 v = ld16<true>(p + (size_t)k2 * range_stride);
+            sum[0] += __uint_as_float(v.x); sum[1] += __uint_as_float(v.y); sum[2] += __uint_as_float(v.z); sum[3] += __uint_as_float(v.w);
+          }
+          gemm_finish_sum<EPI>(a, nt0 + si, j * WCQ + wc, sum, inv_s, rows_here, lane);
+        }
+    }
+}
+
+int device_cus() {
+  static const int n_cus = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
+    return cus > 0 ? cus : 256;
+  }();
+  return n_cus;
+}
+
+constexpr int KS_MAX = 8;        // most ranges of the reduction dimension
+constexpr int MIN_STAGES = 8;    // fewest stages a range is worth
+
+// strips per workgroup: 8 when that still gives at least half the compute units a workgroup (activations are
+// re-staged once per workgroup, so wider tiles halve that traffic), else 4
+int tiled_tn(int NT) { return (NT + 7) / 8 * 2 >= device_cus() ? 8 : 4; }
+// ranges of the reduction dimension for a product with `tiles` workgroups per range and `stages` stages
+int tiled_ks(int tiles, int stages) {
+  int ks = device_cus() / tiles;
+  if (ks > KS_MAX) ks = KS_MAX;
+  if (ks > stages / MIN_STAGES) ks = stages / MIN_STAGES;
+  return ks < 1 ? 1 : ks;
+}
+
+template <int WS, int WCQ, int KP, int C, int SK, int EPI>
+hipError_t run_shape(const GemmArgs& a, hipStream_t s) {
+  using Sh = TiledShape<WS, WCQ, KP, C, SK>;
+  auto kern = gemm_bf16_tiled_kernel<WS, WCQ, KP, C, SK, EPI>;
+  static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
+  if (attr != hipSuccess) return attr;
+  const int NT = a.N >> 4, tiles = (NT + Sh::TN - 1) / Sh::TN;
+  int ks = 1;
+  if (a.part && a.counters) ks = tiled_ks(tiles, ((a.K >> 5) + SK - 1) / SK);
+  hipLaunchKernelGGL(kern, dim3(tiles, ks), dim3(TW * 64), Sh::LDS_BYTES, s, a);
+  return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t run_tiled(GemmArgs a, hipStream_t s) {
+  // passes of at most 192 rows, of equal size
+  const int n_pass = (a.R + 191) / 192;
+  const int rows_pass = (((a.R + n_pass - 1) / n_pass) + 7) / 8 * 8;
+  const bool wide = tiled_tn(a.N >> 4) == 8;
+  for (int r0 = 0; r0 < a.R; r0 += rows_pass) {
+    a.row0 = r0;
+    const int rows = a.R - r0 < rows_pass ? a.R - r0 : rows_pass;
+    hipError_t e;
+    if (rows <= 32) e = run_shape<2, 1, 4, 4, 4, EPI>(a, s);
+    else if (rows <= 64) e = wide ? run_shape<2, 2, 2, 4, 4, EPI>(a, s) : run_shape<1, 2, 4, 4, 4, EPI>(a, s);
+    else if (rows <= 128) e = wide ? run_shape<2, 4, 1, 4, 2, EPI>(a, s) : run_shape<1, 4, 2, 4, 2, EPI>(a, s);
+    else e = wide ? run_shape<2, 4, 1, 6, 2, EPI>(a, s) : run_shape<1, 4, 2, 6, 2, EPI>(a, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+bool gemm_tiled_wide(int N) { return tiled_tn(N >> 4) == 8; }
+
+// floats of workspace the k split of a product with N outputs may use (0: never split)
+size_t gemm_tiled_split_floats(int N) {
+  const int NT = N >> 4;
+  if (NT < 1) return 0;
+  const int TN = tiled_tn(NT), tiles = (NT + TN - 1) / TN;
+  int ks = device_cus() / tiles;
+  if (ks > KS_MAX) ks = KS_MAX;
+  if (ks < 2) return 0;
+  return (size_t)tiles * ks * TN * 24 * 256;  // TN strips x up to 24 column groups x 64 lanes x 4 floats per range
+}
+int gemm_tiled_split_counters(int N) { return gemm_tiled_split_floats(N) ? ((N >> 4) + 3) / 4 : 0; }
+
+hipError_t launch_gemm_bf16_tiled(const GemmArgs& a, int epi, hipStream_t s) {
+  switch (epi) {
+    case EPI_STORE: return run_tiled<EPI_STORE>(a, s);
+    case EPI_RESID: return run_tiled<EPI_RESID>(a, s);
+    case EPI_SWIGLU: return run_tiled<EPI_SWIGLU>(a, s);
+    case EPI_QKV: return run_tiled<EPI_QKV>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace mtad

@@ -51,20 +51,23 @@ def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None, ctx=None):
                                    (5, 12288, 4096), (5, 4096, 11008), (33, 80, 96), (41, 512, 2048), (100, 96, 160),
                                    (164, 640, 5120), (200, 32, 64), (256, 1024, 1376),
                                    # more than 8 rows and more strips than compute units: several strips per workgroup
-                                   (17, 12288, 4096), (9, 22016, 256), (30, 12304, 128), (41, 8192, 96), (24, 4112, 64)])
+                                   (17, 12288, 4096), (9, 22016, 256), (30, 12304, 128), (41, 8192, 96), (24, 4112, 64),
+                                   # many rows: activations staged through LDS, 4 or 8 strips per workgroup, 8 / 16 / 24 column groups
+                                   (164, 16400, 256), (64, 16384, 160), (128, 16384, 96), (70, 16, 32), (190, 48, 1056), (77, 2000, 352), (25, 16400, 288), (32, 32000, 2048)])
 def test_gemm_bf16_matches_float64(R, N, K):
     mb = _mb()
     print(f"gemm bf16 R={R} N={N} K={K}", flush=True)
     _gemm_case(mb, R, N, K, 1, seed=R * 7 + N)
 
 
-@pytest.mark.parametrize("R,N,K", [(17, 4096, 4096), (17, 4096, 11008), (64, 4096, 4096), (41, 5120, 5120), (9, 2064, 2048), (30, 4112, 2080)])
+@pytest.mark.parametrize("R,N,K", [(17, 4096, 4096), (17, 4096, 11008), (64, 4096, 4096), (41, 5120, 5120), (9, 2064, 2048), (30, 4112, 2080),
+                                   (164, 5120, 5120), (164, 16384, 2048), (100, 4112, 1056), (256, 4096, 1024)])
 def test_gemm_bf16_reduction_split_over_workgroups(R, N, K):
     """Few output strips and more than 8 rows: with a context's workspace the reduction dimension is cut over workgroups
     and the last one to arrive adds the ranges; twice in a row, so that the arrival counters are seen to return to zero."""
     mb = _mb()
     shape = si.ModelShape(1, 4096, 32, 32, 128, 11008, 32000, "bf16")
-    draft = si.ModelShape(1, 5120, 40, 40, 128, 1024, 32000, "bf16")
+    draft = si.ModelShape(1, 5120, 40, 40, 128, 8192, 32000, "bf16")
     desc = lambda s: mb.mtad_model(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 1, s.rms_eps, s.rope_theta, None)
     ctx = mb.mtad_create(mb.mtad_config(1, 4, 4, 1, 64, 256), desc(shape), desc(draft))
     ws = torch.empty(mb.mtad_workspace_bytes(ctx), dtype=torch.uint8, device=DEV)
