@@ -1,13 +1,15 @@
 // Tree-masked paged attention for bf16 models (half-precision K/V cache), few query rows per sequence
 // (Section 3.3: tree attention gives every tree token its conditional likelihood in one pass).
 //
-// Work item = (key split, head, chunk of 16 or 32 query rows, sequence) = one workgroup of AW waves (4 in both
-// configurations used; 8 measured no faster).  The keys of the item are cut into 32-key tiles dealt round-robin to the waves; every wave
-// runs its own online softmax over its tiles, with the K and V of two tiles in flight, and the waves merge through
-// LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup, which writes the attention output
-// itself: no exchange through global memory.  Longer contexts are cut into splits (at least one tile per wave each, at
-// most as many as fill the machine once) and the workgroup that arrives last merges the splits in split order (same
-// partial layout and protocol as the generic kernel).
+// Work item = (key split, KV head, chunk of 16 or 32 (query head, row) pairs, sequence) = one workgroup of AW waves (4 in
+// all configurations used; 8 measured no faster).  The query heads that share a KV head are rows of the same item, so a
+// grouped-query model reads K and V once for all of them.  The keys of the item are cut into 32-key tiles dealt
+// round-robin to the waves; every wave runs its own online softmax over its tiles, with the K and V of the next tile in
+// flight, and the waves merge through LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup,
+// which writes the attention output itself: no exchange through global memory.  Longer contexts are cut into splits
+// (at least one tile per wave each, at most as many as fill the machine once) and the workgroup that arrives last
+// merges the splits in split order (same partial layout and protocol as the generic kernel), with the loads of all
+// its rows in flight together: that exchange is a chain of memory latencies, not volume.
 //
 // Both products run on the matrix cores, transposed, so that every operand is cheap to fetch:
 //   S^T = K Q^T   A operand = 8 consecutive dims of one key per lane = 16 contiguous bytes of a cache row, loaded from
@@ -23,6 +25,13 @@
 namespace mtad {
 
 namespace {
+
+#ifdef MTAD_ATTN_PROFILE
+__device__ unsigned long long attn_prof[4096 * 8];
+#define ATTN_STAMP(i) do { if (threadIdx.x == 0) { const int b_ = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x; if (b_ < 4096) attn_prof[b_ * 8 + (i)] = wall_clock64(); } } while (0)
+#else
+#define ATTN_STAMP(i) do { } while (0)
+#endif
 
 constexpr int ATK = 32;              // keys per tile
 
@@ -42,7 +51,7 @@ struct MfmaAttnSmem {
       _Float16 v[AW][ATK][VS];         // V tile of each wave
       _Float16 q[2][NRG * 16][VS];     // query rows, hi and lo halves
     } a;
-    float o[AW][16][HD];               // per-wave outputs of one row group for the final merge
+    float o[AW][NRG * 16][HD + 4];     // per-wave outputs for the final merge (padded rows: the 16 rows of a store land in different banks)
   };
   float m[AW][NRG * 16], l[AW][NRG * 16];
   int last;
@@ -76,10 +85,15 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int split = blockIdx.x, head = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks, seq = blockIdx.z;
+  // work item: key split, (KV head g, chunk of RBK (query head, row) pairs), sequence.  Pair p = hq * R + row of the G
+  // query heads that share KV head g: grouped-query models read K and V once for all of them
+  ATTN_STAMP(0);
+  const int split = blockIdx.x, g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks, seq = blockIdx.z;
   const int B = gridDim.z;
-  const int row0 = chunk * RBK, nrows = min(RBK, R - row0);
-  const int KVH = kv.n_kv_heads, g = head * KVH / n_heads;
+  const int KVH = kv.n_kv_heads, G = n_heads / KVH;
+  const int pair0 = chunk * RBK, nrows = min(RBK, G * R - pair0);
+  auto pair_head = [&](int r) { return g * G + (pair0 + r) / R; };  // query head and tree row of pair r of this item
+  auto pair_row = [&](int r) { return (pair0 + r) % R; };
   const int len = kv.len[seq];
   const int nspec = max(0, min(rd.nspec[seq], 64));
   const int ktot = min(len + nspec, kv_capacity(kv));
@@ -96,7 +110,7 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int srow = lane & 15, sg4 = lane >> 4;  // this lane's query row (within a row group) and key group
   unsigned long long rmask[NRG];
 #pragma unroll
-  for (int rg = 0; rg < NRG; ++rg) rmask[rg] = (rg * 16 + srow < nrows) ? rd.mask[seq * R + row0 + rg * 16 + srow] : 0ull;
+  for (int rg = 0; rg < NRG; ++rg) rmask[rg] = (rg * 16 + srow < nrows) ? rd.mask[seq * R + pair_row(rg * 16 + srow)] : 0ull;
 
   // token index of key (tile start + lane % 32), looked up once per tile and handed round by shuffles
   auto lookup = [&](int ti) -> int {
@@ -107,36 +121,31 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const kv16_t* kbase = (const kv16_t*)kv.k + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
   const kv16_t* vbase = (const kv16_t*)kv.v + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
 
-  // K and V of the wave's first two tiles are requested before the queries are staged
+  // K and V of the wave's first tile are requested before the queries are staged.  The loads are unconditional (keys past
+  // the end read token 0 of page 0): their scores are masked, and their V rows are zeroed so that they contribute exact zeros
   KFrag kf[2][2][KS], vf[2][NV];
   auto load_kv = [&](KFrag (&kfs)[2][KS], KFrag (&vfs)[NV], int tok32) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
-      const int tk = __shfl(tok32, blk * 16 + srow, 64);
+      const int tk = max(0, __shfl(tok32, blk * 16 + srow, 64));
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        kfs[blk][ks].u = make_uint4(0, 0, 0, 0);
-        if (tk >= 0) kfs[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
-      }
+      for (int ks = 0; ks < KS; ++ks) kfs[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
     }
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int tk = __shfl(tok32, j * KPL + lane / CH, 64);
-      vfs[j].u = make_uint4(0, 0, 0, 0);  // keys past the end contribute exact zeros
-      if (tk >= 0) vfs[j].u = *(const uint4*)(vbase + (int64_t)tk * tok_stride + (lane % CH) * 8);
+      const uint4 v = *(const uint4*)(vbase + (int64_t)max(0, tk) * tok_stride + (lane % CH) * 8);
+      vfs[j].u = tk >= 0 ? v : make_uint4(0, 0, 0, 0);
     }
   };
-  {
-    const int tok0 = lookup(wave), tok1 = lookup(wave + AW);
-    if (wave < n_tiles) load_kv(kf[0], vf[0], tok0);
-    if (wave + AW < n_tiles) load_kv(kf[1], vf[1], tok1);
-  }
+  if (wave < n_tiles) load_kv(kf[0], vf[0], lookup(wave));
+  ATTN_STAMP(1);
 
   // queries of the item as half hi / lo terms in LDS (rows beyond the item are zero)
   for (int i = t; i < RBK * (HD / 4); i += AW * 64) {
     const int r = i / (HD / 4), d = (i % (HD / 4)) * 4;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (r < nrows) v = *(const float4*)(q + (int64_t)(seq * R + row0 + r) * q_stride + (int64_t)head * HD + d);
+    if (r < nrows) v = *(const float4*)(q + (int64_t)(seq * R + pair_row(r)) * q_stride + (int64_t)pair_head(r) * HD + d);
     const float x[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -147,6 +156,7 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   }
   __syncthreads();
 
+  ATTN_STAMP(2);
   float m_run[NRG], l_run[NRG];  // of row rg*16 + srow (replicated over the four key groups)
   floatx4 acc[NRG][DB];          // O^T: dims db*16 + sg4*4 + i of row rg*16 + srow
 #pragma unroll
@@ -238,19 +248,38 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the V tile has been read before the next one overwrites it
   };
-  // two register sets: while a tile is worked on, the other tile's loads (and then this set's reload) are in flight
-  for (int ti = wave; ti < n_tiles; ti += 2 * AW) {
+  // two register sets: while a tile is worked on, the next tile's loads are in flight; the sets swap by register moves so
+  // that the tile code exists once (a wave runs it only a few times: its size is paid for in instruction fetches)
+#pragma unroll 1
+  for (int ti = wave; ti < n_tiles; ti += AW) {
+    if (ti + AW < n_tiles) load_kv(kf[1], vf[1], lookup(ti + AW));
     process(kf[0], vf[0], ti);
-    if (ti + 2 * AW < n_tiles) load_kv(kf[0], vf[0], lookup(ti + 2 * AW));
-    if (ti + AW < n_tiles) {
-      process(kf[1], vf[1], ti + AW);
-      if (ti + 3 * AW < n_tiles) load_kv(kf[1], vf[1], lookup(ti + 3 * AW));
-    }
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[0][blk][ks].u = kf[1][blk][ks].u;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) vf[0][j].u = vf[1][j].u;
   }
 
-  // ---- the waves meet in LDS, one row group at a time (the buffer aliases the V tiles and the queries)
-  const int mrow = t / TPR, md = (t % TPR) * DPT;  // merge role: row within the group, first of DPT dims
+  ATTN_STAMP(3);
+  // ---- the waves meet in LDS (the buffer aliases the V tiles and the queries)
+  const int mrow = t / TPR, md = (t % TPR) * DPT;  // merge role: row within a row group, first of DPT dims
   const int64_t lo_plane = (int64_t)B * R * n_heads * HD;
+  typedef bf16_t bf16xd __attribute__((ext_vector_type(DPT)));
+  auto store_out = [&](int r, const float (&o)[DPT], float L) {  // normalised row -> hi / lo planes, one vector store each
+    const int64_t idx = (int64_t)(seq * R + pair_row(r)) * n_heads * HD + (int64_t)pair_head(r) * HD + md;
+    bf16xd hi, lo;
+#pragma unroll
+    for (int x = 0; x < DPT; ++x) {
+      bf16_t h, l;
+      split_bf16((L > 0.f) ? o[x] / L : 0.f, h, l);
+      hi[x] = h;
+      lo[x] = l;
+    }
+    *(bf16xd*)(out + idx) = hi;
+    *(bf16xd*)(out + lo_plane + idx) = lo;
+  };
 #pragma unroll
   for (int rg = 0; rg < NRG; ++rg) {
     if (sg4 == 0) {
@@ -258,13 +287,15 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       sm.l[wave][rg * 16 + srow] = l_run[rg];
     }
   }
+  __syncthreads();  // everyone is done with the tiles
 #pragma unroll
-  for (int rg = 0; rg < NRG; ++rg) {
-    __syncthreads();  // everyone is done with the tiles (first pass) / with the previous row group's buffer
+  for (int rg = 0; rg < NRG; ++rg)
 #pragma unroll
     for (int db = 0; db < DB; ++db)
-      *(float4*)&sm.o[wave][srow][db * 16 + sg4 * 4] = make_float4(acc[rg][db][0], acc[rg][db][1], acc[rg][db][2], acc[rg][db][3]);
-    __syncthreads();
+      *(float4*)&sm.o[wave][rg * 16 + srow][db * 16 + sg4 * 4] = make_float4(acc[rg][db][0], acc[rg][db][1], acc[rg][db][2], acc[rg][db][3]);
+  __syncthreads();
+#pragma unroll
+  for (int rg = 0; rg < NRG; ++rg) {
     const int r = rg * 16 + mrow;
     float M = -INFINITY;
 #pragma unroll
@@ -278,88 +309,94 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       const float e = (mw == -INFINITY) ? 0.f : expf(mw - M);
       L += sm.l[w2][r] * e;
 #pragma unroll
-      for (int x = 0; x < DPT; ++x) o[x] += sm.o[w2][mrow][md + x] * e;
+      for (int x4 = 0; x4 < DPT; x4 += 4) {
+        const float4 v = *(const float4*)&sm.o[w2][r][md + x4];
+        o[x4] += v.x * e; o[x4 + 1] += v.y * e; o[x4 + 2] += v.z * e; o[x4 + 3] += v.w * e;
+      }
     }
     if (r < nrows) {
       if (eff == 1) {  // nothing to exchange: this workgroup saw every key
-        const int64_t idx = (int64_t)(seq * R + row0 + r) * n_heads * HD + (int64_t)head * HD + md;
-#pragma unroll
-        for (int x = 0; x < DPT; ++x) {
-          bf16_t hi, lo;
-          split_bf16((L > 0.f) ? o[x] / L : 0.f, hi, lo);
-          out[idx + x] = hi;
-          out[lo_plane + idx + x] = lo;
-        }
+        store_out(r, o, L);
       } else {  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]); device-scope write-through stores
-        float* p = partial + ((((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits + split) * (HD + 2);
+        float* p = partial + ((((int64_t)seq * n_heads + pair_head(r)) * R + pair_row(r)) * n_splits + split) * (HD + 2);
 #pragma unroll
-        for (int x = 0; x < DPT; ++x) __hip_atomic_store(p + 2 + md + x, o[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (t % TPR == 0) {
-          __hip_atomic_store(p, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_store(p + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        for (int x = 0; x < DPT; x += 2) st8<true>(p + 2 + md + x, make_uint2(__float_as_uint(o[x]), __float_as_uint(o[x + 1])));
+        if (t % TPR == 0) st8<true>(p, make_uint2(__float_as_uint(M), __float_as_uint(L)));
       }
     }
   }
+  ATTN_STAMP(4);
   if (eff == 1) return;
 
   // the workgroup that arrives last merges the splits of its rows (split order: deterministic)
   __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
   __syncthreads();
+  ATTN_STAMP(5);
   if (t == 0) {
-    int* c = counters + ((int64_t)seq * n_heads + head) * n_chunks + chunk;
+    int* c = counters + ((int64_t)seq * KVH + g) * n_chunks + chunk;
     const int prev = __hip_atomic_fetch_add(c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     sm.last = (prev == eff - 1);
     if (sm.last) __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
   }
   __syncthreads();
+  ATTN_STAMP(6);
   if (!sm.last) return;
+  // all row groups' loads of a batch of splits are issued together: the exchange is latency, not volume
+  constexpr int SB = 8;  // splits per batch
+  float M2[NRG], L2[NRG], o2[NRG][DPT];
+  const float* pp[NRG];
 #pragma unroll
   for (int rg = 0; rg < NRG; ++rg) {
-    const int r = rg * 16 + mrow;
-    if (r >= nrows) continue;
-    const float* p = partial + (((int64_t)seq * n_heads + head) * R + row0 + r) * n_splits * (HD + 2);
-    float M2 = -INFINITY, L2 = 0.f, o2[DPT];
+    const int r = (rg * 16 + mrow < nrows) ? rg * 16 + mrow : 0;  // threads without a row read pair 0 and drop it
+    pp[rg] = partial + (((int64_t)seq * n_heads + pair_head(r)) * R + pair_row(r)) * n_splits * (HD + 2);
+    M2[rg] = -INFINITY;
+    L2[rg] = 0.f;
 #pragma unroll
-    for (int x = 0; x < DPT; ++x) o2[x] = 0.f;
-    constexpr int SB = 8;  // splits whose loads are in flight together
-    for (int s0 = 0; s0 < eff; s0 += SB) {
-      float mm[SB], ll[SB], oo[SB][DPT];
-#pragma unroll
-      for (int j = 0; j < SB; ++j) {
-        const bool ok = s0 + j < eff;
-        const float* ps = p + (int64_t)(ok ? s0 + j : 0) * (HD + 2);
-        mm[j] = ok ? __hip_atomic_load(ps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -INFINITY;
-        ll[j] = ok ? __hip_atomic_load(ps + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
-#pragma unroll
-        for (int x = 0; x < DPT; ++x) oo[j][x] = ok ? __hip_atomic_load(ps + 2 + md + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
-      }
-#pragma unroll
-      for (int j = 0; j < SB; ++j) {
-        if (mm[j] == -INFINITY) continue;
-        const float Mn = fmaxf(M2, mm[j]);
-        const float ws = (M2 == -INFINITY) ? 0.f : expf(M2 - Mn), wj = expf(mm[j] - Mn);
-        L2 = L2 * ws + ll[j] * wj;
-#pragma unroll
-        for (int x = 0; x < DPT; ++x) o2[x] = o2[x] * ws + oo[j][x] * wj;
-        M2 = Mn;
-      }
-    }
-    const int64_t idx = (int64_t)(seq * R + row0 + r) * n_heads * HD + (int64_t)head * HD + md;
-#pragma unroll
-    for (int x = 0; x < DPT; ++x) {
-      bf16_t hi, lo;
-      split_bf16((L2 > 0.f) ? o2[x] / L2 : 0.f, hi, lo);
-      out[idx + x] = hi;
-      out[lo_plane + idx + x] = lo;
-    }
+    for (int x = 0; x < DPT; ++x) o2[rg][x] = 0.f;
   }
+  for (int s0 = 0; s0 < eff; s0 += SB) {
+    unsigned long long ml[NRG][SB];
+    uint4 oo[NRG][SB][DPT / 4];
+#pragma unroll
+    for (int rg = 0; rg < NRG; ++rg)
+#pragma unroll
+      for (int j = 0; j < SB; ++j) {
+        const float* ps = pp[rg] + (int64_t)min(s0 + j, eff - 1) * (HD + 2);
+        ml[rg][j] = __hip_atomic_load((const unsigned long long*)ps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int x4 = 0; x4 < DPT / 4; ++x4) oo[rg][j][x4] = ld16<true>(ps + 2 + md + x4 * 4);
+      }
+#pragma unroll
+    for (int rg = 0; rg < NRG; ++rg)
+#pragma unroll
+      for (int j = 0; j < SB; ++j) {
+        const float mj = __uint_as_float((uint32_t)ml[rg][j]), lj = __uint_as_float((uint32_t)(ml[rg][j] >> 32));
+        if (s0 + j >= eff || mj == -INFINITY) continue;
+        const float Mn = fmaxf(M2[rg], mj);
+        const float ws = (M2[rg] == -INFINITY) ? 0.f : expf(M2[rg] - Mn), wj = expf(mj - Mn);
+        L2[rg] = L2[rg] * ws + lj * wj;
+#pragma unroll
+        for (int x4 = 0; x4 < DPT / 4; ++x4) {
+          const uint4 v = oo[rg][j][x4];
+          o2[rg][x4 * 4] = o2[rg][x4 * 4] * ws + __uint_as_float(v.x) * wj;
+          o2[rg][x4 * 4 + 1] = o2[rg][x4 * 4 + 1] * ws + __uint_as_float(v.y) * wj;
+          o2[rg][x4 * 4 + 2] = o2[rg][x4 * 4 + 2] * ws + __uint_as_float(v.z) * wj;
+          o2[rg][x4 * 4 + 3] = o2[rg][x4 * 4 + 3] * ws + __uint_as_float(v.w) * wj;
+        }
+        M2[rg] = Mn;
+      }
+  }
+#pragma unroll
+  for (int rg = 0; rg < NRG; ++rg)
+    if (rg * 16 + mrow < nrows) store_out(rg * 16 + mrow, o2[rg], L2[rg]);
+  ATTN_STAMP(7);
 }
 
 template <int HD, int NRG, int AW>
 hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvView& kv, int layer, int B, int R, int n_heads, float* partial,
                     int n_splits, int* counters, void* out, hipStream_t s) {
-  const int n_chunks = (R + NRG * 16 - 1) / (NRG * 16);
+  const int KVH = kv.n_kv_heads, G = n_heads / KVH;
+  const int n_chunks = (G * R + NRG * 16 - 1) / (NRG * 16);  // chunks of (query head, row) pairs per KV head
   const float scale = 1.0f / sqrtf((float)HD);
   auto kern = tree_attn_mfma_kernel<HD, NRG, AW>;
   constexpr size_t lds = sizeof(MfmaAttnSmem<HD, NRG, AW>);
@@ -372,24 +409,33 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
     return cus > 0 ? cus : 256;
   }();
-  const int items = n_heads * n_chunks * B;
+  const int items = KVH * n_chunks * B;
   const int want = items >= n_cus ? 1 : (n_cus + items - 1) / items;
   const int gx = n_splits < want ? n_splits : want;
-  hipLaunchKernelGGL(kern, dim3(gx, n_heads * n_chunks, B), dim3(AW * 64), lds, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale,
+  hipLaunchKernelGGL(kern, dim3(gx, KVH * n_chunks, B), dim3(AW * 64), lds, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale,
                      partial, n_splits, counters, (bf16_t*)out, want);
   return hipGetLastError();
 }
 
+#ifdef MTAD_ATTN_PROFILE
+unsigned long long* attn_prof_ptr() { unsigned long long* p = nullptr; (void)hipGetSymbolAddress((void**)&p, HIP_SYMBOL(attn_prof)); return p; }
+#endif
 }  // namespace
+
+#ifdef MTAD_ATTN_PROFILE
+extern "C" void* mtad_attn_profile() { return attn_prof_ptr(); }
+#endif
 
 // bf16 models: q float32 [B*R][q_stride], half-precision cache, output = bf16 hi / lo planes [2][B*R][n_heads*hd].
 // Passes of up to 16 rows per sequence use 16-row work items, larger ones 32-row items (K and V are read once per item).
 hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
                                  float* partial, int n_splits, int* counters, void* out, hipStream_t s) {
   const int hd = kv.head_dim;
-  if (hd == 128 && R <= 16) return run_mfma<128, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (kv.n_kv_heads < 1 || n_heads % kv.n_kv_heads) return hipErrorInvalidValue;
+  const int pairs = n_heads / kv.n_kv_heads * R;  // (query head, row) pairs that share a KV head
+  if (hd == 128 && pairs <= 16) return run_mfma<128, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (hd == 128) return run_mfma<128, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
-  if (hd == 64 && R <= 16) return run_mfma<64, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 64 && pairs <= 16) return run_mfma<64, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (hd == 64) return run_mfma<64, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   return hipErrorInvalidValue;
 }
