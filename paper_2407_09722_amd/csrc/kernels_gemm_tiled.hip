@@ -21,6 +21,8 @@
 #include "gemm.h"
 #include "gemm_device.h"
 
+#include <type_traits>
+
 namespace mtad {
 
 namespace {
@@ -51,9 +53,11 @@ template <int WS, int WCQ, int KP, int C, int SK, int EPI>
 __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   using Sh = TiledShape<WS, WCQ, KP, C, SK>;
   constexpr int TN = Sh::TN, NCG = Sh::NCG, KW = Sh::KW, FR = Sh::FR, FPW = Sh::FPW, WF = Sh::WF, WPW = Sh::WPW, SLAB = Sh::SLAB, OWN = Sh::OWN;
-  constexpr int DW = 4, DX = 2;  // stages ahead the weights / the activations are requested = register sets of each
+  // stages ahead the weights / the activations are requested = register sets of each (one set fewer where the
+  // accumulators leave no room)
+  constexpr int DW = (WS == 2 && C == 6) ? 3 : 4, DX = 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  uint4* const slab = reinterpret_cast<uint4*>(lds_raw);  // [2][SLAB][64]
+  uintx4* const slab = reinterpret_cast<uintx4*>(lds_raw);  // [2][SLAB][64]
   __shared__ float inv_s[NCG * 8];
   __shared__ int last_s;
 
@@ -72,22 +76,24 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
 
   // staging roles.  Activation fragment f = i*TW + wave of a stage is (column group f / SK, k tile f % SK); weight tile
   // g = i*TW + wave of a stage is (strip g / SK, k tile g % SK).  Both land in LDS in operand order.
-  unsigned xsrc[FPW];  // byte offset from the stage's first k element, or ~0u for a lane beyond the pass's rows
+  // The stage loop is free of branches (the compiler's wait counts stay exact, so the requests really stay in flight
+  // across stages): every load is unconditional from an address clamped into the operand.  Lanes of rows beyond the
+  // pass read row 0: their columns are never stored.  Requests for stages beyond the range and k tiles beyond K read the
+  // last valid ones (finite activations), and such weights are replaced by zeros on their way to LDS.
+  static_assert(TW % SK == 0, "a wave stages the same k tile of every fragment it takes");
+  const int xkk = wave % SK;  // (i*TW + wave) % SK for every i
+  unsigned xsrc[FPW];         // byte offset of this lane's 16 bytes from the first element of its k tile in row row0
 #pragma unroll
   for (int i = 0; i < FPW; ++i) {
-    const int f = i * TW + wave, cg = f / SK, kk = f % SK;
+    const int cg = (i * TW + wave) / SK;
     const int row = cg * 8 + (lane & 7), plane = (lane >> 3) & 1;
-    xsrc[i] = row < rows_here ? (unsigned)((((size_t)plane * R + row) * K + kk * 32 + (lane >> 4) * 8) * 2) : ~0u;
+    xsrc[i] = (unsigned)((((size_t)plane * R + (row < rows_here ? row : 0)) * K + (lane >> 4) * 8) * 2);
   }
   const char* const X = (const char*)a.X + (size_t)row0 * K * 2;
-  auto load_x = [&](uint4 (&xr)[FPW], int t) {  // stage t of this workgroup's range
-    const int st = st_lo + t;
+  auto load_x = [&](uintx4 (&xr)[FPW], int t) {  // stage t of this workgroup's range
+    const int kt = min((st_lo + t) * SK + xkk, KT_all - 1);
 #pragma unroll
-    for (int i = 0; i < FPW; ++i) {
-      const int kk = (i * TW + wave) % SK;
-      xr[i] = make_uint4(0, 0, 0, 0);
-      if (t < n_st && xsrc[i] != ~0u && st * SK + kk < KT_all) xr[i] = *(const uint4*)(X + (size_t)st * (SK * 64) + xsrc[i]);
-    }
+    for (int i = 0; i < FPW; ++i) xr[i] = *(const uintx4*)(X + (size_t)kt * 64 + xsrc[i]);
   };
   const char* const W = (const char*)a.W;
   const unsigned voff = (unsigned)lane * 16u;
@@ -96,13 +102,19 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
 #pragma unroll
     for (int i = 0; i < WPW; ++i) {
       const int g = i * TW + wave, nt = tile * TN + g / SK, kt = st * SK + g % SK;
-      wr[i].u = make_uint4(0, 0, 0, 0);
-      if (t < n_st && nt < NT && kt < KT_all) wr[i].n = __builtin_nontemporal_load((const uintx4*)(W + ((((size_t)nt) * KT_all + kt) << 10) + voff));
+      wr[i].n = __builtin_nontemporal_load((const uintx4*)(W + ((((size_t)min(nt, NT - 1)) * KT_all + min(kt, KT_all - 1)) << 10) + voff));
     }
   };
-  auto store_stage = [&](const Frag (&wr)[WPW], const uint4 (&xr)[FPW], int buf) {
+  // stage t's registers go to slab buf; weight tiles that do not exist become zeros here, where the value is first used
+  // (a mask at the load would make the wave wait for it at once)
+  auto store_stage = [&](const Frag (&wr)[WPW], const uintx4 (&xr)[FPW], int t, int buf) {
+    const int st = st_lo + t;
 #pragma unroll
-    for (int i = 0; i < WPW; ++i) slab[(buf * SLAB + i * TW + wave) * 64 + lane] = wr[i].u;
+    for (int i = 0; i < WPW; ++i) {
+      const int g = i * TW + wave, nt = tile * TN + g / SK, kt = st * SK + g % SK;
+      const unsigned keep = (t < n_st && nt < NT && kt < KT_all) ? ~0u : 0u;
+      slab[(buf * SLAB + i * TW + wave) * 64 + lane] = uintx4{wr[i].n[0] & keep, wr[i].n[1] & keep, wr[i].n[2] & keep, wr[i].n[3] & keep};
+    }
 #pragma unroll
     for (int i = 0; i < FPW; ++i) slab[(buf * SLAB + WF + i * TW + wave) * 64 + lane] = xr[i];
   };
@@ -119,21 +131,18 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
       const int kk = wk + KP * i;
       Frag w[4], b[C];
 #pragma unroll
-      for (int si = 0; si < 4; ++si) w[si].u = slab[(buf * SLAB + (ws * 4 + si) * SK + kk) * 64 + lane];
+      for (int si = 0; si < 4; ++si) w[si].n = slab[(buf * SLAB + (ws * 4 + si) * SK + kk) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < C; ++j) b[j].n = slab[(buf * SLAB + WF + (j * WCQ + wc) * SK + kk) * 64 + lane];
 #pragma unroll
       for (int j = 0; j < C; ++j)
-        if (j < cv) b[j].u = slab[(buf * SLAB + WF + (j * WCQ + wc) * SK + kk) * 64 + lane];
 #pragma unroll
-      for (int j = 0; j < C; ++j)
-        if (j < cv) {
-#pragma unroll
-          for (int si = 0; si < 4; ++si) acc[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[si].v, b[j].v, acc[si][j], 0, 0, 0);
-        }
+        for (int si = 0; si < 4; ++si) acc[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[si].v, b[j].v, acc[si][j], 0, 0, 0);
     }
   };
 
   Frag wr[DW][WPW];
-  uint4 xr[DX][FPW];
+  uintx4 xr[DX][FPW];
   // stage 0 goes to slab 0; the next stages' requests are issued, activations before weights within a stage (loads
   // complete in issue order: a wait for stage t's activations must not include later weight requests)
   load_x(xr[0], 0);
@@ -141,20 +150,38 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   load_x(xr[1], 1);
 #pragma unroll
   for (int u = 1; u < DW; ++u) load_w(wr[u], u);
-  store_stage(wr[0], xr[0], 0);
+  store_stage(wr[0], xr[0], 0, 0);
   __syncthreads();
-  for (int t0 = 0; t0 < n_st; t0 += DW) {
-#pragma unroll
-    for (int u = 0; u < DW; ++u) {
-      const int t = t0 + u;
-      if (t < n_st) {  // uniform over the workgroup
-        load_x(xr[u % DX], t + DX);  // these registers went to LDS during the previous stage
-        load_w(wr[u], t + DW);
-        compute(u & 1);
-        if (t + 1 < n_st) store_stage(wr[(u + 1) % DW], xr[(u + 1) % DX], (u + 1) & 1);
-        __syncthreads();  // the other slab is complete; this one has been consumed
-      }
+  auto stage = [&](auto U, int t) {  // U: position in the register rotation, a compile-time constant
+    constexpr int u = decltype(U)::value;
+    load_x(xr[u % DX], t + DX);  // these registers went to LDS during the previous stage
+    load_w(wr[u % DW], t + DW);
+    compute(u & 1);
+    store_stage(wr[(u + 1) % DW], xr[(u + 1) % DX], t + 1, (u + 1) & 1);
+    __syncthreads();  // the other slab is complete; this one has been consumed
+  };
+  // whole trips of the rotation (CYC stages: both register rotations and the slab parity are back where they began),
+  // then the first stages of one more trip
+  constexpr int CYC = (DW % DX == 0) ? DW : DW * DX;
+  static_assert(CYC % 2 == 0 && CYC <= 6, "slab parity; the stages below are written out up to 6");
+  int t0 = 0;
+  for (; t0 + CYC <= n_st; t0 += CYC) {
+    stage(std::integral_constant<int, 0>{}, t0);
+    stage(std::integral_constant<int, 1>{}, t0 + 1);
+    stage(std::integral_constant<int, 2>{}, t0 + 2);
+    stage(std::integral_constant<int, 3>{}, t0 + 3);
+    if constexpr (CYC > 4) {
+      stage(std::integral_constant<int, 4>{}, t0 + 4);
+      stage(std::integral_constant<int, 5>{}, t0 + 5);
     }
+  }
+  const int rem = n_st - t0;  // uniform over the workgroup
+  if (rem > 0) stage(std::integral_constant<int, 0>{}, t0);
+  if (rem > 1) stage(std::integral_constant<int, 1>{}, t0 + 1);
+  if (rem > 2) stage(std::integral_constant<int, 2>{}, t0 + 2);
+  if constexpr (CYC > 4) {
+    if (rem > 3) stage(std::integral_constant<int, 3>{}, t0 + 3);
+    if (rem > 4) stage(std::integral_constant<int, 4>{}, t0 + 4);
   }
 
   gemm_row_factors(a, inv_s, rows_here, wave, lane, TW);
