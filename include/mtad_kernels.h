@@ -21,7 +21,8 @@ extern "C" {
  * accumulate != 0 adds to Y (the residual connection).  This is the product kernel of the passes with its plain store
  * epilogue.  ctx may be NULL; with a context whose bound workspace covers the shape (it does for the context's own
  * model shapes) products with few output strips and more than 8 rows also split the reduction dimension over
- * workgroups, as in the passes. */
+ * workgroups, and products of many rows (65 or more, or 25 or more with at least 16384 outputs) take the kernel that
+ * stages both operands through LDS, as in the passes. */
 int mtad_k_gemm(mtad_ctx *ctx, int32_t dtype, const void *W, const void *X, float *Y, int32_t R, int32_t N, int32_t K, int32_t ldy,
                 int32_t accumulate, void *stream);
 

@@ -39,6 +39,10 @@ struct GemmArgs {
   // of 256 floats, and one zeroed counter per group (left zeroed); null = no split
   float* part;
   int* counters;
+  // scratch for the many-row kernel: the pass's activations rewritten in B-operand fragment order; null = not offered
+  // (such products then run on the skinny kernels)
+  bf16_t* xfrag;
+  size_t xfrag_elems;
 };
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s);
@@ -46,6 +50,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s);
 hipError_t launch_gemm_bf16_tiled(const GemmArgs& a, int epi, hipStream_t s);
 bool gemm_tiled_wide(int N);  // enough strips for workgroups of 8
 size_t gemm_tiled_split_floats(int N);
+size_t gemm_tiled_xfrag_elems(int R, int K);  // scratch elements a product with R rows and reduction width K wants
 int gemm_tiled_split_counters(int N);
 // workspace a context should offer for the k split of a product with N outputs (0 if it would never be split)
 size_t gemm_split_floats(int N);

@@ -26,12 +26,6 @@ namespace mtad {
 
 namespace {
 
-#ifdef MTAD_ATTN_PROFILE
-__device__ unsigned long long attn_prof[4096 * 8];
-#define ATTN_STAMP(i) do { if (threadIdx.x == 0) { const int b_ = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x; if (b_ < 4096) attn_prof[b_ * 8 + (i)] = wall_clock64(); } } while (0)
-#else
-#define ATTN_STAMP(i) do { } while (0)
-#endif
 
 constexpr int ATK = 32;              // keys per tile
 
@@ -87,7 +81,6 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   // work item: key split, (KV head g, chunk of RBK (query head, row) pairs), sequence.  Pair p = hq * R + row of the G
   // query heads that share KV head g: grouped-query models read K and V once for all of them
-  ATTN_STAMP(0);
   const int split = blockIdx.x, g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks, seq = blockIdx.z;
   const int B = gridDim.z;
   const int KVH = kv.n_kv_heads, G = n_heads / KVH;
@@ -139,7 +132,6 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
   };
   if (wave < n_tiles) load_kv(kf[0], vf[0], lookup(wave));
-  ATTN_STAMP(1);
 
   // queries of the item as half hi / lo terms in LDS (rows beyond the item are zero)
   for (int i = t; i < RBK * (HD / 4); i += AW * 64) {
@@ -155,8 +147,6 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     }
   }
   __syncthreads();
-
-  ATTN_STAMP(2);
   float m_run[NRG], l_run[NRG];  // of row rg*16 + srow (replicated over the four key groups)
   floatx4 acc[NRG][DB];          // O^T: dims db*16 + sg4*4 + i of row rg*16 + srow
 #pragma unroll
@@ -261,8 +251,6 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
     for (int j = 0; j < NV; ++j) vf[0][j].u = vf[1][j].u;
   }
-
-  ATTN_STAMP(3);
   // ---- the waves meet in LDS (the buffer aliases the V tiles and the queries)
   const int mrow = t / TPR, md = (t % TPR) * DPT;  // merge role: row within a row group, first of DPT dims
   const int64_t lo_plane = (int64_t)B * R * n_heads * HD;
@@ -325,13 +313,11 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       }
     }
   }
-  ATTN_STAMP(4);
   if (eff == 1) return;
 
   // the workgroup that arrives last merges the splits of its rows (split order: deterministic)
   __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
   __syncthreads();
-  ATTN_STAMP(5);
   if (t == 0) {
     int* c = counters + ((int64_t)seq * KVH + g) * n_chunks + chunk;
     const int prev = __hip_atomic_fetch_add(c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -339,7 +325,6 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     if (sm.last) __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
   }
   __syncthreads();
-  ATTN_STAMP(6);
   if (!sm.last) return;
   // all row groups' loads of a batch of splits are issued together: the exchange is latency, not volume
   constexpr int SB = 8;  // splits per batch
@@ -389,7 +374,6 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
   for (int rg = 0; rg < NRG; ++rg)
     if (rg * 16 + mrow < nrows) store_out(rg * 16 + mrow, o2[rg], L2[rg]);
-  ATTN_STAMP(7);
 }
 
 template <int HD, int NRG, int AW>
@@ -417,14 +401,8 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
   return hipGetLastError();
 }
 
-#ifdef MTAD_ATTN_PROFILE
-unsigned long long* attn_prof_ptr() { unsigned long long* p = nullptr; (void)hipGetSymbolAddress((void**)&p, HIP_SYMBOL(attn_prof)); return p; }
-#endif
 }  // namespace
 
-#ifdef MTAD_ATTN_PROFILE
-extern "C" void* mtad_attn_profile() { return attn_prof_ptr(); }
-#endif
 
 // bf16 models: q float32 [B*R][q_stride], half-precision cache, output = bf16 hi / lo planes [2][B*R][n_heads*hd].
 // Passes of up to 16 rows per sequence use 16-row work items, larger ones 32-row items (K and V are read once per item).

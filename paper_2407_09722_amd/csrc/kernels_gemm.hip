@@ -406,7 +406,10 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
 // Passes of many rows stage both operands through LDS (kernels_gemm_tiled.hip).  Measured against the kernels above at
 // the 7B- and 13B-shaped products: it wins from 65 rows up everywhere, and from 25 rows up for products wide enough
 // to give every compute unit a workgroup of 8 strips.
-static bool use_tiled(const GemmArgs& a) { return a.R >= 65 || (a.R >= 25 && gemm_tiled_wide(a.N)); }
+static bool use_tiled(const GemmArgs& a) {
+  if (!a.xfrag || a.xfrag_elems < gemm_tiled_xfrag_elems(a.R, a.K)) return false;  // needs its scratch
+  return a.R >= 65 || (a.R >= 25 && gemm_tiled_wide(a.N));
+}
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, int epi, int tag, hipStream_t s) {
   if (a.R <= 0) return hipSuccess;

@@ -7,7 +7,9 @@
 // One workgroup (8 waves) owns TN = 4*WS strips of 16 output features and all NCG = WCQ*C column groups of the pass
 // (a column group = the hi and lo terms of 8 rows = the 16 columns of one MFMA).  The reduction dimension runs in
 // stages of SK k tiles.  A stage's weight tiles (TN x SK KiB) and activation fragments (SK x NCG KiB, in B-operand
-// order) are fetched by all waves together, every byte once, into registers and written to one of two LDS slabs
+// order: a small kernel rewrites the pass's activation planes that way first, once per product, so that staging reads
+// whole cache lines instead of gathering 64-byte pieces of 16 rows) are fetched by all waves together, every byte once,
+// into registers and written to one of two LDS slabs
 // while the other slab is being consumed: one barrier per stage.  Registers, not LDS, are the prefetch buffer: the
 // weights (HBM latency) are requested DW = 4 stages ahead, the activations (L2) DX = 2 stages ahead, in rotating
 // register sets, so that about 48 KiB of weights per compute unit are in flight.  A wave is (ws, wc, wk): strips
@@ -32,7 +34,7 @@ constexpr int TW = 8;  // waves per workgroup
 template <int WS, int WCQ, int KP, int C, int SK>
 struct TiledShape {
   static_assert(WS * WCQ * KP == TW, "eight waves");
-  static_assert(SK % KP == 0, "every wave takes the same number of k tiles per stage");
+  static_assert(SK == KP, "every wave takes one k tile per stage");
   static constexpr int TN = 4 * WS;          // strips per workgroup
   static constexpr int NCG = WCQ * C;        // column groups per pass
   static constexpr int KW = SK / KP;         // k tiles per wave and stage
@@ -49,13 +51,31 @@ struct TiledShape {
   static constexpr int LDS_BYTES = (SLAB_KIB > RED_KIB ? SLAB_KIB : RED_KIB) * 1024;
 };
 
+// Activation planes [2][R][K] -> fragments [k tile][column group][64 lanes][8]: lane l of fragment (kt, cg) holds row
+// cg*8 + l%8 of plane (l/8)%2, k = kt*32 + (l/16)*8 .. +8 (the B operand of one MFMA); rows beyond the pass are zeros.
+// One wave per fragment.
+__global__ __launch_bounds__(256) void xfrag_kernel(const bf16_t* __restrict__ X, bf16_t* __restrict__ out, int R, int K, int row0, int rows_here,
+                                                    int ncg) {
+  const int lane = threadIdx.x & 63;
+  const int64_t f = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int KT = K >> 5;
+  if (f >= (int64_t)KT * ncg) return;
+  const int kt = (int)(f / ncg), cg = (int)(f % ncg);
+  const int row = cg * 8 + (lane & 7), plane = (lane >> 3) & 1;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < rows_here) v = *(const uint4*)(X + ((size_t)plane * R + row0 + row) * K + kt * 32 + (lane >> 4) * 8);
+  *(uint4*)(out + (f * 64 + lane) * 8) = v;
+}
+
 template <int WS, int WCQ, int KP, int C, int SK, int EPI>
 __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   using Sh = TiledShape<WS, WCQ, KP, C, SK>;
-  constexpr int TN = Sh::TN, NCG = Sh::NCG, KW = Sh::KW, FR = Sh::FR, FPW = Sh::FPW, WF = Sh::WF, WPW = Sh::WPW, SLAB = Sh::SLAB, OWN = Sh::OWN;
-  // stages ahead the weights / the activations are requested = register sets of each (one set fewer where the
-  // accumulators leave no room)
-  constexpr int DW = (WS == 2 && C == 6) ? 3 : 4, DX = 2;
+  constexpr int TN = Sh::TN, NCG = Sh::NCG, FR = Sh::FR, FPW = Sh::FPW, WF = Sh::WF, WPW = Sh::WPW, SLAB = Sh::SLAB, OWN = Sh::OWN;
+  // stages ahead the weights / the activations are requested = register sets of each (powers of two; about 32 and 48
+  // registers): the weights come from HBM and need the longer flight
+  constexpr int DW0 = 8 / (WPW * SK), DW = DW0 >= 8 ? 8 : (DW0 >= 4 ? 4 : 2);
+  constexpr int DX0 = 12 / (FPW * SK), DX = DX0 >= 4 ? 4 : 2;
+  constexpr int CYC = DW > DX ? DW : DX;  // stages after which both rotations and the slab parity repeat
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   uintx4* const slab = reinterpret_cast<uintx4*>(lds_raw);  // [2][SLAB][64]
   __shared__ float inv_s[NCG * 8];
@@ -77,26 +97,18 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   // staging roles.  Activation fragment f = i*TW + wave of a stage is (column group f / SK, k tile f % SK); weight tile
   // g = i*TW + wave of a stage is (strip g / SK, k tile g % SK).  Both land in LDS in operand order.
   // The stage loop is free of branches (the compiler's wait counts stay exact, so the requests really stay in flight
-  // across stages): every load is unconditional from an address clamped into the operand.  Lanes of rows beyond the
-  // pass read row 0: their columns are never stored.  Requests for stages beyond the range and k tiles beyond K read the
+  // across stages): every load is unconditional from an address clamped into the operand.  Requests for stages beyond the range and k tiles beyond K read the
   // last valid ones (finite activations), and such weights are replaced by zeros on their way to LDS.
+  const unsigned voff = (unsigned)lane * 16u;
   static_assert(TW % SK == 0, "a wave stages the same k tile of every fragment it takes");
   const int xkk = wave % SK;  // (i*TW + wave) % SK for every i
-  unsigned xsrc[FPW];         // byte offset of this lane's 16 bytes from the first element of its k tile in row row0
-#pragma unroll
-  for (int i = 0; i < FPW; ++i) {
-    const int cg = (i * TW + wave) / SK;
-    const int row = cg * 8 + (lane & 7), plane = (lane >> 3) & 1;
-    xsrc[i] = (unsigned)((((size_t)plane * R + (row < rows_here ? row : 0)) * K + (lane >> 4) * 8) * 2);
-  }
-  const char* const X = (const char*)a.X + (size_t)row0 * K * 2;
+  const char* const XF = (const char*)a.xfrag;
   auto load_x = [&](uintx4 (&xr)[FPW], int t) {  // stage t of this workgroup's range
     const int kt = min((st_lo + t) * SK + xkk, KT_all - 1);
 #pragma unroll
-    for (int i = 0; i < FPW; ++i) xr[i] = *(const uintx4*)(X + (size_t)kt * 64 + xsrc[i]);
+    for (int i = 0; i < FPW; ++i) xr[i] = *(const uintx4*)(XF + ((((size_t)kt * NCG + (i * TW + wave) / SK) * 64) << 4) + voff);
   };
   const char* const W = (const char*)a.W;
-  const unsigned voff = (unsigned)lane * 16u;
   auto load_w = [&](Frag (&wr)[WPW], int t) {
     const int st = st_lo + t;
 #pragma unroll
@@ -125,20 +137,24 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < C; ++j) acc[si][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   const int cv = max(0, min(C, (ncg_here - wc + WCQ - 1) / WCQ));  // column groups of this wave that hold rows
-  auto compute = [&](int buf) {
+  // The two waves of a SIMD (waves w and w + 4) work half a stage apart: a stage is a memory phase (this stage's operand
+  // fragments LDS -> registers, requests for later stages, the next stage's registers -> LDS) and a compute phase (the
+  // MFMAs, operands all in registers), each ended by a workgroup barrier; waves 4..7 pass one extra barrier at the start
+  // and waves 0..3 one at the end, so that on every SIMD one wave computes while the other moves data.  Slab (t+1)&1 is
+  // written in the memory phases of stage t (two consecutive barrier intervals) and read in those of stage t+1 (the two
+  // after), and was last read two intervals before the first write.
+  Frag fw[4], fb[C];
+  auto fetch = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < KW; ++i) {
-      const int kk = wk + KP * i;
-      Frag w[4], b[C];
+    for (int si = 0; si < 4; ++si) fw[si].n = slab[(buf * SLAB + (ws * 4 + si) * SK + wk) * 64 + lane];
 #pragma unroll
-      for (int si = 0; si < 4; ++si) w[si].n = slab[(buf * SLAB + (ws * 4 + si) * SK + kk) * 64 + lane];
+    for (int j = 0; j < C; ++j) fb[j].n = slab[(buf * SLAB + WF + (j * WCQ + wc) * SK + wk) * 64 + lane];
+  };
+  auto compute = [&]() {
 #pragma unroll
-      for (int j = 0; j < C; ++j) b[j].n = slab[(buf * SLAB + WF + (j * WCQ + wc) * SK + kk) * 64 + lane];
+    for (int j = 0; j < C; ++j)
 #pragma unroll
-      for (int j = 0; j < C; ++j)
-#pragma unroll
-        for (int si = 0; si < 4; ++si) acc[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[si].v, b[j].v, acc[si][j], 0, 0, 0);
-    }
+      for (int si = 0; si < 4; ++si) acc[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[si].v, fb[j].v, acc[si][j], 0, 0, 0);
   };
 
   Frag wr[DW][WPW];
@@ -147,42 +163,59 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   // complete in issue order: a wait for stage t's activations must not include later weight requests)
   load_x(xr[0], 0);
   load_w(wr[0], 0);
-  load_x(xr[1], 1);
 #pragma unroll
-  for (int u = 1; u < DW; ++u) load_w(wr[u], u);
+  for (int u = 1; u < CYC; ++u) {
+    if (u < DX) load_x(xr[u], u);
+    if (u < DW) load_w(wr[u], u);
+  }
   store_stage(wr[0], xr[0], 0, 0);
   __syncthreads();
-  auto stage = [&](auto U, int t) {  // U: position in the register rotation, a compile-time constant
+  const bool late = wave >= TW / 2;
+  if (late) __syncthreads();
+  auto stage = [&](auto U, int t) {  // U: position in the register rotations, a compile-time constant
     constexpr int u = decltype(U)::value;
+    fetch(u & 1);
     load_x(xr[u % DX], t + DX);  // these registers went to LDS during the previous stage
     load_w(wr[u % DW], t + DW);
-    compute(u & 1);
     store_stage(wr[(u + 1) % DW], xr[(u + 1) % DX], t + 1, (u + 1) & 1);
-    __syncthreads();  // the other slab is complete; this one has been consumed
+    __builtin_amdgcn_sched_barrier(0);  // the MFMAs below use registers only: without this they drift above the barrier
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    compute();
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
   };
-  // whole trips of the rotation (CYC stages: both register rotations and the slab parity are back where they began),
-  // then the first stages of one more trip
-  constexpr int CYC = (DW % DX == 0) ? DW : DW * DX;
-  static_assert(CYC % 2 == 0 && CYC <= 6, "slab parity; the stages below are written out up to 6");
+  // whole trips of the rotation, then the first stages of one more trip
+  static_assert(CYC == 2 || CYC == 4 || CYC == 8, "the stages below are written out for these");
   int t0 = 0;
   for (; t0 + CYC <= n_st; t0 += CYC) {
     stage(std::integral_constant<int, 0>{}, t0);
     stage(std::integral_constant<int, 1>{}, t0 + 1);
-    stage(std::integral_constant<int, 2>{}, t0 + 2);
-    stage(std::integral_constant<int, 3>{}, t0 + 3);
+    if constexpr (CYC > 2) {
+      stage(std::integral_constant<int, 2>{}, t0 + 2);
+      stage(std::integral_constant<int, 3>{}, t0 + 3);
+    }
     if constexpr (CYC > 4) {
       stage(std::integral_constant<int, 4>{}, t0 + 4);
       stage(std::integral_constant<int, 5>{}, t0 + 5);
+      stage(std::integral_constant<int, 6>{}, t0 + 6);
+      stage(std::integral_constant<int, 7>{}, t0 + 7);
     }
   }
   const int rem = n_st - t0;  // uniform over the workgroup
   if (rem > 0) stage(std::integral_constant<int, 0>{}, t0);
-  if (rem > 1) stage(std::integral_constant<int, 1>{}, t0 + 1);
-  if (rem > 2) stage(std::integral_constant<int, 2>{}, t0 + 2);
+  if constexpr (CYC > 2) {
+    if (rem > 1) stage(std::integral_constant<int, 1>{}, t0 + 1);
+    if (rem > 2) stage(std::integral_constant<int, 2>{}, t0 + 2);
+  }
   if constexpr (CYC > 4) {
     if (rem > 3) stage(std::integral_constant<int, 3>{}, t0 + 3);
     if (rem > 4) stage(std::integral_constant<int, 4>{}, t0 + 4);
+    if (rem > 5) stage(std::integral_constant<int, 5>{}, t0 + 5);
+    if (rem > 6) stage(std::integral_constant<int, 6>{}, t0 + 6);
   }
+  if (!late) __syncthreads();
 
   gemm_row_factors(a, inv_s, rows_here, wave, lane, TW);
   if constexpr (KP > 1) {  // the waves of one accumulator tile add their sums in wave order
@@ -293,6 +326,12 @@ hipError_t run_shape(const GemmArgs& a, hipStream_t s) {
   static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
   if (attr != hipSuccess) return attr;
   const int NT = a.N >> 4, tiles = (NT + Sh::TN - 1) / Sh::TN;
+  {  // this pass's activations in fragment order
+    const int64_t frags = (int64_t)(a.K >> 5) * Sh::NCG;
+    if ((size_t)frags * 512 > a.xfrag_elems) return hipErrorInvalidValue;
+    const int rows = a.R - a.row0 < Sh::NCG * 8 ? a.R - a.row0 : Sh::NCG * 8;
+    hipLaunchKernelGGL(xfrag_kernel, dim3((unsigned)((frags + 3) / 4)), dim3(256), 0, s, a.X, a.xfrag, a.R, a.K, a.row0, rows, Sh::NCG);
+  }
   int ks = 1;
   if (a.part && a.counters) ks = tiled_ks(tiles, ((a.K >> 5) + SK - 1) / SK);
   hipLaunchKernelGGL(kern, dim3(tiles, ks), dim3(TW * 64), Sh::LDS_BYTES, s, a);
@@ -310,15 +349,18 @@ hipError_t run_tiled(GemmArgs a, hipStream_t s) {
     const int rows = a.R - r0 < rows_pass ? a.R - r0 : rows_pass;
     hipError_t e;
     if (rows <= 32) e = run_shape<2, 1, 4, 4, 4, EPI>(a, s);
-    else if (rows <= 64) e = wide ? run_shape<2, 2, 2, 4, 4, EPI>(a, s) : run_shape<1, 2, 4, 4, 4, EPI>(a, s);
-    else if (rows <= 128) e = wide ? run_shape<2, 4, 1, 4, 2, EPI>(a, s) : run_shape<1, 4, 2, 4, 2, EPI>(a, s);
-    else e = wide ? run_shape<2, 4, 1, 6, 2, EPI>(a, s) : run_shape<1, 4, 2, 6, 2, EPI>(a, s);
+    else if (rows <= 64) e = wide ? run_shape<2, 2, 2, 4, 2, EPI>(a, s) : run_shape<1, 2, 4, 4, 4, EPI>(a, s);
+    else if (rows <= 128) e = wide ? run_shape<2, 4, 1, 4, 1, EPI>(a, s) : run_shape<1, 4, 2, 4, 2, EPI>(a, s);
+    else e = wide ? run_shape<2, 4, 1, 6, 1, EPI>(a, s) : run_shape<1, 4, 2, 6, 2, EPI>(a, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
 }  // namespace
+
+
+size_t gemm_tiled_xfrag_elems(int R, int K) { (void)R; return (size_t)(K >> 5) * 24 * 512; }  // up to 24 column groups per pass
 
 bool gemm_tiled_wide(int N) { return tiled_tn(N >> 4) == 8; }
 

@@ -29,6 +29,8 @@ struct mtad_ctx {
   float* gemm_part;  // k-split partial sums of the product kernel (products with few strips, more than 8 rows)
   int* gemm_cnt;
   int gemm_cnt_n;
+  bf16_t* gemm_xfrag;  // scratch of the many-row product kernel: a pass's activations in operand-fragment order
+  size_t gemm_xfrag_n;
   size_t attn_cnt_n;
   float2* rope;
   int* part_idx;
@@ -125,6 +127,9 @@ void carve(mtad_ctx* c, char* base) {
     c->gemm_part = k.take<float>(pf + 64);
     c->gemm_cnt_n = pc + 1;
     c->gemm_cnt = k.take<int>((size_t)c->gemm_cnt_n);
+    // widest reduction dimension of any product: the model widths and FFN widths
+    c->gemm_xfrag_n = gemm_tiled_xfrag_elems((int)rows, imax(imax(dmax, fmax), hhd));
+    c->gemm_xfrag = k.take<bf16_t>(c->gemm_xfrag_n);
   }
   c->bar = k.take<unsigned long long>(32);
   for (int i = 0; i < 2; ++i) c->steps_dev[i] = k.take<PassStep>(pass_steps(PASS_MAX_LAYERS, true));
@@ -293,6 +298,8 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     a.eps = m->rms_eps;
     a.part = c->gemm_part;
     a.counters = c->gemm_cnt;
+    a.xfrag = c->gemm_xfrag;
+    a.xfrag_elems = c->gemm_xfrag_n;
     // qkv
     a.W = (const bf16_t*)L[1]; a.X = (const bf16_t*)c->xg; a.N = qkvw; a.K = d;
     a.ssq = c->ssq; a.NP = np;
@@ -337,7 +344,7 @@ int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* ls
     a.W = (const bf16_t*)W[tail + 1]; a.X = (const bf16_t*)c->xg; a.R = rows; a.N = m->vocab; a.K = m->d_model;
     a.ssq = c->ssq; a.NP = m->d_model / 16; a.eps = m->rms_eps;
     a.Y = logits; a.ldy = m->vocab; a.lse_part = c->lse_part;
-    a.part = c->gemm_part; a.counters = c->gemm_cnt;
+    a.part = c->gemm_part; a.counters = c->gemm_cnt; a.xfrag = c->gemm_xfrag; a.xfrag_elems = c->gemm_xfrag_n;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_STORE, same_shape(m, &c->tshape) ? 1 : 0, s));
     return finish_lse(c, m, rows, logits, lse, s);
   }
@@ -588,6 +595,10 @@ int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float*
   if (c && c->ws && gemm_split_floats(N) > 0 && gemm_split_floats(N) <= gemm_split_floats_cap(c)) {  // k split needs the workspace
     a.part = c->gemm_part;
     a.counters = c->gemm_cnt;
+  }
+  if (c && c->ws && gemm_tiled_xfrag_elems(R, K) <= c->gemm_xfrag_n) {  // the many-row kernel needs its scratch
+    a.xfrag = c->gemm_xfrag;
+    a.xfrag_elems = c->gemm_xfrag_n;
   }
   return launch_gemm_bf16(a, EPI_STORE, 2, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
 }

@@ -61,10 +61,15 @@ def test_gemm_bf16_matches_float64(R, N, K):
 
 
 @pytest.mark.parametrize("R,N,K", [(17, 4096, 4096), (17, 4096, 11008), (64, 4096, 4096), (41, 5120, 5120), (9, 2064, 2048), (30, 4112, 2080),
-                                   (164, 5120, 5120), (164, 16384, 2048), (100, 4112, 1056), (256, 4096, 1024)])
-def test_gemm_bf16_reduction_split_over_workgroups(R, N, K):
-    """Few output strips and more than 8 rows: with a context's workspace the reduction dimension is cut over workgroups
-    and the last one to arrive adds the ranges; twice in a row, so that the arrival counters are seen to return to zero."""
+                                   (164, 5120, 5120), (164, 16384, 2048), (100, 4112, 1056), (256, 4096, 1024),
+                                   # many rows (with a context's scratch): 4 or 8 strips per workgroup, 4 / 8 / 16 / 24 column
+                                   # groups, ragged strips, rows and k tiles
+                                   (164, 16400, 256), (64, 16384, 160), (128, 16384, 96), (70, 16, 32), (190, 48, 1056),
+                                   (77, 2000, 352), (25, 16400, 288), (32, 32000, 2048), (100, 96, 160), (200, 32, 64)])
+def test_gemm_bf16_with_context_workspace(R, N, K):
+    """With a context's workspace: few output strips and more than 8 rows cut the reduction dimension over workgroups and
+    the last one to arrive adds the ranges; passes of many rows take the kernel that stages both operands through LDS.
+    Twice in a row, so that the arrival counters are seen to return to zero."""
     mb = _mb()
     shape = si.ModelShape(1, 4096, 32, 32, 128, 11008, 32000, "bf16")
     draft = si.ModelShape(1, 5120, 40, 40, 128, 8192, 32000, "bf16")
