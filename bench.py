@@ -166,7 +166,7 @@ def main():
 
     def replay():
         for Wt, n, k in launches:
-            mb.mtad_k_gemm(dt_id, Wt, X, Y, rows, n, k, n, False)
+            mb.mtad_k_gemm(dt_id, Wt, X, Y, rows, n, k, n, False, ctx=eng.ctx)   # the pass's own kernel choice
     replay()
     reps = max(3, min(20, K // 3))
     ev[0].record(stream)
@@ -185,7 +185,12 @@ def main():
                           "write_bytes_per_launch": int(float(kv["write_bytes_per_launch"])),
                           "source": "profiles/c3_gemm_hbm_counters.md (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel)"}
         traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]   # HBM bytes per launch
-    roofline = {"kernel": "gemm_bf16_kernel (skinny weight-streaming GEMM, all target matrices)" if dt_id else "gemm_f32_kernel",
+    kname = "gemm_f32_kernel"
+    if dt_id:
+        kname = ("gemm_bf16_kernel (skinny weight-streaming GEMM, all target matrices)" if rows <= 8 else
+                 "gemm_bf16_multi_kernel / gemm_bf16_kernel (several strips per workgroup)" if rows < 65 else
+                 "gemm_bf16_tiled_kernel (operands staged through LDS)")
+    roofline = {"kernel": kname,
                 "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_detail": traffic_detail,
                 "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(gemm_ms * 1e3, 3),
