@@ -10,7 +10,16 @@ these readings of what the paper leaves open or misprints:
   * MTAD passes a prefix when min(1, p/q) > tau (strict, Section 3.2 and Algorithm 1);
     MMTAD passes a node when p/q** >= tau (Eq. 9).  tau = 0 is legal and passes everything.
   * All prefixes are examined: a failing prefix does not stop longer ones from passing.
-  * q is the raw (unwarped) joint likelihood the beam search stored (Section 2.1).
+  * q is the raw (unwarped) joint likelihood the beam search stored (Section 2.1), unless
+    warping is asked for: then every next-token distribution of both models is warped as
+    the appendix "Hyper-parameter Details" describes (keep the top_k most likely tokens
+    and normalise; then, in descending order, keep the shortest prefix whose cumulative
+    probability exceeds top_p; read as: and normalise again), the beam search scores with
+    log q~, verification gathers log p~ (minus infinity for a draft token outside the
+    target's support) and the bonus token is drawn from p~ (footnote of Section 3.2: it is
+    equally valid to approximate p~ with q~).  A beam step with fewer than b candidates of
+    non-zero likelihood fills the remaining beams with zero-likelihood candidates in index
+    order; they can never be x**, and MMTAD judges them like any other node.
   * Deterministic beam search keeps the b best candidates (last sentence of Section 2.1);
     ties go to the lowest flat index beam*V + token; survivors are listed best first.
     Stochastic beam sampling draws b distinct candidates in proportion to p_beam (Eq. 2)
@@ -47,6 +56,37 @@ def perplexity(logp_tokens):
     return float(np.exp(-np.mean(np.asarray(logp_tokens, dtype=np.float64))))
 
 
+def warp_log_probs(logits_row, top_k, top_p, dt=np.float64):
+    """log p~ of one next-token distribution (appendix "Hyper-parameter Details"): (1) the top_k most likely
+    tokens keep their probabilities, the others get 0, normalise; (2) in descending order keep the first K tokens
+    whose cumulative probability is larger than top_p (the smallest such K; all top_k tokens if it never is),
+    the others get 0; normalise.  Equal logits rank by token id.  Sums run in descending order of probability.
+    Returns (row of log p~ with -inf outside the support, margin): margin = how far the two integer decisions
+    are from flipping (gap between the last kept and the first dropped logit of step 1, distance of the
+    nearest cumulative probability from top_p)."""
+    x = np.asarray(logits_row).astype(dt)
+    V = x.size
+    k = min(int(top_k), V)
+    order = top_b(x, min(k + 1, V))
+    gap = float(x[order[k - 1]] - x[order[k]]) if V > k else np.inf
+    top = order[:k]
+    e = np.exp(x[top] - x[top[0]])
+    p = e / np.cumsum(e)[-1]                         # step 1: normalised over the top_k tokens
+    c = np.cumsum(p)
+    over = np.nonzero(c > dt(top_p))[0]
+    K = int(over[0]) + 1 if over.size else k
+    margin = min(gap, float(np.min(np.abs(c.astype(np.float64) - float(dt(top_p))))))
+    out = np.full(V, -np.inf, dtype=dt)
+    out[top[:K]] = np.log(p[:K] / np.cumsum(p[:K])[-1])
+    return out, margin
+
+
+def warp_rows(rows, warp, dt=np.float64):
+    """warp_log_probs of every row; warp = (top_k, top_p).  Returns (rows of log p~, smallest margin)."""
+    out = [warp_log_probs(r, warp[0], warp[1], dt) for r in rows]
+    return np.stack([o[0] for o in out]), min(o[1] for o in out)
+
+
 def top_b(keys, b):
     """Indices of the b largest keys, best first; equal keys: lowest index first."""
     keys = np.asarray(keys)
@@ -56,7 +96,7 @@ def top_b(keys, b):
 
 # ---- draft: beam sampling on the auxiliary model (Section 2.1, Eq. 2) --------------------
 
-def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=np.float64):
+def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=np.float64, warp=None):
     """gamma beam steps from the session's context.  Returns a history dict with, per step
     i and survivor j: tok[i][j], parent[i][j] (index of the beam it extends in step i-1; 0 at
     step 0 where the only beam is the context), score[i][j] = log q(branch | context), and
@@ -67,12 +107,18 @@ def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=
     live_score = np.zeros(1, dtype=dt)
     live_node = [-1]
     n0 = len(session.context)
-    hist = {"tok": [], "parent": [], "score": [], "node": [], "margin": []}
+    hist = {"tok": [], "parent": [], "score": [], "node": [], "margin": [], "warp_margin": []}
     for i in range(gamma):
         logits = live_rows.astype(dt)
         V = logits.shape[1]
-        _, lse = log_softmax_rows(live_rows)
-        cand = live_score[:, None] + (logits - lse.astype(dt)[:, None])      # joint log q of every extension
+        if warp is None:
+            _, lse = log_softmax_rows(live_rows)
+            logq = logits - lse.astype(dt)[:, None]
+            hist["warp_margin"].append(np.inf)
+        else:
+            logq, wm = warp_rows(logits, warp, dt)
+            hist["warp_margin"].append(wm)
+        cand = live_score[:, None] + logq                                    # joint log q of every extension
         flat = cand.ravel()
         if stochastic:
             g = rng.gumbel(seed, rng.stream_id(seq_index, rng.STREAM_BEAM), n0 + i, np.arange(flat.size))
@@ -151,21 +197,27 @@ def ancestor_masks(parent):
 
 # ---- verification by the target model (Algorithm 1, P = M_p(input, X); Section 3.3) -------
 
-def verify(session, tree):
+def verify(session, tree, warp=None, dt=np.float64):
     """Target logits after the root and after every tree node, the conditional log-likelihood
-    of every node's token given its branch, and the joint log p of every branch."""
+    of every node's token given its branch, and the joint log p of every branch.  With warp =
+    (top_k, top_p) the rows returned as "logits" are the rows of log p~ (their logsumexp is 0)."""
     M = len(tree["tok"])
     base = len(session.node_tok)                 # row r >= 1 becomes session node base + r - 1
     rows, ids = session.tree_logits([-1 if p == 0 else base + int(p) - 1 for p in tree["parent"][1:]],
                                     tree["tok"][1:])
-    logp, lse = log_softmax_rows(rows)
+    wm = np.inf
+    if warp is None:
+        logp, lse = log_softmax_rows(rows)
+    else:
+        rows, wm = warp_rows(np.asarray(rows).astype(dt), warp, dt)
+        logp, lse = rows, np.zeros(len(rows))
     cond = np.zeros(M)
     joint = np.zeros(M)
     for c in range(1, M):
         p = int(tree["parent"][c])
         cond[c] = logp[p, tree["tok"][c]]
         joint[c] = joint[p] + cond[c]
-    return {"logits": rows, "lse": lse, "logp_cond": cond, "logp_joint": joint, "node_ids": [-1] + list(ids)}
+    return {"logits": rows, "lse": lse, "logp_cond": cond, "logp_joint": joint, "node_ids": [-1] + list(ids), "warp_margin": wm}
 
 
 def joint_from_cond(tree, cond, dt=np.float64):
@@ -183,6 +235,12 @@ def _log_tau(tau, dt):
         return np.log(dt(tau)).astype(dt) if tau > 0 else dt(-np.inf)
 
 
+def _margin(log_ratio, log_tau):
+    """Distance of a log ratio from the threshold; infinite when either is (a zero likelihood cannot flip)."""
+    d = float(log_ratio) - float(log_tau)
+    return abs(d) if np.isfinite(d) else np.inf
+
+
 def accept_mtad(tree, joint, tau, dt=np.float64):
     """Longest prefix i of the chain with min(1, p_i/q_i) > tau; eta = 0 if none."""
     log_tau = _log_tau(tau, dt)
@@ -192,7 +250,7 @@ def accept_mtad(tree, joint, tau, dt=np.float64):
     for c in range(1, len(tree["tok"])):
         i = int(tree["depth"][c])
         ratio = min(dt(0), joint[c] - qref[i - 1])          # log min(1, p/q)
-        margins.append(abs(float(joint[c] - qref[i - 1]) - float(log_tau)))
+        margins.append(_margin(joint[c] - qref[i - 1], log_tau))
         if ratio > log_tau:
             eta, node = i, c                                  # all prefixes are examined; the longest wins
     return eta, node, margins
@@ -206,7 +264,7 @@ def accept_mmtad(tree, joint, tau, dt=np.float64):
     best, margins = (0, -np.inf, 0), []
     for c in range(1, len(tree["tok"])):
         i = int(tree["depth"][c])
-        margins.append(abs(float(joint[c] - qref[i - 1]) - float(log_tau)))
+        margins.append(_margin(joint[c] - qref[i - 1], log_tau))
         if joint[c] - qref[i - 1] >= log_tau:
             if i > best[0] or (i == best[0] and joint[c] > best[1]):
                 best = (i, joint[c], c)
@@ -237,14 +295,14 @@ def bonus_token(logits_row, *, sample, seed=0, seq_index=0, position=0, dt=np.fl
 # ---- one iteration and the loop -------------------------------------------------------------
 
 def iteration(sq, sp, *, gamma, beam, mode, tau, stochastic_beam=False, sample_bonus=True, seed=0,
-              seq_index=0, dt=np.float64):
+              seq_index=0, dt=np.float64, warp=None):
     """One iteration on draft session sq and target session sp (both hold the same context).
     Returns a trace; both sessions end with the context extended by [x_1..x_eta, t]."""
     assert sq.context == sp.context
     n = len(sp.context)
-    hist = beam_search(sq, gamma, beam, stochastic=stochastic_beam, seed=seed, seq_index=seq_index, dt=dt)
+    hist = beam_search(sq, gamma, beam, stochastic=stochastic_beam, seed=seed, seq_index=seq_index, dt=dt, warp=warp)
     tree = build_tree(hist, mode)
-    ver = verify(sp, tree)
+    ver = verify(sp, tree, warp=warp, dt=dt)
     joint = joint_from_cond(tree, ver["logp_cond"].astype(dt), dt)
     eta, node, margins = (accept_mtad if mode == "mtad" else accept_mmtad)(tree, joint, tau, dt)
     rows = branch_rows(tree, node)

@@ -331,3 +331,94 @@ def test_cached_and_recompute_sessions_give_the_same_run():
 
 def test_perplexity_eq1():
     assert np.isclose(mtad.perplexity(np.log([0.5, 0.25, 0.5])), (0.5 * 0.25 * 0.5) ** (-1 / 3))
+
+
+# ---- warped distributions (appendix "Hyper-parameter Details") --------------------------------
+
+def test_warp_worked_example_by_hand():
+    """12 tokens with the probabilities below.  Step 1 keeps the ten largest (their sum is 0.99) and normalises;
+    the cumulative sums 0.40, 0.65, 0.80, 0.88, 0.92 (each / 0.99) first exceed 0.9 at the fifth token, so step 2
+    keeps five tokens; normalised again they are 0.40, 0.25, 0.15, 0.08, 0.04 over 0.92."""
+    p = np.array([0.02, 0.40, 0.005, 0.25, 0.01, 0.15, 0.08, 0.01, 0.04, 0.02, 0.01, 0.005])
+    assert np.isclose(p.sum(), 1.0)
+    lw, margin = mtad.warp_log_probs(np.log(p) + 2.5, 10, 0.9)       # any shift of the logits: the same distribution
+    want = np.zeros(12)
+    want[[1, 3, 5, 6, 8]] = np.array([0.40, 0.25, 0.15, 0.08, 0.04]) / 0.92
+    assert np.allclose(np.exp(lw), want, atol=1e-12)
+    assert np.all(np.isneginf(lw[want == 0]))
+    assert np.isclose(margin, (0.88 / 0.99 - 0.9) * -1)             # the nearest cumulative sum is 0.88/0.99
+
+
+def test_warp_support_matches_exact_rational_arithmetic():
+    """Probabilities that are ratios of integers: the two integer decisions (which top_k tokens, how long the top_p
+    prefix) are recomputed with exact fractions; the kept tokens keep their mutual ratios and sum to one."""
+    from fractions import Fraction
+    g = np.random.default_rng(5)
+    for trial in range(200):
+        V = int(g.integers(3, 40))
+        top_k = int(g.integers(1, 14))
+        top_p = Fraction(int(g.integers(1, 20)), 20)               # 0.05 .. 0.95
+        n = g.permutation(np.arange(1, 5 * V + 1))[:V].astype(np.int64)   # distinct counts: no ties
+        if trial % 4 == 0:
+            n[int(g.integers(V))] = 50 * n.sum()                    # one token above every threshold: support of one
+        lw, _ = mtad.warp_log_probs(np.log(n.astype(np.float64)), top_k, float(top_p))
+        order = sorted(range(V), key=lambda i: -n[i])[:min(top_k, V)]
+        tot = sum(int(n[i]) for i in order)
+        cum, K = Fraction(0), len(order)
+        for r, i in enumerate(order):
+            cum += Fraction(int(n[i]), tot)
+            if cum > top_p:
+                K = r + 1
+                break
+        keep = order[:K]
+        if any(abs(float(sum(Fraction(int(n[i]), tot) for i in order[:r + 1]) - top_p)) < 1e-9 for r in range(len(order))):
+            continue                                                 # a cumulative sum exactly on the threshold: either side is rounding
+        assert sorted(np.nonzero(np.isfinite(lw))[0]) == sorted(keep), (trial, V, top_k, top_p)
+        kept = sum(int(n[i]) for i in keep)
+        for i in keep:
+            assert np.isclose(np.exp(lw[i]), n[i] / kept, rtol=1e-12)
+
+
+def test_warp_ties_rank_by_token_id_and_short_vocabularies():
+    lw, _ = mtad.warp_log_probs(np.zeros(6), 3, 0.99)               # six equal tokens, keep three: ids 0, 1, 2
+    assert list(np.nonzero(np.isfinite(lw))[0]) == [0, 1, 2] and np.allclose(np.exp(lw[:3]), 1 / 3)
+    lw, _ = mtad.warp_log_probs(np.array([0.3, -1.0]), 10, 0.5)     # fewer tokens than top_k
+    assert np.isfinite(lw[0]) and np.isneginf(lw[1]) and lw[0] == 0.0
+
+
+def test_warp_that_keeps_everything_is_the_unwarped_method():
+    """top_k = |V| and a top_p no cumulative sum exceeds keep every token: p~ = p, and the warped iteration takes the
+    decisions of the plain one (scores agree to rounding)."""
+    V, gamma = 9, 3
+    fq, fp = table_lm(V, 41, temp=1.5), table_lm(V, 42, temp=1.5)
+    for mode in ("mtad", "mmtad"):
+        for seed in range(5):
+            kw = dict(gamma=gamma, beam=3, mode=mode, tau=0.3, stochastic_beam=True, sample_bonus=True, seed=seed)
+            a = mtad.iteration(TableSession(fq, (1, 2)), TableSession(fp, (1, 2)), **kw)
+            b = mtad.iteration(TableSession(fq, (1, 2)), TableSession(fp, (1, 2)), warp=(V, 1.5), **kw)
+            assert np.array_equal(a["hist"]["tok"], b["hist"]["tok"]) and np.array_equal(a["hist"]["parent"], b["hist"]["parent"])
+            assert np.allclose(a["hist"]["score"], b["hist"]["score"]) and np.allclose(a["joint"], b["joint"])
+            assert a["eta"] == b["eta"] and a["node"] == b["node"] and a["emitted"] == b["emitted"]
+
+
+def test_warped_iteration_stays_inside_the_supports():
+    """Every drafted token lies in the draft's warped support of its step (finite score) as long as the beam is no
+    wider than the support; a drafted token outside the target's support has zero target likelihood and cannot pass
+    a positive threshold; the bonus token lies in the target's support of its row."""
+    V, gamma, b = 30, 4, 2
+    fq, fp = table_lm(V, 51, temp=3.0), table_lm(V, 52, temp=3.0)
+    seen_reject = False
+    for seed in range(40):
+        tr = mtad.iteration(TableSession(fq, (3,)), TableSession(fp, (3,)), gamma=gamma, beam=b, mode="mmtad", tau=0.05,
+                            stochastic_beam=True, sample_bonus=True, seed=seed, warp=(4, 0.8))
+        assert np.isfinite(tr["verify"]["logits"][tr["node"], tr["bonus"]])
+        finite = np.isfinite(tr["verify"]["logits"]).sum(axis=1)
+        assert np.all(finite >= 1) and np.all(finite <= 4)
+        assert np.allclose(np.exp(tr["verify"]["logits"]).sum(axis=1), 1.0)
+        for c in range(1, len(tr["tree"]["tok"])):
+            if np.isneginf(tr["joint"][c]):
+                seen_reject = True
+                assert c not in tr["path_rows"]
+        for r in tr["path_rows"]:
+            assert np.isfinite(tr["joint"][r])
+    assert seen_reject
