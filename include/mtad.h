@@ -144,11 +144,20 @@ void mtad_destroy(mtad_ctx *ctx);
  * any hot call.  The contents need no initialisation.  ECAP if too small. */
 size_t mtad_workspace_bytes(const mtad_ctx *ctx);
 int mtad_bind_workspace(mtad_ctx *ctx, void *device_buf, size_t bytes);
-/* bf16 models with at most 32 rows in a pass run all layers of a pass in one persistent kernel (one workgroup per
- * compute unit, software grid barriers with bounded waits; a wait that gives up sets status bit 3).  on = 0 selects
- * one kernel per product instead (same arithmetic; used for comparison and as the path for larger passes).
- * Default on; the environment variable MTAD_PERSISTENT=0 turns it off at context creation. */
+/* on != 0: bf16 models with at most 32 rows in a pass run all layers of a pass in one persistent kernel (one workgroup
+ * per compute unit, software grid barriers with bounded waits; a wait that gives up sets status bit 3).  Default off
+ * (one kernel per product: same arithmetic, and faster on this machine); the environment variable MTAD_PERSISTENT=1
+ * turns it on at context creation. */
 int mtad_set_persistent(mtad_ctx *ctx, int32_t on);
+/* Warped distributions (appendix "Hyper-parameter Details"; the footnote of Section 3.2 allows approximating p~ with
+ * q~): with top_k > 0 every next-token distribution of both models is warped before it is used: the top_k most likely
+ * tokens keep their probabilities and are normalised; of those, in descending order, the shortest prefix whose cumulative
+ * probability exceeds top_p is kept and normalised again.  mtad_draft_beam_step then scores with log q~;
+ * mtad_verify_tree returns rows of log p~ in `logits` (minus infinity outside the support), 0 in `row_lse`, and
+ * log p~ of the draft tokens in `logp_cond` (minus infinity for a token outside the target's support: such a branch
+ * passes no positive threshold); mtad_accept, given those rows, draws the bonus token from p~.  1 <= top_k <= 16,
+ * top_p > 0 (a top_p of 1 or more keeps all top_k tokens); top_k = 0 turns warping off (the default). */
+int mtad_set_warp(mtad_ctx *ctx, int32_t top_k, float top_p);
 const char *mtad_strerror(int status);
 int mtad_last_hip_error(const mtad_ctx *ctx); /* hipError_t of the last failed HIP call, 0 if none */
 /* Copies the sticky device status word to *host_bits after synchronising `stream` (the only call that

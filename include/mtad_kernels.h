@@ -34,6 +34,10 @@ int mtad_k_rmsnorm(int32_t dtype, const float *h, const float *g, void *out, int
 /* lse[row] = log sum_v exp(logits[row][v]) (the normaliser that turns a logits row into a row of P, Algorithm 1). */
 int mtad_k_row_lse(const float *logits, float *lse, int32_t rows, int32_t vocab, void *stream);
 
+/* The warping step of mtad_set_warp on given rows, in place: logits [rows][vocab] become rows of log p~ (minus infinity
+ * outside the support), lse[row] becomes 0.  1 <= top_k <= 16, top_p > 0. */
+int mtad_k_warp_rows(float *logits, float *lse, int32_t rows, int32_t vocab, int32_t top_k, float top_p, void *stream);
+
 /* The selection part of one beam step (Section 2.1, Eq. 2) on given draft logits [batch][rows_per_seq][vocab] and
  * their row logsumexps: candidate (r, v) scores hist.cum_logq[step-1][r] + (logits[r][v] - lse[r]) (at step 0 the
  * only live beam is row catchup_cnt-1 with score 0); writes hist[.][step][.].  `len` = committed draft tokens per

@@ -127,7 +127,10 @@ def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=
             key = flat
         k = min(b, flat.size)                    # a step has fewer than b candidates only if b > |V| (tests)
         sel = top_b(key, k + 1)
-        margin = float(key[sel[k - 1]] - key[sel[k]]) if len(sel) > k else np.inf
+        with np.errstate(invalid="ignore"):
+            margin = float(key[sel[k - 1]] - key[sel[k]]) if len(sel) > k else np.inf
+        if not np.isfinite(margin):
+            margin = np.inf if np.isfinite(key[sel[k - 1]]) else 0.0     # zero-likelihood beams: chosen by index alone
         sel = sel[:k]
         parent, tok = sel // V, sel % V
         score = flat[sel]

@@ -17,9 +17,9 @@ MTAD_MODE_MTAD, MTAD_MODE_MMTAD = 0, 1
 MTAD_MAX_ROWS, MTAD_MAX_BEAM = 64, 8
 
 EXPORTS = ["mtad_create", "mtad_destroy", "mtad_workspace_bytes", "mtad_bind_workspace", "mtad_strerror",
-           "mtad_last_hip_error", "mtad_device_status", "mtad_set_persistent", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
+           "mtad_last_hip_error", "mtad_device_status", "mtad_set_persistent", "mtad_set_warp", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
            "mtad_verify_tree", "mtad_accept", "mtad_kv_commit",
-           "mtad_k_gemm", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_beam_topb", "mtad_k_copy"]
+           "mtad_k_gemm", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_copy"]
 
 i32, u64, f32, vp = C.c_int32, C.c_uint64, C.c_float, C.c_void_p
 
@@ -82,6 +82,7 @@ def lib():
         L.mtad_last_hip_error.argtypes = [vp]
         L.mtad_device_status.argtypes = [vp, P(C.c_uint32), vp]
         L.mtad_set_persistent.argtypes = [vp, i32]
+        L.mtad_set_warp.argtypes = [vp, i32, f32]
         L.mtad_pack_matrix.argtypes = [i32, vp, vp, i32, i32, i32, vp]
         L.mtad_prefill.argtypes = [vp, P(mtad_model), P(mtad_kv), vp, i32, vp]
         L.mtad_draft_beam_step.argtypes = [vp, P(mtad_model), P(mtad_kv), P(mtad_beam), i32, P(mtad_state), i32, u64, vp]
@@ -92,6 +93,7 @@ def lib():
         L.mtad_k_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.mtad_k_rmsnorm.argtypes = [i32, vp, vp, vp, i32, i32, f32, vp]
         L.mtad_k_row_lse.argtypes = [vp, vp, i32, i32, vp]
+        L.mtad_k_warp_rows.argtypes = [vp, vp, i32, i32, i32, f32, vp]
         L.mtad_k_copy.argtypes = [vp, vp, C.c_int64, vp]
         L.mtad_k_beam_topb.argtypes = [vp, vp, vp, P(mtad_beam), i32, vp, vp, i32, i32, i32, u64, vp]
         for name in EXPORTS:
@@ -136,6 +138,14 @@ def mtad_workspace_bytes(ctx) -> int:
 
 def mtad_bind_workspace(ctx, buf: torch.Tensor):
     _check("mtad_bind_workspace", lib().mtad_bind_workspace(ctx, ptr(buf), buf.numel() * buf.element_size()))
+
+
+def mtad_set_warp(ctx, top_k: int, top_p: float):
+    _check("mtad_set_warp", lib().mtad_set_warp(ctx, int(top_k), f32(top_p)))
+
+
+def mtad_k_warp_rows(logits, lse, rows, vocab, top_k, top_p, stream=None):
+    _check("mtad_k_warp_rows", lib().mtad_k_warp_rows(ptr(logits), ptr(lse), rows, vocab, int(top_k), f32(top_p), _stream_ptr(stream)))
 
 
 def mtad_set_persistent(ctx, on: bool):

@@ -33,6 +33,8 @@ hipError_t launch_topb(const float* logits, const float* lse, BeamView hist, con
                        int B, int R, int gamma, int beam, int V, int sample, uint64_t seed, float* part_key, int* part_idx, int G,
                        hipStream_t s);
 hipError_t launch_build_tree(BeamView hist, TreeView tree, int B, int gamma, int beam, int mode, hipStream_t s);
+// rows of logits -> rows of log p~ (top_k, then top_p prefix; 1 <= top_k <= 16), lse -> 0; in place
+hipError_t launch_warp_rows(float* logits, float* lse, int rows, int V, int top_k, float top_p, hipStream_t s);
 hipError_t launch_gather_logp(const float* logits, const float* lse, TreeView tree, int B, int V, float* logp_cond, hipStream_t s);
 hipError_t launch_accept(TreeView tree, const float* logp_cond, const float* logits, int V, const int32_t* len, float log_tau, int mode,
                          int B, int gamma, int sample, uint64_t seed, AcceptView out, hipStream_t s);

@@ -207,6 +207,31 @@ __device__ __forceinline__ void block_best(float& k, int& i, float* shk, int* sh
     if (better(shk[w], shi[w], k, i)) { k = shk[w]; i = shi[w]; }
 }
 
+// The same for a workgroup of exactly 1024 threads with the second level on the shuffle network of wave 0 (16 entries):
+// shorter than 15 serial comparisons in every thread when it runs many times in a row.  shk, shi: 17 entries.
+__device__ __forceinline__ void block_best_1024(float& k, int& i, float* shk, int* shi) {
+  for (int off = 32; off > 0; off >>= 1) {
+    const float ok = __shfl_xor(k, off, 64);
+    const int oi = __shfl_xor(i, off, 64);
+    if (better(ok, oi, k, i)) { k = ok; i = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { shk[threadIdx.x >> 6] = k; shi[threadIdx.x >> 6] = i; }
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float k2 = shk[threadIdx.x & 15];
+    int i2 = shi[threadIdx.x & 15];
+    for (int off = 8; off > 0; off >>= 1) {
+      const float ok = __shfl_xor(k2, off, 64);
+      const int oi = __shfl_xor(i2, off, 64);
+      if (better(ok, oi, k2, i2)) { k2 = ok; i2 = oi; }
+    }
+    if (threadIdx.x == 0) { shk[16] = k2; shi[16] = i2; }
+  }
+  __syncthreads();
+  k = shk[16];
+  i = shi[16];
+}
+
 // b rounds of "best head wins and is popped"; thread 0 receives the winners in order
 __device__ __forceinline__ void block_merge(TopList& L, int b, float* out_key, int* out_idx, float* shk, int* shi) {
   for (int j = 0; j < b; ++j) {
@@ -451,6 +476,93 @@ __global__ __launch_bounds__(1024) void accept_kernel(TreeView tree, const float
 hipError_t launch_accept(TreeView tree, const float* logp_cond, const float* logits, int V, const int32_t* len, float log_tau, int mode,
                          int B, int gamma, int sample, uint64_t seed, AcceptView out, hipStream_t s) {
   hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(1024), 0, s, tree, logp_cond, logits, V, len, log_tau, mode, gamma, sample, seed, out);
+  return hipGetLastError();
+}
+
+// ---- warped distributions -------------------------------------------------------------------------------------
+
+// One workgroup per logits row: the row becomes the row of log p~ of the warped distribution (appendix
+// "Hyper-parameter Details": the top_k most likely tokens, normalised; of those, in descending order, the shortest
+// prefix whose cumulative probability exceeds top_p; normalised again), minus infinity outside the support, and the
+// row's logsumexp becomes 0, so that every consumer of (logits, lse) rows works on p~ unchanged.  The top_k tokens
+// are found by top_k rounds of a workgroup-wide argmax over every thread's best remaining entry; after a round only the
+// winner's owner looks for its next best, among its entries that rank after the winner (value descending, token id
+// ascending): no bookkeeping of removed entries.  The ten-element arithmetic runs on one thread
+// in a fixed order (float32, sums in descending order of probability).
+constexpr int WARP_MAXK = 16;
+__global__ __launch_bounds__(1024) void warp_rows_kernel(float* __restrict__ logits, float* __restrict__ lse, int V, int top_k, float top_p) {
+  __shared__ float shk[17];
+  __shared__ int shi[17];
+  __shared__ float tv[WARP_MAXK];
+  __shared__ int ti[WARP_MAXK];
+  __shared__ int keep_s;
+  float* row = logits + (int64_t)blockIdx.x * V;
+  const int k = min(min(top_k, WARP_MAXK), V);
+  // the first 32768 entries of the row live in registers for all rounds (entry tid + 1024*j in x[j]); longer rows read
+  // the rest from memory in every round
+  constexpr int PT = 32;
+  float x[PT];
+#pragma unroll
+  for (int j = 0; j < PT; ++j) {
+    const int v = (int)threadIdx.x + 1024 * j;
+    float t = v < V ? row[v] : -INFINITY;
+    x[j] = (t == t) ? t : -INFINITY;                                // a NaN logit ranks last
+  }
+  // this thread's best entry among those that rank after (pv, pi) (value descending, token id ascending)
+  auto local_best = [&](float pv, int pi, float& bk, int& bi) {
+    bk = -INFINITY;
+    bi = 0x7FFFFFFF;
+#pragma unroll
+    for (int j = 0; j < PT; ++j) {
+      const int v = (int)threadIdx.x + 1024 * j;
+      const bool after = x[j] < pv || (x[j] == pv && v > pi);
+      if (v < V && after && better(x[j], v, bk, bi)) { bk = x[j]; bi = v; }
+    }
+    for (int v = (int)threadIdx.x + 1024 * PT; v < V; v += 1024) {
+      float t = row[v];
+      if (!(t == t)) t = -INFINITY;
+      const bool after = t < pv || (t == pv && v > pi);
+      if (after && better(t, v, bk, bi)) { bk = t; bi = v; }
+    }
+  };
+  float lk;
+  int li;
+  local_best(INFINITY, -1, lk, li);
+  for (int r = 0; r < k; ++r) {
+    float bk = lk;
+    int bi = li;
+    block_best_1024(bk, bi, shk, shi);  // its first barrier also orders this round after the previous round's reads
+    if (threadIdx.x == 0) { tv[r] = bk; ti[r] = bi; }
+    // only the winner's owner has lost its best entry: all its other entries rank after the winner
+    if (li == bi && bi != 0x7FFFFFFF) local_best(bk, bi, lk, li);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float e[WARP_MAXK], p[WARP_MAXK];
+    float S = 0.f;
+    for (int i = 0; i < k; ++i) { e[i] = expf(tv[i] - tv[0]); S += e[i]; }
+    float c = 0.f;
+    int K = k;
+    for (int i = 0; i < k; ++i) {
+      p[i] = e[i] / S;
+      c += p[i];
+      if (K == k && c > top_p) K = i + 1;
+    }
+    float s2 = 0.f;
+    for (int i = 0; i < K; ++i) s2 += p[i];
+    for (int i = 0; i < K; ++i) tv[i] = logf(p[i] / s2);
+    keep_s = K;
+    lse[blockIdx.x] = 0.f;
+  }
+  __syncthreads();
+  for (int v = threadIdx.x; v < V; v += (int)blockDim.x) row[v] = -INFINITY;
+  __syncthreads();
+  if ((int)threadIdx.x < keep_s && ti[threadIdx.x] >= 0 && ti[threadIdx.x] < V) row[ti[threadIdx.x]] = tv[threadIdx.x];
+}
+
+hipError_t launch_warp_rows(float* logits, float* lse, int rows, int V, int top_k, float top_p, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(warp_rows_kernel, dim3(rows), dim3(1024), 0, s, logits, lse, V, top_k, top_p);
   return hipGetLastError();
 }
 

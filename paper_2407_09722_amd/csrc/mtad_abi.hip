@@ -29,6 +29,8 @@ struct mtad_ctx {
   float* gemm_part;  // k-split partial sums of the product kernel (products with few strips, more than 8 rows)
   int* gemm_cnt;
   int gemm_cnt_n;
+  int warp_k;      // > 0: next-token distributions of both models are warped (mtad_set_warp)
+  float warp_p;
   bf16_t* gemm_xfrag;  // scratch of the many-row product kernel: a pass's activations in operand-fragment order
   size_t gemm_xfrag_n;
   size_t attn_cnt_n;
@@ -489,6 +491,7 @@ int mtad_draft_beam_step(mtad_ctx* c, const mtad_model* draft, mtad_kv* dkv, mta
                                dkv->page_size * dkv->max_pages, c->status, s));
   int rc = decoder_pass(c, draft, dkv, R, s, c->dlogits, c->lse);
   if (rc) return rc;
+  if (c->warp_k > 0) HIP_TRY(c, launch_warp_rows(c->dlogits, c->lse, B * R, draft->vocab, c->warp_k, c->warp_p, s));
   HIP_TRY(c, launch_topb(c->dlogits, c->lse, hv, st->catchup_cnt, dkv->len, step, B, R, gamma, beam, draft->vocab, sample_beam ? 1 : 0,
                          seed, c->part_key, c->part_idx, TOPB_BLOCKS, s));
   return MTAD_OK;
@@ -514,14 +517,15 @@ int mtad_verify_tree(mtad_ctx* c, const mtad_model* target, mtad_kv* tkv, const 
   hipStream_t s = (hipStream_t)stream;
   const int B = c->cfg.batch, M = tree->M;
   HIP_TRY(c, launch_verify_rows(c->rd, tkv->len, root_tok, tview(tree), B, tkv->page_size * tkv->max_pages, c->status, s));
-  c->gather_tree = tree;
-  c->gather_out = logp_cond;
+  c->gather_tree = c->warp_k > 0 ? nullptr : tree;  // warped rows are gathered after the warp
+  c->gather_out = c->warp_k > 0 ? nullptr : logp_cond;
   int rc = decoder_pass(c, target, tkv, M, s, logits, row_lse);
   const bool gathered = c->gather_out == nullptr;
   c->gather_tree = nullptr;
   c->gather_out = nullptr;
   if (rc) return rc;
-  if (!gathered) HIP_TRY(c, launch_gather_logp(logits, row_lse, tview(tree), B, target->vocab, logp_cond, s));
+  if (c->warp_k > 0) HIP_TRY(c, launch_warp_rows(logits, row_lse, B * M, target->vocab, c->warp_k, c->warp_p, s));
+  if (!gathered || c->warp_k > 0) HIP_TRY(c, launch_gather_logp(logits, row_lse, tview(tree), B, target->vocab, logp_cond, s));
   return MTAD_OK;
 }
 
@@ -564,6 +568,19 @@ int mtad_kv_commit(mtad_ctx* c, mtad_kv* tkv, mtad_kv* dkv, const mtad_tree* tre
 #ifdef MTAD_PASS_PROFILE
 extern "C" void* mtad_pass_profile(mtad_ctx* c) { return c ? c->prof : nullptr; }
 #endif
+
+int mtad_set_warp(mtad_ctx* c, int32_t top_k, float top_p) {
+  if (!c) return MTAD_EINVAL;
+  if (top_k < 0 || top_k > 16 || (top_k > 0 && !(top_p > 0.f))) return MTAD_EINVAL;
+  c->warp_k = top_k;
+  c->warp_p = top_p;
+  return MTAD_OK;
+}
+
+int mtad_k_warp_rows(float* logits, float* lse, int32_t rows, int32_t vocab, int32_t top_k, float top_p, void* stream) {
+  if (!logits || !lse || rows < 1 || vocab < 1 || top_k < 1 || top_k > 16 || !(top_p > 0.f)) return MTAD_EINVAL;
+  return launch_warp_rows(logits, lse, rows, vocab, top_k, top_p, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
+}
 
 int mtad_set_persistent(mtad_ctx* c, int32_t on) {
   if (!c) return MTAD_EINVAL;

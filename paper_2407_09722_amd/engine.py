@@ -92,7 +92,7 @@ class Engine:
     """One (target, draft) pair, one batch: buffers + the per-iteration call sequence."""
 
     def __init__(self, target: DeviceModel, draft: DeviceModel, *, batch, gamma, beam, mode, max_context,
-                 prefill_rows=64, page_size=16, device="cuda:0", kv_seed=0, persistent=None):
+                 prefill_rows=64, page_size=16, device="cuda:0", kv_seed=0, persistent=None, warp=None):
         self.target, self.draft = target, draft
         self.B, self.gamma, self.beam = batch, gamma, beam
         self.mode = mb.MTAD_MODE_MTAD if mode in ("mtad", 0) else mb.MTAD_MODE_MMTAD
@@ -105,6 +105,8 @@ class Engine:
         mb.mtad_bind_workspace(self.ctx, self.workspace)
         if persistent is not None:
             mb.mtad_set_persistent(self.ctx, persistent)
+        if warp is not None:                                # (top_k, top_p): both models' distributions are warped
+            mb.mtad_set_warp(self.ctx, warp[0], warp[1])
         self.tkv = DeviceKV(target.shape, batch, max_context, page_size, device, seed=kv_seed)
         self.dkv = DeviceKV(draft.shape, batch, max_context, page_size, device, seed=kv_seed + 1)
         i32 = dict(dtype=torch.int32, device=device)

@@ -21,6 +21,9 @@ def logit_tolerance(dtype):
 def close(got, want, dtype, what=""):
     rtol, atol = logit_tolerance(dtype)
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    same_inf = np.isinf(got) & (got == want)               # zero likelihoods (warped rows): equal infinities agree
+    assert np.array_equal(np.isinf(got), np.isinf(want)), f"{what}: infinities in different places"
+    got, want = np.where(same_inf, 0.0, got), np.where(same_inf, 0.0, want)
     err = np.abs(got - want)
     lim = atol + rtol * np.abs(want)
     assert np.all(err <= lim), f"{what}: max err {err.max():.3e} (limit {lim.flat[int(np.argmax(err - lim))]:.3e})"
@@ -29,7 +32,7 @@ def close(got, want, dtype, what=""):
 
 def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, tau, sample_bonus=True,
              sample_beam=False, seed=0, max_context=None, page_size=16, prefill_rows=64, check_kv=False,
-             max_iters=None, device="cuda:0", persistent=None):
+             max_iters=None, device="cuda:0", persistent=None, warp=None):
     from paper_2407_09722_amd.engine import DeviceModel, Engine
     prompt = np.asarray(prompt, np.int32)
     B, n0 = prompt.shape
@@ -37,7 +40,8 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
     M = 1 + (gamma if mode == "mtad" else gamma * beam)
     max_context = max_context or (n0 + new_tokens + 2 * (gamma + 1) + M + 8)
     eng = Engine(DeviceModel(tshape, wt, device), DeviceModel(dshape, wd, device), batch=B, gamma=gamma, beam=beam,
-                 mode=mode, max_context=max_context, prefill_rows=prefill_rows, page_size=page_size, device=device, persistent=persistent)
+                 mode=mode, max_context=max_context, prefill_rows=prefill_rows, page_size=page_size, device=device, persistent=persistent,
+                 warp=warp)
     lm_p, lm_q = DecoderLM(tshape, wt), DecoderLM(dshape, wd)
     sp = [CachedSession(lm_p, list(prompt[s])) for s in range(B)]
     sq = [CachedSession(lm_q, list(prompt[s])) for s in range(B)]
@@ -62,16 +66,17 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
             if not alive[s]:
                 continue
             tr = mtad.iteration(sq[s], sp[s], gamma=gamma, beam=beam, mode=mode, tau=tau, stochastic_beam=sample_beam,
-                                sample_bonus=sample_bonus, seed=seed, seq_index=s, dt=np.float32)
+                                sample_bonus=sample_bonus, seed=seed, seq_index=s, dt=np.float32, warp=warp)
             h = tr["hist"]
             # --- draft: beam history
             for i in range(gamma):
                 same = np.array_equal(g["h_tok"][s, i], h["tok"][i]) and np.array_equal(g["h_parent"][s, i], h["parent"][i])
                 if not same:
-                    assert h["margin"][i] < margin_tol or _near_tie(h["score"][i], margin_tol), \
+                    assert h["margin"][i] < margin_tol or _near_tie(h["score"][i], margin_tol) or h["warp_margin"][i] < margin_tol, \
                         f"seq {s} iter {stats['iters']} beam step {i}: survivors differ, margin {h['margin'][i]}"
                     alive[s] = False
-                    diff = np.abs(np.sort(g["h_cum"][s, i].astype(np.float64)) - np.sort(h["score"][i].astype(np.float64))).max()
+                    with np.errstate(invalid="ignore"):
+                        diff = np.nanmax(np.abs(np.sort(g["h_cum"][s, i].astype(np.float64)) - np.sort(h["score"][i].astype(np.float64))))
                     stats["events"].append(("beam step", stats["iters"], i, float(h["margin"][i]), float(diff)))
                     break
                 close(g["h_cum"][s, i], h["score"][i], dtype, f"cum_logq step {i}")
@@ -86,6 +91,13 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
             close(g["t_qref"][s], t["qref"], dtype, "qref")
             # --- verify
             v = tr["verify"]
+            if warp is not None and not np.array_equal(np.isinf(g["logits"][s]), np.isinf(v["logits"])):
+                # a warped support differs: only where a top-k or top-p decision sits on its threshold
+                assert v["warp_margin"] < margin_tol, f"warped supports differ with margin {v['warp_margin']}"
+                stats["events"].append(("warp support", stats["iters"], float(v["warp_margin"])))
+                alive[s] = False
+                stats["excused"] += 1
+                continue
             stats["max_logit_err"] = max(stats["max_logit_err"], close(g["logits"][s], v["logits"], dtype, "target logits"))
             close(g["row_lse"][s], v["lse"], dtype, "row lse")
             close(g["logp_cond"][s], v["logp_cond"], dtype, "logp_cond")

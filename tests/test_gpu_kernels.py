@@ -96,6 +96,39 @@ def test_gemm_fp32_matches_float64(R, N, K):
     _gemm_case(mb, R, N, K, 0, seed=R + N + K)
 
 
+@pytest.mark.parametrize("rows,V,top_k,top_p", [(37, 32000, 10, 0.9), (5, 1000, 10, 0.9), (3, 7, 10, 0.9), (9, 4099, 16, 0.5), (4, 32000, 1, 0.9), (3, 40001, 10, 0.9),
+                                                (6, 2048, 10, 1.0)])
+def test_warp_rows_matches_oracle(rows, V, top_k, top_p):
+    """Rows of logits -> rows of log p~: same support as the oracle (float32 decisions) unless the oracle reports a decision
+    on its threshold, values to 1e-5, minus infinity elsewhere, lse = 0.  Rows with exact ties, a dominant token
+    (support of one) and NaN entries included."""
+    from oracle import mtad
+    mb = _mb()
+    g = np.random.default_rng(rows * 31 + V)
+    x = (g.standard_normal((rows, V)) * 3.0).astype(np.float32)
+    x[0, : min(V, 12)] = x[0].max() + 1.0                      # twelve-way tie at the top: token ids decide
+    if rows > 1:
+        x[1, V // 2] = x[1].max() + 30.0                       # one token holds all the mass
+    if rows > 2 and V > 20:
+        x[2, 5] = np.nan                                       # ranks last
+    xd = torch.from_numpy(x).to(DEV)
+    lse = torch.full((rows,), 7.0, dtype=torch.float32, device=DEV)
+    mb.mtad_k_warp_rows(xd, lse, rows, V, top_k, top_p)
+    torch.cuda.synchronize()
+    got = xd.cpu().numpy()
+    assert torch.all(lse == 0).item()
+    for r in range(rows):
+        ref = np.where(np.isnan(x[r]), -np.inf, x[r]).astype(np.float32)
+        want, margin = mtad.warp_log_probs(ref, top_k, top_p, dt=np.float32)
+        if not np.array_equal(np.isfinite(got[r]), np.isfinite(want)):
+            assert margin < 1e-5, f"row {r}: supports differ with margin {margin}"
+            continue
+        sup = np.isfinite(want)
+        assert np.all(np.isneginf(got[r][~sup]))
+        assert np.allclose(got[r][sup], want[sup], rtol=1e-5, atol=1e-5), (r, got[r][sup], want[sup])
+        assert abs(np.exp(got[r][sup].astype(np.float64)).sum() - 1.0) < 1e-5
+
+
 def test_lm_head_shape_full_vocab():
     """The 7B-shaped lm_head at its real size, checked on every output."""
     mb = _mb()
