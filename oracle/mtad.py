@@ -325,6 +325,20 @@ def iteration(sq, sp, *, gamma, beam, mode, tau, stochastic_beam=False, sample_b
             "emitted": accepted + [t], "n_before": n}
 
 
+def autoregressive_step(sp, *, sample=True, seed=0, seq_index=0, dt=np.float64, warp=None):
+    """Plain decoding with the target alone (the multinomial-sampling baseline of Section 2.2): one token from the
+    target's next-token distribution (warped if asked), drawn like the bonus token of an iteration that accepted
+    nothing.  Returns a trace; the session's context grows by the token."""
+    n = len(sp.context)
+    rows, _ = sp.tree_logits([], [])
+    wm = np.inf
+    if warp is not None:
+        rows, wm = warp_rows(np.asarray(rows).astype(dt), warp, dt)
+    t, gap = bonus_token(rows[0], sample=sample, seed=seed, seq_index=seq_index, position=n, dt=dt)
+    sp.commit(None, [t])
+    return {"logits": rows[0], "bonus": t, "bonus_gap": gap, "warp_margin": wm, "n_before": n}
+
+
 def generate(make_sq, make_sp, prompt, new_tokens, **kw):
     """Decoding loop (Section 2.2 step 4 applied to MTAD): iterate until new_tokens tokens
     exist; the surplus of the last iteration is cut.  make_sq / make_sp build a session from

@@ -132,6 +132,13 @@ class Engine:
         self.catchup_cnt = torch.ones(B, **i32)
         self.state = mb.mtad_state(mb.ptr(self.root_tok), mb.ptr(self.catchup_tok), mb.ptr(self.catchup_cnt))
 
+        # a one-row tree (the root alone) for plain autoregressive decoding on the same kernels
+        self.ar_tok, self.ar_depth, self.ar_src = (torch.zeros(B, 1, **i32) for _ in range(3))
+        self.ar_parent = torch.full((B, 1), -1, **i32)
+        self.ar_mask = torch.ones(B, 1, dtype=torch.int64, device=device)
+        self.ar_tree = mb.mtad_tree(1, mb.ptr(self.ar_tok), mb.ptr(self.ar_parent), mb.ptr(self.ar_depth), mb.ptr(self.ar_src),
+                                    mb.ptr(self.ar_mask), mb.ptr(self.t_qref))
+
     def close(self):
         if self.ctx is not None:
             mb.mtad_destroy(self.ctx)
@@ -183,6 +190,16 @@ class Engine:
         self.verify_phase(stream)
         self.accept_phase(tau, sample_bonus, seed, stream)
         self.commit_phase(stream)
+
+    def iteration_autoregressive(self, sample=True, seed=0, stream=None):
+        """One token of plain decoding with the target alone (the baseline MTAD is measured against, Section 2.2): a target
+        pass over the root row, the token drawn from that row like a bonus token, the root's K/V committed.  The draft
+        model and its cache are not touched.  Row 0 of `logits` / `row_lse` and `bonus_tok` hold the results."""
+        mb.mtad_verify_tree(self.ctx, self.target.desc, self.tkv.desc, self.root_tok, self.ar_tree, self.logp_cond,
+                            self.row_lse, self.logits, stream)
+        mb.mtad_accept(self.ctx, self.ar_tree, self.logp_cond, self.logits, self.V, self.tkv.desc, 0.5, mb.MTAD_MODE_MTAD,
+                       int(sample), seed, self.acc, stream)
+        mb.mtad_kv_commit(self.ctx, self.tkv.desc, None, self.ar_tree, self.acc, self.state, stream)
 
     def capture_iteration(self, tau, sample_beam=False, sample_bonus=True, seed=0):
         """Records one iteration as a HIP graph and returns it (`graph.replay()` = one iteration on the current

@@ -135,6 +135,49 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
     return stats
 
 
+def run_autoregressive(tshape, wt, prompt, new_tokens, *, sample=True, seed=0, warp=None, device="cuda:0"):
+    """Plain decoding with the target alone on the HIP path against the oracle, token by token (free running; the runs
+    may part only where the oracle reports a near-tie)."""
+    from paper_2407_09722_amd.engine import DeviceModel, Engine
+    prompt = np.asarray(prompt, np.int32)
+    B, n0 = prompt.shape
+    dtype = tshape.dtype
+    tm = DeviceModel(tshape, wt, device)
+    eng = Engine(tm, tm, batch=B, gamma=1, beam=1, mode="mtad", max_context=n0 + new_tokens + 8, prefill_rows=16, device=device, warp=warp)
+    lm = DecoderLM(tshape, wt)
+    sp = [CachedSession(lm, list(prompt[s])) for s in range(B)]
+    eng.prefill(prompt)
+    _, atol = logit_tolerance(dtype)
+    margin_tol = max(atol, 1e-4) * 2
+    out = {"tokens": [[] for _ in range(B)], "excused": 0, "max_logit_err": 0.0}
+    alive = [True] * B
+    for it in range(new_tokens):
+        eng.iteration_autoregressive(sample, seed)
+        torch.cuda.synchronize()
+        logits, tok, tlen = eng.logits.cpu().numpy().reshape(-1, tshape.vocab)[:B], eng.bonus_tok.cpu().numpy(), eng.tkv.len.cpu().numpy()
+        for s in range(B):
+            if not alive[s]:
+                continue
+            tr = mtad.autoregressive_step(sp[s], sample=sample, seed=seed, seq_index=s, dt=np.float32, warp=warp)
+            if warp is not None and not np.array_equal(np.isinf(logits[s]), np.isinf(tr["logits"])):
+                assert tr["warp_margin"] < margin_tol
+                alive[s] = False
+                out["excused"] += 1
+                continue
+            out["max_logit_err"] = max(out["max_logit_err"], close(logits[s], tr["logits"], dtype, "target row"))
+            if tok[s] != tr["bonus"]:
+                assert tr["bonus_gap"] < margin_tol, f"token differs with gap {tr['bonus_gap']}"
+                alive[s] = False
+                out["excused"] += 1
+                continue
+            assert tlen[s] == len(sp[s].context) - 1
+            out["tokens"][s].append(int(tok[s]))
+    status = _status(eng)
+    eng.close()
+    assert status == 0
+    return out
+
+
 def _near_tie(scores, tol):
     s = np.sort(np.asarray(scores, np.float64))
     return len(s) > 1 and np.min(np.diff(s)) < tol

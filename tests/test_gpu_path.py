@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from tests._parity import run_pair
+from tests._parity import run_autoregressive, run_pair
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -173,3 +173,14 @@ def test_warp_with_fewer_candidates_than_beams():
     prompt = np.random.default_rng(3).integers(0, ts.vocab, (1, 12)).astype(np.int32)
     st = run_pair(ts, ds, wt, wd, prompt, 10, gamma=3, beam=4, mode="mmtad", tau=0.2, seed=4, sample_beam=False, check_kv=True, warp=(2, 0.9))
     assert st["excused"] == 0
+
+
+@pytest.mark.parametrize("kind,warp", [("fp32", None), ("bf16", None), ("bf16_hd128", (10, 0.9))])
+def test_autoregressive_baseline_matches(kind, warp):
+    """Plain decoding with the target alone (the baseline of Section 2.2) through the same entry points: a one-row target
+    pass, the token drawn from its row, the root committed."""
+    ts = SMALL[kind][0]
+    wt = _weights(ts, 23, "target", boost=4.0)
+    prompt = np.random.default_rng(4).integers(0, ts.vocab, (2, 19)).astype(np.int32)
+    st = run_autoregressive(ts, wt, prompt, 12, sample=True, seed=6, warp=warp)
+    assert st["excused"] == 0 and all(len(t) == 12 for t in st["tokens"])

@@ -422,3 +422,27 @@ def test_warped_iteration_stays_inside_the_supports():
         for r in tr["path_rows"]:
             assert np.isfinite(tr["joint"][r])
     assert seen_reject
+
+
+def test_autoregressive_step_is_ancestral_sampling_from_the_target():
+    """Greedy: the argmax chain.  Sampled: first tokens over many seeds follow the target's first-row distribution
+    (chi-square), warped or not."""
+    V = 6
+    fp = table_lm(V, 61, temp=1.5)
+    sess = TableSession(fp, (2,))
+    toks = [mtad.autoregressive_step(sess, sample=False)["bonus"] for _ in range(4)]
+    cur = (2,)
+    for t in toks:
+        assert t == int(np.argmax(fp(cur)))
+        cur += (t,)
+    for warp in (None, (3, 0.95)):
+        p = np.exp(fp((2,)))
+        if warp:
+            p = np.exp(mtad.warp_log_probs(fp((2,)), *warp)[0])
+        N = 4000
+        counts = np.zeros(V)
+        for seed in range(N):
+            counts[mtad.autoregressive_step(TableSession(fp, (2,)), sample=True, seed=seed, warp=warp)["bonus"]] += 1
+        keep = p > 0
+        assert np.all(counts[~keep] == 0)
+        assert stats.chisquare(counts[keep], p[keep] * N).pvalue > 1e-3
