@@ -96,7 +96,7 @@ def top_b(keys, b):
 
 # ---- draft: beam sampling on the auxiliary model (Section 2.1, Eq. 2) --------------------
 
-def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=np.float64, warp=None):
+def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=np.float64, warp=None, keep_rows=False):
     """gamma beam steps from the session's context.  Returns a history dict with, per step
     i and survivor j: tok[i][j], parent[i][j] (index of the beam it extends in step i-1; 0 at
     step 0 where the only beam is the context), score[i][j] = log q(branch | context), and
@@ -107,7 +107,7 @@ def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=
     live_score = np.zeros(1, dtype=dt)
     live_node = [-1]
     n0 = len(session.context)
-    hist = {"tok": [], "parent": [], "score": [], "node": [], "margin": [], "warp_margin": []}
+    hist = {"tok": [], "parent": [], "score": [], "node": [], "margin": [], "warp_margin": [], "logq_rows": []}
     for i in range(gamma):
         logits = live_rows.astype(dt)
         V = logits.shape[1]
@@ -118,6 +118,8 @@ def beam_search(session, gamma, b, *, stochastic=False, seed=0, seq_index=0, dt=
         else:
             logq, wm = warp_rows(logits, warp, dt)
             hist["warp_margin"].append(wm)
+        if keep_rows:
+            hist["logq_rows"].append(logq)                                   # log q(. | beam) of every live beam of this step
         cand = live_score[:, None] + logq                                    # joint log q of every extension
         flat = cand.ravel()
         if stochastic:
@@ -311,6 +313,14 @@ def iteration(sq, sp, *, gamma, beam, mode, tau, stochastic_beam=False, sample_b
     rows = branch_rows(tree, node)
     t, gap = bonus_token(ver["logits"][node], sample=sample_bonus, seed=seed, seq_index=seq_index,
                          position=n + eta, dt=dt)
+    accepted = _commit(sq, sp, hist, tree, ver, node, rows, eta, t, gamma)
+    return {"hist": hist, "tree": tree, "verify": ver, "joint": joint, "eta": eta, "node": node,
+            "path_rows": rows, "bonus": t, "bonus_gap": gap, "accept_margins": margins,
+            "emitted": accepted + [t], "n_before": n}
+
+
+def _commit(sq, sp, hist, tree, ver, node, rows, eta, t, gamma):
+    """Both sessions take [x_1..x_eta, t]; returns the accepted tokens."""
     accepted = [int(tree["tok"][r]) for r in rows]
     sp.commit(ver["node_ids"][node] if node > 0 else None, [t])
     # the draft never ran its final-step tokens: commit what it has, hand over the rest as context
@@ -320,9 +330,64 @@ def iteration(sq, sp, *, gamma, beam, mode, tau, stochastic_beam=False, sample_b
         r = rows[keep - 1]
         dnode = hist["node"][keep - 1][int(tree["src_beam"][r])]
     sq.commit(dnode, accepted[keep:] + [t])
-    return {"hist": hist, "tree": tree, "verify": ver, "joint": joint, "eta": eta, "node": node,
-            "path_rows": rows, "bonus": t, "bonus_gap": gap, "accept_margins": margins,
-            "emitted": accepted + [t], "n_before": n}
+    return accepted
+
+
+# ---- vanilla speculative decoding (Section 2.2), the baseline MTAD is compared with ---------------
+
+def accept_tokenwise(tok, logp_rows, logq_rows, *, seed=0, seq_index=0, n=0, dt=np.float64):
+    """Section 2.2 step 3: draft token x_t is accepted with probability min(1, p(x_t)/q(x_t)), each with its own
+    uniform draw (keyed by the token's absolute position n + t - 1); the tokens before the first rejection are
+    kept.  tok[t-1] = x_t; row t-1 of logp_rows / logq_rows is the distribution x_t was drawn from / is judged by.
+    Returns (eta, margins): margin = distance of each examined draw from its threshold in the log domain."""
+    gamma = len(tok)
+    eta, margins = gamma, []
+    for t in range(1, gamma + 1):
+        u = rng.uniform(seed, rng.stream_id(seq_index, rng.STREAM_ACCEPT), n + t - 1, 0)
+        log_u = np.log(dt(u))
+        ratio = min(dt(0), dt(logp_rows[t - 1][tok[t - 1]]) - dt(logq_rows[t - 1][tok[t - 1]]))
+        margins.append(_margin(log_u, ratio))
+        if not log_u < ratio:
+            eta = t - 1
+            break
+    return eta, margins
+
+
+def residual_token(logp_row, logq_row, *, seed=0, seq_index=0, position=0, dt=np.float64):
+    """The correction token after a rejection: a draw from the residual distribution norm(max(0, p - q)), as
+    argmax(log weight + Gumbel noise).  Returns (token, gap between the best and second-best key)."""
+    w = np.exp(np.asarray(logp_row).astype(dt)) - np.exp(np.asarray(logq_row).astype(dt))
+    with np.errstate(divide="ignore"):
+        key = np.where(w > 0, np.log(np.where(w > 0, w, dt(1))), dt(-np.inf)).astype(dt)
+    g = rng.gumbel(seed, rng.stream_id(seq_index, rng.STREAM_BONUS), position, np.arange(key.size))
+    key = key + g.astype(dt)
+    t = int(np.argmax(key))
+    rest = np.delete(key, t)
+    return t, float(key[t] - rest.max()) if rest.size else np.inf
+
+
+def iteration_spd(sq, sp, *, gamma, seed=0, seq_index=0, dt=np.float64, warp=None):
+    """One iteration of vanilla speculative decoding: gamma tokens drawn one after the other from the draft model
+    (beam sampling of width one is ancestral sampling), one target pass over the chain, token-wise acceptance, then the
+    correction token from the residual distribution at the first rejection, or one more token from the target's next row
+    if everything was accepted.  Same trace keys as `iteration`."""
+    assert sq.context == sp.context
+    n = len(sp.context)
+    hist = beam_search(sq, gamma, 1, stochastic=True, seed=seed, seq_index=seq_index, dt=dt, warp=warp, keep_rows=True)
+    tree = build_tree(hist, "mtad")
+    ver = verify(sp, tree, warp=warp, dt=dt)
+    logp_rows = np.asarray(ver["logits"]).astype(dt) - np.asarray(ver["lse"]).astype(dt)[:, None]
+    logq_rows = [hist["logq_rows"][i][0] for i in range(gamma)]
+    eta, margins = accept_tokenwise([int(t) for t in tree["tok"][1:]], logp_rows, logq_rows, seed=seed, seq_index=seq_index, n=n, dt=dt)
+    if eta < gamma:
+        t, gap = residual_token(logp_rows[eta], logq_rows[eta], seed=seed, seq_index=seq_index, position=n + eta, dt=dt)
+    else:
+        t, gap = bonus_token(logp_rows[gamma], sample=True, seed=seed, seq_index=seq_index, position=n + gamma, dt=dt)
+    rows = list(range(1, eta + 1))
+    accepted = _commit(sq, sp, hist, tree, ver, eta, rows, eta, t, gamma)
+    return {"hist": hist, "tree": tree, "verify": ver, "joint": joint_from_cond(tree, ver["logp_cond"].astype(dt), dt), "eta": eta,
+            "node": eta, "path_rows": rows, "bonus": t, "bonus_gap": gap, "accept_margins": margins, "emitted": accepted + [t],
+            "n_before": n}
 
 
 def autoregressive_step(sp, *, sample=True, seed=0, seq_index=0, dt=np.float64, warp=None):

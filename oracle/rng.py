@@ -16,6 +16,7 @@ _M2 = np.uint64(0x94D049BB133111EB)
 
 STREAM_BONUS = 0   # bonus token drawn from the target row
 STREAM_BEAM = 1    # stochastic beam sampling on the draft model
+STREAM_ACCEPT = 2  # token-wise accept draws of vanilla speculative decoding
 STREAMS_PER_SEQ = 4
 
 

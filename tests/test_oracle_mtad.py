@@ -446,3 +446,64 @@ def test_autoregressive_step_is_ancestral_sampling_from_the_target():
         keep = p > 0
         assert np.all(counts[~keep] == 0)
         assert stats.chisquare(counts[keep], p[keep] * N).pvalue > 1e-3
+
+
+# ---- vanilla speculative decoding (Section 2.2) ---------------------------------------------------
+
+def test_speculative_decoding_keeps_the_target_distribution():
+    """The property the method is built on (Section 2.2, last sentence: an identical sampling distribution): the first
+    token an iteration emits, whether an accepted draft token or the correction token, follows the target's next-token
+    distribution, for an unrelated draft model, warped or not; and so does the pair of the first two tokens."""
+    V, gamma = 5, 3
+    fq, fp = table_lm(V, 71, temp=1.5), table_lm(V, 72, temp=1.5)
+    ctx = (1, 3)
+    for warp in (None, (3, 0.95)):
+        def dist(fn, c):
+            lp = fn(c)
+            return np.exp(mtad.warp_log_probs(lp, *warp)[0]) if warp else np.exp(lp)
+        N = 6000
+        first = np.zeros(V)
+        pair = np.zeros((V, V))
+        n_pair = 0
+        for seed in range(N):
+            tr = mtad.iteration_spd(TableSession(fq, ctx), TableSession(fp, ctx), gamma=gamma, seed=seed, warp=warp)
+            first[tr["emitted"][0]] += 1
+            if len(tr["emitted"]) >= 2:
+                pair[tr["emitted"][0], tr["emitted"][1]] += 1
+                n_pair += 1
+        p1 = dist(fp, ctx)
+        keep = p1 > 0
+        assert np.all(first[~keep] == 0)
+        assert stats.chisquare(first[keep], p1[keep] * N).pvalue > 1e-3
+        # second token given the first: rows of the conditional table, each tested on its own sample
+        for a in np.nonzero(keep)[0]:
+            na = pair[a].sum()
+            if na < 200:
+                continue
+            p2 = dist(fp, ctx + (int(a),))
+            k2 = p2 > 0
+            assert np.all(pair[a][~k2] == 0)
+            # an iteration that rejects its first token emits one token only: among iterations that emit two, the second
+            # token still follows the target given the first (the first was accepted, the second is accepted or corrected)
+            assert stats.chisquare(pair[a][k2], p2[k2] * na).pvalue > 1e-4
+
+
+def test_speculative_decoding_special_cases():
+    """Identical models: every ratio is one, every token passes.  A draft whose mass lies where the target has none:
+    the first token is always rejected and the correction is a plain draw from the target (the residual is p)."""
+    V, gamma = 6, 4
+    fn = table_lm(V, 81)
+    for seed in range(20):
+        tr = mtad.iteration_spd(TableSession(fn, (0,)), TableSession(fn, (0,)), gamma=gamma, seed=seed)
+        assert tr["eta"] == gamma and len(tr["emitted"]) == gamma + 1
+    def fq(seq):
+        lp = np.full(V, -60.0); lp[:3] = np.log(1 / 3); return lp
+    def fp(seq):
+        lp = np.full(V, -60.0); lp[3:] = np.log(np.array([0.5, 0.3, 0.2])); return lp
+    counts = np.zeros(V)
+    for seed in range(3000):
+        tr = mtad.iteration_spd(TableSession(fq, (0,)), TableSession(fp, (0,)), gamma=gamma, seed=seed)
+        assert tr["eta"] == 0 and len(tr["emitted"]) == 1
+        counts[tr["bonus"]] += 1
+    assert np.all(counts[:3] == 0)
+    assert stats.chisquare(counts[3:], np.array([0.5, 0.3, 0.2]) * 3000).pvalue > 1e-3
