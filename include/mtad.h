@@ -226,6 +226,17 @@ int mtad_accept(mtad_ctx *ctx, const mtad_tree *tree, const float *logp_cond, co
                 const mtad_kv *tkv, float tau, int32_t mode, int32_t sample_bonus, uint64_t seed,
                 mtad_accept_out *out, void *stream);
 
+/* Vanilla speculative decoding (Section 2.2), the baseline the paper compares with, on the same entry points: a
+ * context created with beam = 1 and mode MTAD drafts a chain token by token (mtad_draft_beam_step with sample_beam = 1 is
+ * ancestral sampling; it also keeps log q of every step in the workspace), mtad_verify_tree runs the target over the
+ * chain, and this call replaces mtad_accept: draft token x_t passes with probability min(1, p(x_t)/q(x_t)) (a uniform
+ * number keyed by seed, sequence and the token's absolute position), the tokens before the first failure are kept, and
+ * the next token is drawn from the residual distribution norm(max(0, p - q)) of the failed position, or from the
+ * target's row after the last token when all passed.  p and q are the warped distributions when mtad_set_warp is on.
+ * `logits` [B][gamma+1][vocab] and `row_lse` [B][gamma+1] as mtad_verify_tree wrote them; `out` as mtad_accept;
+ * mtad_kv_commit follows unchanged.  MTAD_ESHAPE unless beam == 1, tree->M == gamma + 1 and both models share `vocab`. */
+int mtad_accept_spd(mtad_ctx *ctx, const mtad_tree *tree, const float *logits, const float *row_lse, int32_t vocab, const mtad_kv *tkv,
+                    uint64_t seed, mtad_accept_out *out, void *stream);
 /* Commit / rollback.  Target cache: the root row and the accepted branch are moved to logical slots
  * len .. len+eta (a no-op copy for a chain) and tkv.len += eta + 1; everything else in the speculative
  * window is dropped.  Draft cache (may be NULL): catch-up rows and the rows of the accepted branch the

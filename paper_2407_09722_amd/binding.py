@@ -18,7 +18,7 @@ MTAD_MAX_ROWS, MTAD_MAX_BEAM = 64, 8
 
 EXPORTS = ["mtad_create", "mtad_destroy", "mtad_workspace_bytes", "mtad_bind_workspace", "mtad_strerror",
            "mtad_last_hip_error", "mtad_device_status", "mtad_set_persistent", "mtad_set_warp", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
-           "mtad_verify_tree", "mtad_accept", "mtad_kv_commit",
+           "mtad_verify_tree", "mtad_accept", "mtad_accept_spd", "mtad_kv_commit",
            "mtad_k_gemm", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_copy"]
 
 i32, u64, f32, vp = C.c_int32, C.c_uint64, C.c_float, C.c_void_p
@@ -89,6 +89,7 @@ def lib():
         L.mtad_build_tree.argtypes = [vp, P(mtad_beam), i32, P(mtad_tree), vp]
         L.mtad_verify_tree.argtypes = [vp, P(mtad_model), P(mtad_kv), vp, P(mtad_tree), vp, vp, vp, vp]
         L.mtad_accept.argtypes = [vp, P(mtad_tree), vp, vp, i32, P(mtad_kv), f32, i32, i32, u64, P(mtad_accept_out), vp]
+        L.mtad_accept_spd.argtypes = [vp, P(mtad_tree), vp, vp, i32, P(mtad_kv), u64, P(mtad_accept_out), vp]
         L.mtad_kv_commit.argtypes = [vp, P(mtad_kv), P(mtad_kv), P(mtad_tree), P(mtad_accept_out), P(mtad_state), vp]
         L.mtad_k_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.mtad_k_rmsnorm.argtypes = [i32, vp, vp, vp, i32, i32, f32, vp]
@@ -186,6 +187,11 @@ def mtad_verify_tree(ctx, target, tkv, root_tok, tree, logp_cond, row_lse, logit
 def mtad_accept(ctx, tree, logp_cond, logits, vocab, tkv, tau, mode, sample_bonus, seed, out, stream=None):
     _check("mtad_accept", lib().mtad_accept(ctx, C.byref(tree), ptr(logp_cond), ptr(logits), vocab, C.byref(tkv), f32(tau), mode,
                                            int(sample_bonus), u64(seed), C.byref(out), _stream_ptr(stream)))
+
+
+def mtad_accept_spd(ctx, tree, logits, row_lse, vocab, tkv, seed, out, stream=None):
+    _check("mtad_accept_spd", lib().mtad_accept_spd(ctx, C.byref(tree), ptr(logits), ptr(row_lse), vocab, C.byref(tkv), u64(seed),
+                                                   C.byref(out), _stream_ptr(stream)))
 
 
 def mtad_kv_commit(ctx, tkv, dkv, tree, acc, st, stream=None):

@@ -33,6 +33,11 @@ hipError_t launch_topb(const float* logits, const float* lse, BeamView hist, con
                        int B, int R, int gamma, int beam, int V, int sample, uint64_t seed, float* part_key, int* part_idx, int G,
                        hipStream_t s);
 hipError_t launch_build_tree(BeamView hist, TreeView tree, int B, int gamma, int beam, int mode, hipStream_t s);
+// vanilla speculative decoding: keep log q of a width-1 draft step's live row; token-wise acceptance + next token
+hipError_t launch_save_logq_row(const float* logits, const float* lse, const int32_t* cu_cnt, int step, int B, int R, int gamma, int V,
+                                float* qrows, hipStream_t s);
+hipError_t launch_accept_spd(TreeView tree, const float* logits, const float* lse, const float* qrows, int V, const int32_t* len, int B,
+                             int gamma, uint64_t seed, AcceptView out, hipStream_t s);
 // rows of logits -> rows of log p~ (top_k, then top_p prefix; 1 <= top_k <= 16), lse -> 0; in place
 hipError_t launch_warp_rows(float* logits, float* lse, int rows, int V, int top_k, float top_p, hipStream_t s);
 hipError_t launch_gather_logp(const float* logits, const float* lse, TreeView tree, int B, int V, float* logp_cond, hipStream_t s);

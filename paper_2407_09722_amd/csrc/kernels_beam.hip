@@ -23,7 +23,12 @@ __device__ __forceinline__ float gumbel(uint64_t key, uint64_t idx) {
   const float u = ((float)(uint32_t)(h >> 41) + 0.5f) * 1.1920928955078125e-07f;
   return -logf(-logf(u));
 }
-constexpr int STREAM_BONUS = 0, STREAM_BEAM = 1, STREAMS_PER_SEQ = 4;
+constexpr int STREAM_BONUS = 0, STREAM_BEAM = 1, STREAM_ACCEPT = 2, STREAMS_PER_SEQ = 4;
+// the uniform number behind the noise: u = (k + 1/2) / 2^23, exact in float32
+__device__ __forceinline__ float uniform01(uint64_t key, uint64_t idx) {
+  const uint64_t h = mix64(key ^ (GOLDEN * (idx + 1)));
+  return ((float)(uint32_t)(h >> 41) + 0.5f) * 1.1920928955078125e-07f;
+}
 
 // ---- row descriptors ------------------------------------------------------------------------------
 
@@ -476,6 +481,95 @@ __global__ __launch_bounds__(1024) void accept_kernel(TreeView tree, const float
 hipError_t launch_accept(TreeView tree, const float* logp_cond, const float* logits, int V, const int32_t* len, float log_tau, int mode,
                          int B, int gamma, int sample, uint64_t seed, AcceptView out, hipStream_t s) {
   hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(1024), 0, s, tree, logp_cond, logits, V, len, log_tau, mode, gamma, sample, seed, out);
+  return hipGetLastError();
+}
+
+// ---- vanilla speculative decoding (Section 2.2), the baseline: token-wise acceptance and the correction token ------------
+
+// log q(. | prefix) of the one live beam of a draft step (beam width 1), kept for the accept step: row r of the step's
+// logits (the last catch-up row at step 0, row 0 afterwards) minus its logsumexp.  grid (blocks, B).
+__global__ __launch_bounds__(256) void save_logq_row_kernel(const float* __restrict__ logits, const float* __restrict__ lse,
+                                                            const int32_t* __restrict__ cu_cnt, int step, int R, int gamma, int V,
+                                                            float* __restrict__ qrows) {
+  const int s = blockIdx.y;
+  int r = 0;
+  if (step == 0) {
+    int cnt = cu_cnt[s];
+    if (cnt < 1 || cnt > gamma + 1) cnt = 1;
+    r = cnt - 1;
+  }
+  const float* row = logits + ((int64_t)s * R + r) * V;
+  const float l = lse[s * R + r];
+  float* out = qrows + ((int64_t)s * gamma + step) * V;
+  for (int v = blockIdx.x * blockDim.x + threadIdx.x; v < V; v += gridDim.x * blockDim.x) out[v] = row[v] - l;
+}
+
+hipError_t launch_save_logq_row(const float* logits, const float* lse, const int32_t* cu_cnt, int step, int B, int R, int gamma, int V,
+                                float* qrows, hipStream_t s) {
+  hipLaunchKernelGGL(save_logq_row_kernel, dim3(8, B), dim3(256), 0, s, logits, lse, cu_cnt, step, R, gamma, V, qrows);
+  return hipGetLastError();
+}
+
+// One workgroup per sequence.  Thread 0 walks the chain: x_t passes when log u_t < min(0, log p(x_t) - log q(x_t)), u_t
+// keyed by the token's absolute position; the tokens before the first failure are kept.  Then the whole workgroup draws
+// the next token: from the residual distribution norm(max(0, p - q)) of the failed position, or, when every token passed,
+// from the target's row after the last one; both as argmax(log weight + Gumbel noise).
+__global__ __launch_bounds__(1024) void accept_spd_kernel(TreeView tree, const float* __restrict__ logits, const float* __restrict__ lse,
+                                                         const float* __restrict__ qrows, int V, const int32_t* __restrict__ len, int gamma,
+                                                         uint64_t seed, AcceptView out) {
+  __shared__ int eta_s;
+  __shared__ float shk[16];
+  __shared__ int shi[16];
+  const int s = blockIdx.x, M = tree.M;
+  const int32_t* tok = tree.tok + (int64_t)s * M;
+  if (threadIdx.x == 0) {
+    int eta = gamma;
+    for (int t = 1; t <= gamma; ++t) {
+      int x = tok[t];
+      if (x < 0 || x >= V) x = 0;
+      const float lp = logits[((int64_t)s * M + t - 1) * V + x] - lse[s * M + t - 1];
+      const float lq = qrows[((int64_t)s * gamma + t - 1) * V + x];
+      const float u = uniform01(noise_key(seed, s * STREAMS_PER_SEQ + STREAM_ACCEPT, len[s] + t), 0);
+      if (!(logf(u) < fminf(0.f, lp - lq))) { eta = t - 1; break; }
+    }
+    eta_s = eta;
+    out.eta[s] = eta;
+    out.bonus_row[s] = eta;
+    out.out_cnt[s] = eta + 1;
+    for (int i = 0; i < gamma; ++i) out.path[s * gamma + i] = i < eta ? i + 1 : -1;
+    for (int i = 0; i < eta; ++i) out.out_tok[s * (gamma + 1) + i] = tok[i + 1];
+  }
+  __syncthreads();
+  const int eta = eta_s;
+  const float* prow = logits + ((int64_t)s * M + eta) * V;
+  const float pl = lse[s * M + eta];
+  const float* qrow = qrows + ((int64_t)s * gamma + (eta < gamma ? eta : 0)) * V;
+  const uint64_t nk = noise_key(seed, s * STREAMS_PER_SEQ + STREAM_BONUS, len[s] + 1 + eta);
+  float bk = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int v = threadIdx.x; v < V; v += (int)blockDim.x) {
+    const float lp = prow[v] - pl;
+    float k;
+    if (eta < gamma) {
+      const float w = expf(lp) - expf(qrow[v]);
+      k = w > 0.f ? logf(w) : -INFINITY;
+    } else {
+      k = lp;
+    }
+    k += gumbel(nk, (uint64_t)v);
+    if (better(k, v, bk, bi)) { bk = k; bi = v; }
+  }
+  block_best(bk, bi, shk, shi);
+  if (bi < 0 || bi >= V) bi = 0;  // only reachable with non-finite rows: stay in the vocabulary
+  if (threadIdx.x == 0) {
+    out.bonus_tok[s] = bi;
+    out.out_tok[s * (gamma + 1) + eta] = bi;
+  }
+}
+
+hipError_t launch_accept_spd(TreeView tree, const float* logits, const float* lse, const float* qrows, int V, const int32_t* len, int B,
+                             int gamma, uint64_t seed, AcceptView out, hipStream_t s) {
+  hipLaunchKernelGGL(accept_spd_kernel, dim3(B), dim3(1024), 0, s, tree, logits, lse, qrows, V, len, gamma, seed, out);
   return hipGetLastError();
 }
 

@@ -24,6 +24,7 @@ struct mtad_ctx {
   char* ws;
   // workspace carve-up
   float *h, *qkv, *gu, *dlogits, *lse, *partial, *part_key, *ssq, *lse_part;
+  float* qrows;  // [batch][gamma][draft vocab]: log q of every draft step's live row when the beam is one wide (mtad_accept_spd)
   void *xn, *xg;  // xn: attention output / FFN activation; xg: h*gain planes feeding the next normalised product
   int* attn_cnt;
   float* gemm_part;  // k-split partial sums of the product kernel (products with few strips, more than 8 rows)
@@ -152,6 +153,7 @@ void carve(mtad_ctx* c, char* base) {
   c->qkv = k.take<float>(rows * qkv);
   c->gu = k.take<float>(rows * 2 * fmax);
   c->dlogits = k.take<float>((size_t)c->cfg.batch * c->draft_rows * d.vocab);
+  c->qrows = k.take<float>(c->cfg.beam == 1 ? (size_t)c->cfg.batch * c->cfg.gamma * d.vocab : 1);
   c->lse = k.take<float>(rows);
   const size_t pt = attention_partial_floats(c->cfg.batch, c->Rmax, t.n_heads, t.head_dim, 32);
   const size_t pd = attention_partial_floats(c->cfg.batch, c->Rmax, d.n_heads, d.head_dim, 32);
@@ -492,6 +494,8 @@ int mtad_draft_beam_step(mtad_ctx* c, const mtad_model* draft, mtad_kv* dkv, mta
   int rc = decoder_pass(c, draft, dkv, R, s, c->dlogits, c->lse);
   if (rc) return rc;
   if (c->warp_k > 0) HIP_TRY(c, launch_warp_rows(c->dlogits, c->lse, B * R, draft->vocab, c->warp_k, c->warp_p, s));
+  if (beam == 1)  // a chain drawn token by token: keep log q of each step for token-wise acceptance (mtad_accept_spd)
+    HIP_TRY(c, launch_save_logq_row(c->dlogits, c->lse, st->catchup_cnt, step, B, R, gamma, draft->vocab, c->qrows, s));
   HIP_TRY(c, launch_topb(c->dlogits, c->lse, hv, st->catchup_cnt, dkv->len, step, B, R, gamma, beam, draft->vocab, sample_beam ? 1 : 0,
                          seed, c->part_key, c->part_idx, TOPB_BLOCKS, s));
   return MTAD_OK;
@@ -541,6 +545,18 @@ int mtad_accept(mtad_ctx* c, const mtad_tree* tree, const float* logp_cond, cons
   const AcceptView av{out->eta, out->path, out->bonus_row, out->bonus_tok, out->out_tok, out->out_cnt};
   HIP_TRY(c, launch_accept(tview(tree), logp_cond, logits, vocab, tkv->len, log_tau, mode, c->cfg.batch, c->cfg.gamma,
                            sample_bonus ? 1 : 0, seed, av, (hipStream_t)stream));
+  return MTAD_OK;
+}
+
+int mtad_accept_spd(mtad_ctx* c, const mtad_tree* tree, const float* logits, const float* row_lse, int32_t vocab, const mtad_kv* tkv,
+                    uint64_t seed, mtad_accept_out* out, void* stream) {
+  if (!c || !c->ws || !tree_ok(tree) || !logits || !row_lse || !tkv || !tkv->len || !out || !out->eta || !out->path || !out->bonus_row ||
+      !out->bonus_tok || !out->out_tok || !out->out_cnt)
+    return MTAD_EINVAL;
+  if (c->cfg.beam != 1 || tree->M != c->cfg.gamma + 1 || vocab != c->dshape.vocab || vocab != c->tshape.vocab) return MTAD_ESHAPE;
+  const AcceptView av{out->eta, out->path, out->bonus_row, out->bonus_tok, out->out_tok, out->out_cnt};
+  HIP_TRY(c, launch_accept_spd(tview(tree), logits, row_lse, c->qrows, vocab, tkv->len, c->cfg.batch, c->cfg.gamma, seed, av,
+                               (hipStream_t)stream));
   return MTAD_OK;
 }
 

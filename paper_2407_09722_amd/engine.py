@@ -191,6 +191,18 @@ class Engine:
         self.accept_phase(tau, sample_bonus, seed, stream)
         self.commit_phase(stream)
 
+    def accept_spd_phase(self, seed=0, stream=None):
+        mb.mtad_accept_spd(self.ctx, self.tree, self.logits, self.row_lse, self.V, self.tkv.desc, seed, self.acc, stream)
+
+    def iteration_spd(self, seed=0, stream=None):
+        """One iteration of vanilla speculative decoding (Section 2.2; an engine built with beam = 1, mode "mtad"): the chain
+        is drawn token by token from the draft, verified in one target pass, accepted token by token, and followed by the
+        correction token (or one more target token when all passed)."""
+        self.draft_phase(True, seed, stream)
+        self.verify_phase(stream)
+        self.accept_spd_phase(seed, stream)
+        self.commit_phase(stream)
+
     def iteration_autoregressive(self, sample=True, seed=0, stream=None):
         """One token of plain decoding with the target alone (the baseline MTAD is measured against, Section 2.2): a target
         pass over the root row, the token drawn from that row like a bonus token, the root's K/V committed.  The draft

@@ -32,7 +32,8 @@ def close(got, want, dtype, what=""):
 
 def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, tau, sample_bonus=True,
              sample_beam=False, seed=0, max_context=None, page_size=16, prefill_rows=64, check_kv=False,
-             max_iters=None, device="cuda:0", persistent=None, warp=None):
+             max_iters=None, device="cuda:0", persistent=None, warp=None, method="mtad"):
+    """method "spd": vanilla speculative decoding (beam 1, chain, token-wise acceptance) instead of the joint rule."""
     from paper_2407_09722_amd.engine import DeviceModel, Engine
     prompt = np.asarray(prompt, np.int32)
     B, n0 = prompt.shape
@@ -51,9 +52,12 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
     margin_tol = max(atol, 1e-4) * 2
     alive = [True] * B
     while min(len(t) for t in stats["tokens"]) < new_tokens and (max_iters is None or stats["iters"] < max_iters):
-        eng.draft_phase(sample_beam, seed)
+        eng.draft_phase(sample_beam or method == "spd", seed)
         eng.verify_phase()
-        eng.accept_phase(tau, sample_bonus, seed)
+        if method == "spd":
+            eng.accept_spd_phase(seed)
+        else:
+            eng.accept_phase(tau, sample_bonus, seed)
         torch.cuda.synchronize()
         g = {k: getattr(eng, k).cpu().numpy() for k in ("h_tok", "h_parent", "h_cum", "t_tok", "t_parent", "t_depth", "t_src",
                                                          "t_mask", "t_qref", "logp_cond", "row_lse", "logits", "eta", "path",
@@ -65,8 +69,11 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
         for s in range(B):
             if not alive[s]:
                 continue
-            tr = mtad.iteration(sq[s], sp[s], gamma=gamma, beam=beam, mode=mode, tau=tau, stochastic_beam=sample_beam,
-                                sample_bonus=sample_bonus, seed=seed, seq_index=s, dt=np.float32, warp=warp)
+            if method == "spd":
+                tr = mtad.iteration_spd(sq[s], sp[s], gamma=gamma, seed=seed, seq_index=s, dt=np.float32, warp=warp)
+            else:
+                tr = mtad.iteration(sq[s], sp[s], gamma=gamma, beam=beam, mode=mode, tau=tau, stochastic_beam=sample_beam,
+                                    sample_bonus=sample_bonus, seed=seed, seq_index=s, dt=np.float32, warp=warp)
             h = tr["hist"]
             # --- draft: beam history
             for i in range(gamma):

@@ -184,3 +184,43 @@ def test_autoregressive_baseline_matches(kind, warp):
     prompt = np.random.default_rng(4).integers(0, ts.vocab, (2, 19)).astype(np.int32)
     st = run_autoregressive(ts, wt, prompt, 12, sample=True, seed=6, warp=warp)
     assert st["excused"] == 0 and all(len(t) == 12 for t in st["tokens"])
+
+
+@pytest.mark.parametrize("kind,warp", [("fp32", None), ("bf16", None), ("fp32", (10, 0.9)), ("bf16_hd128", (10, 0.9))])
+def test_vanilla_speculative_decoding_matches(kind, warp):
+    """The baseline of Section 2.2 through mtad_accept_spd: the chain is drawn token by token (beam 1, stochastic),
+    accepted token by token with min(1, p/q), and followed by the correction token from the residual distribution.
+    Every accept decision and every correction token is compared; a difference is excused only where the oracle reports
+    the uniform draw or the Gumbel keys within the logit tolerance of each other."""
+    ts, ds = SMALL[kind]
+    print(f"speculative decoding {kind} warp={warp}", flush=True)
+    wt, wd = _weights(ts, 29, "target", boost=4.0), _weights(ds, 29, "draft", boost=4.0)
+    prompt = np.random.default_rng(9).integers(0, ts.vocab, (2, 17)).astype(np.int32)
+    st = run_pair(ts, ds, wt, wd, prompt, 14, gamma=4, beam=1, mode="mtad", tau=0.0, seed=8, prefill_rows=16, check_kv=True,
+                  warp=warp, method="spd")
+    print(f"   iterations {st['iters']}, eta {st['eta']}, parted: {st['events']}", flush=True)
+    if kind == "fp32":
+        assert st["excused"] == 0
+    assert sum(len(t) for t in st["tokens"]) >= 8
+
+
+def test_vanilla_speculative_decoding_identical_models_accept_everything():
+    ts = SMALL["fp32"][0]
+    w = _weights(ts, 3, "target", boost=4.0)
+    prompt = np.random.default_rng(1).integers(0, ts.vocab, (1, 9)).astype(np.int32)
+    st = run_pair(ts, ts, w, w, prompt, 20, gamma=4, beam=1, mode="mtad", tau=0.0, seed=1, check_kv=True, method="spd")
+    assert st["excused"] == 0 and all(e == 4 for e in st["eta"])
+
+
+def test_vanilla_speculative_decoding_partial_acceptance():
+    """A draft that is a perturbed copy of the target: acceptance lengths between 0 and gamma all occur, so passes,
+    first failures in the middle of the chain and both kinds of next token are compared."""
+    ts = SMALL["fp32"][0]
+    wt = _weights(ts, 31, "target", boost=4.0)
+    g = np.random.default_rng(12)
+    wd = {k: (v * (1.0 + 0.08 * g.standard_normal(v.shape))).astype(np.float32) if v.ndim == 2 else v for k, v in wt.items()}
+    prompt = np.random.default_rng(2).integers(0, ts.vocab, (3, 11)).astype(np.int32)
+    st = run_pair(ts, ts, wt, wd, prompt, 30, gamma=4, beam=1, mode="mtad", tau=0.0, seed=13, check_kv=True, method="spd")
+    print(f"   eta histogram {np.bincount(st['eta'], minlength=5)}", flush=True)
+    assert st["excused"] == 0
+    assert len(set(st["eta"])) >= 3
