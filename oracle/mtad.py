@@ -390,6 +390,19 @@ def iteration_spd(sq, sp, *, gamma, seed=0, seq_index=0, dt=np.float64, warp=Non
             "n_before": n}
 
 
+def iteration_mtjd(sp, *, K, beam, stochastic=False, seed=0, seq_index=0, dt=np.float64, warp=None):
+    """Multi-token joint decoding (Section 3.1) as the paper runs it (Section 3.1, last paragraph: beam sampling
+    approximates the draw from the joint distribution): K beam steps on the target model itself, then the K tokens of the
+    final beam with the highest stored likelihood are the output.  K = 1 is single-token decoding.  The session's
+    context grows by the K tokens.  Returns a trace."""
+    n = len(sp.context)
+    hist = beam_search(sp, K, beam, stochastic=stochastic, seed=seed, seq_index=seq_index, dt=dt, warp=warp)
+    beams, toks, q = output_beam(hist)
+    node = hist["node"][K - 2][beams[K - 2]] if K > 1 else None   # the last token was never run: it is handed over as context
+    sp.commit(node, [toks[K - 1]])
+    return {"hist": hist, "out_beams": beams, "emitted": toks, "logq": q, "n_before": n}
+
+
 def autoregressive_step(sp, *, sample=True, seed=0, seq_index=0, dt=np.float64, warp=None):
     """Plain decoding with the target alone (the multinomial-sampling baseline of Section 2.2): one token from the
     target's next-token distribution (warped if asked), drawn like the bonus token of an iteration that accepted

@@ -507,3 +507,49 @@ def test_speculative_decoding_special_cases():
         counts[tr["bonus"]] += 1
     assert np.all(counts[:3] == 0)
     assert stats.chisquare(counts[3:], np.array([0.5, 0.3, 0.2]) * 3000).pvalue > 1e-3
+
+
+# ---- multi-token joint decoding (Section 3.1) -------------------------------------------------------
+
+def test_mtjd_with_a_wide_beam_emits_the_most_likely_block_by_enumeration():
+    """Deterministic, beam wide enough to hold every prefix: each iteration emits the K-token block with the highest
+    joint likelihood under the model given everything emitted so far (all |V|^K blocks enumerated), twice in a row."""
+    V, K = 5, 3
+    fn = table_lm(V, 91, temp=2.0)
+    sess = TableSession(fn, (4, 0))
+    ctx = (4, 0)
+    for _ in range(2):
+        tr = mtad.iteration_mtjd(sess, K=K, beam=V ** (K - 1))
+        blocks = list(itertools.product(range(V), repeat=K))
+        scores = [joint_logprob(fn, ctx, b) for b in blocks]
+        assert tuple(tr["emitted"]) == blocks[int(np.argmax(scores))]
+        assert np.isclose(tr["logq"][-1], max(scores))
+        ctx += tuple(tr["emitted"])
+        assert tuple(sess.context) == ctx
+
+
+def test_mtjd_with_one_token_per_step_is_single_token_decoding():
+    """K = 1 (Section 3.1: equivalent to multinomial sampling): deterministic = greedy, stochastic = a draw from p."""
+    V = 6
+    fn = table_lm(V, 92, temp=1.5)
+    sess = TableSession(fn, (1,))
+    cur = (1,)
+    for _ in range(3):
+        t = mtad.iteration_mtjd(sess, K=1, beam=1)["emitted"]
+        assert t == [int(np.argmax(fn(cur)))]
+        cur += (t[0],)
+    N, counts = 4000, np.zeros(V)
+    for seed in range(N):
+        counts[mtad.iteration_mtjd(TableSession(fn, (1,)), K=1, beam=1, stochastic=True, seed=seed)["emitted"][0]] += 1
+    assert stats.chisquare(counts, np.exp(fn((1,))) * N).pvalue > 1e-3
+
+
+def test_mtjd_blocks_are_at_least_as_likely_as_greedy_blocks():
+    """The point of Section 3.1 on seeded tables: the block a width-4 beam chooses jointly is at least as likely as the greedy
+    block (not a theorem for a finite beam: a fixed set of cases)."""
+    V, K = 8, 4
+    for seed in range(10):
+        fn = table_lm(V, 100 + seed, temp=2.5)
+        a = mtad.iteration_mtjd(TableSession(fn, (0,)), K=K, beam=4)
+        g = mtad.iteration_mtjd(TableSession(fn, (0,)), K=K, beam=1)
+        assert joint_logprob(fn, (0,), a["emitted"]) >= joint_logprob(fn, (0,), g["emitted"]) - 1e-12
