@@ -275,11 +275,29 @@ def main():
         toks = int((engs.tkv.len - len0).sum().item())
         status |= mb.mtad_device_status(engs.ctx)
         engs.close()
+        # multi-token joint decoding: the beam search runs on the target itself (its weights serve as the "draft" of a second engine)
+        engj = Engine(tm, tm, batch=w.batch, gamma=w.gamma, beam=w.beam, mode="mtad", max_context=w.prompt_len + (K + W + 2) * w.gamma + 64,
+                      device=dev)
+        engj.prefill(prompt)
+        for _ in range(min(W, 2)):
+            engj.iteration_mtjd(seed=w.seed)
+        torch.cuda.synchronize()
+        Kj = max(3, K // 4)
+        t = time.perf_counter()
+        for _ in range(Kj):
+            engj.iteration_mtjd(seed=w.seed)
+        torch.cuda.synchronize()
+        dtj = time.perf_counter() - t
+        status |= mb.mtad_device_status(engj.ctx)
+        engj.close()
         it_s = K / dt
         baselines = {
             "autoregressive": {"tokens_per_s": round(K * w.batch / dta, 2), "ms_per_token": round(dta / K * 1e3, 4)},
             "speculative_decoding": {"tokens_per_s": round(toks / dts, 2), "tokens_per_iteration": round(toks / K / w.batch, 3),
                                      "ms_per_step": round(dts / K * 1e3, 4), "gamma": w.gamma},
+            "multi_token_joint_decoding": {"tokens_per_s": round(Kj * w.gamma * w.batch / dtj, 2), "tokens_per_step": w.gamma,
+                                           "ms_per_step": round(dtj / Kj * 1e3, 4), "beam": w.beam,
+                                           "note": "beam sampling on the target itself (Section 3.1): the quality reference MTAD approximates"},
             "projection": {"mtad_over_spd": round((it_s * 3.17) / (K / dts * 2.02), 3),
                            "mtad_over_autoregressive": round((it_s * 3.17) / (K / dta), 3),
                            "note": "iterations/s of each method x the tokens per iteration the paper reports for its Llama-2 pair "

@@ -226,6 +226,14 @@ int mtad_accept(mtad_ctx *ctx, const mtad_tree *tree, const float *logp_cond, co
                 const mtad_kv *tkv, float tau, int32_t mode, int32_t sample_bonus, uint64_t seed,
                 mtad_accept_out *out, void *stream);
 
+/* Multi-token joint decoding (Section 3.1) as the paper runs it: beam sampling on the target model itself, gamma = K tokens
+ * per step.  A context whose "draft" model is the target runs the K beam steps with mtad_draft_beam_step on that model's
+ * cache and builds the chain of the most likely final beam with mtad_build_tree (mode MTAD); this call writes the chain
+ * as an accept record that emits all K tokens (out_tok[0..K-1], out_cnt = K), and mtad_kv_commit with tkv = NULL and that
+ * cache as dkv commits them: the rows of the first K - 1 tokens are gathered into place, the last token, which the beam
+ * steps never ran, becomes the pending token of the next step.  No target pass is involved.
+ * MTAD_ESHAPE unless tree->M == gamma + 1. */
+int mtad_accept_chain(mtad_ctx *ctx, const mtad_tree *tree, mtad_accept_out *out, void *stream);
 /* Vanilla speculative decoding (Section 2.2), the baseline the paper compares with, on the same entry points: a
  * context created with beam = 1 and mode MTAD drafts a chain token by token (mtad_draft_beam_step with sample_beam = 1 is
  * ancestral sampling; it also keeps log q of every step in the workspace), mtad_verify_tree runs the target over the
@@ -239,8 +247,9 @@ int mtad_accept_spd(mtad_ctx *ctx, const mtad_tree *tree, const float *logits, c
                     uint64_t seed, mtad_accept_out *out, void *stream);
 /* Commit / rollback.  Target cache: the root row and the accepted branch are moved to logical slots
  * len .. len+eta (a no-op copy for a chain) and tkv.len += eta + 1; everything else in the speculative
- * window is dropped.  Draft cache (may be NULL): catch-up rows and the rows of the accepted branch the
- * draft has run (depth <= gamma-1) are kept likewise.  `st` is rewritten for the next iteration:
+ * window is dropped.  Draft cache: catch-up rows and the rows of the accepted branch the
+ * draft has run (depth <= gamma-1) are kept likewise.  Either cache may be NULL (not both): plain decoding has no
+ * draft cache, multi-token joint decoding no target cache.  `st` is rewritten for the next iteration:
  * root_tok = t, catchup = [x_gamma, t] if eta == gamma else [t]. */
 int mtad_kv_commit(mtad_ctx *ctx, mtad_kv *tkv, mtad_kv *dkv, const mtad_tree *tree, const mtad_accept_out *acc,
                    mtad_state *st, void *stream);

@@ -18,7 +18,7 @@ MTAD_MAX_ROWS, MTAD_MAX_BEAM = 64, 8
 
 EXPORTS = ["mtad_create", "mtad_destroy", "mtad_workspace_bytes", "mtad_bind_workspace", "mtad_strerror",
            "mtad_last_hip_error", "mtad_device_status", "mtad_set_persistent", "mtad_set_warp", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
-           "mtad_verify_tree", "mtad_accept", "mtad_accept_spd", "mtad_kv_commit",
+           "mtad_verify_tree", "mtad_accept", "mtad_accept_spd", "mtad_accept_chain", "mtad_kv_commit",
            "mtad_k_gemm", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_copy"]
 
 i32, u64, f32, vp = C.c_int32, C.c_uint64, C.c_float, C.c_void_p
@@ -89,6 +89,7 @@ def lib():
         L.mtad_build_tree.argtypes = [vp, P(mtad_beam), i32, P(mtad_tree), vp]
         L.mtad_verify_tree.argtypes = [vp, P(mtad_model), P(mtad_kv), vp, P(mtad_tree), vp, vp, vp, vp]
         L.mtad_accept.argtypes = [vp, P(mtad_tree), vp, vp, i32, P(mtad_kv), f32, i32, i32, u64, P(mtad_accept_out), vp]
+        L.mtad_accept_chain.argtypes = [vp, P(mtad_tree), P(mtad_accept_out), vp]
         L.mtad_accept_spd.argtypes = [vp, P(mtad_tree), vp, vp, i32, P(mtad_kv), u64, P(mtad_accept_out), vp]
         L.mtad_kv_commit.argtypes = [vp, P(mtad_kv), P(mtad_kv), P(mtad_tree), P(mtad_accept_out), P(mtad_state), vp]
         L.mtad_k_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
@@ -189,13 +190,17 @@ def mtad_accept(ctx, tree, logp_cond, logits, vocab, tkv, tau, mode, sample_bonu
                                            int(sample_bonus), u64(seed), C.byref(out), _stream_ptr(stream)))
 
 
+def mtad_accept_chain(ctx, tree, out, stream=None):
+    _check("mtad_accept_chain", lib().mtad_accept_chain(ctx, C.byref(tree), C.byref(out), _stream_ptr(stream)))
+
+
 def mtad_accept_spd(ctx, tree, logits, row_lse, vocab, tkv, seed, out, stream=None):
     _check("mtad_accept_spd", lib().mtad_accept_spd(ctx, C.byref(tree), ptr(logits), ptr(row_lse), vocab, C.byref(tkv), u64(seed),
                                                    C.byref(out), _stream_ptr(stream)))
 
 
 def mtad_kv_commit(ctx, tkv, dkv, tree, acc, st, stream=None):
-    _check("mtad_kv_commit", lib().mtad_kv_commit(ctx, C.byref(tkv), C.byref(dkv) if dkv is not None else None, C.byref(tree),
+    _check("mtad_kv_commit", lib().mtad_kv_commit(ctx, C.byref(tkv) if tkv is not None else None, C.byref(dkv) if dkv is not None else None, C.byref(tree),
                                                  C.byref(acc), C.byref(st), _stream_ptr(stream)))
 
 

@@ -38,6 +38,8 @@ hipError_t launch_save_logq_row(const float* logits, const float* lse, const int
                                 float* qrows, hipStream_t s);
 hipError_t launch_accept_spd(TreeView tree, const float* logits, const float* lse, const float* qrows, int V, const int32_t* len, int B,
                              int gamma, uint64_t seed, AcceptView out, hipStream_t s);
+// multi-token joint decoding: the chain in `tree` as an accept record (all gamma tokens emitted)
+hipError_t launch_accept_chain(TreeView tree, int B, int gamma, AcceptView out, hipStream_t s);
 // rows of logits -> rows of log p~ (top_k, then top_p prefix; 1 <= top_k <= 16), lse -> 0; in place
 hipError_t launch_warp_rows(float* logits, float* lse, int rows, int V, int top_k, float top_p, hipStream_t s);
 hipError_t launch_gather_logp(const float* logits, const float* lse, TreeView tree, int B, int V, float* logp_cond, hipStream_t s);

@@ -708,13 +708,35 @@ hipError_t launch_kv_gather(int dtype, KvView kv, int n_layers, int B, const int
   return hipGetLastError();
 }
 
+// Multi-token joint decoding (Section 3.1): the chain of the beam search is the output.  Written as an accept record
+// whose last token plays the part of the bonus token: the first gamma - 1 tokens were run by the beam steps (their rows
+// are gathered by the commit), the last one was not and becomes the pending token.
+__global__ void accept_chain_kernel(TreeView tree, int B, int gamma, AcceptView out) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= B) return;
+  const int32_t* tok = tree.tok + (int64_t)s * tree.M;
+  out.eta[s] = gamma - 1;
+  out.bonus_row[s] = gamma - 1;
+  out.bonus_tok[s] = tok[gamma];
+  out.out_cnt[s] = gamma;
+  for (int i = 0; i < gamma; ++i) {
+    out.path[s * gamma + i] = i < gamma - 1 ? i + 1 : -1;
+    out.out_tok[s * (gamma + 1) + i] = tok[i + 1];
+  }
+}
+
+hipError_t launch_accept_chain(TreeView tree, int B, int gamma, AcceptView out, hipStream_t s) {
+  hipLaunchKernelGGL(accept_chain_kernel, dim3((B + 63) / 64), dim3(64), 0, s, tree, B, gamma, out);
+  return hipGetLastError();
+}
+
 // lengths and the state of the next iteration
 __global__ void commit_state_kernel(int32_t* tlen, int32_t* dlen, TreeView tree, AcceptView acc, int32_t* root_tok, int32_t* cu_tok,
                                     int32_t* cu_cnt, int B, int gamma, int tcap, int dcap) {
   const int s = blockIdx.x * blockDim.x + threadIdx.x;
   if (s >= B) return;
   const int eta = acc.eta[s], t = acc.bonus_tok[s];
-  tlen[s] = min(tcap, tlen[s] + eta + 1);
+  if (tlen) tlen[s] = min(tcap, tlen[s] + eta + 1);
   if (dlen) {
     int cnt = cu_cnt[s];
     if (cnt < 1 || cnt > gamma + 1) cnt = 1;

@@ -548,6 +548,15 @@ int mtad_accept(mtad_ctx* c, const mtad_tree* tree, const float* logp_cond, cons
   return MTAD_OK;
 }
 
+int mtad_accept_chain(mtad_ctx* c, const mtad_tree* tree, mtad_accept_out* out, void* stream) {
+  if (!c || !tree_ok(tree) || !out || !out->eta || !out->path || !out->bonus_row || !out->bonus_tok || !out->out_tok || !out->out_cnt)
+    return MTAD_EINVAL;
+  if (tree->M != c->cfg.gamma + 1) return MTAD_ESHAPE;
+  const AcceptView av{out->eta, out->path, out->bonus_row, out->bonus_tok, out->out_tok, out->out_cnt};
+  HIP_TRY(c, launch_accept_chain(tview(tree), c->cfg.batch, c->cfg.gamma, av, (hipStream_t)stream));
+  return MTAD_OK;
+}
+
 int mtad_accept_spd(mtad_ctx* c, const mtad_tree* tree, const float* logits, const float* row_lse, int32_t vocab, const mtad_kv* tkv,
                     uint64_t seed, mtad_accept_out* out, void* stream) {
   if (!c || !c->ws || !tree_ok(tree) || !logits || !row_lse || !tkv || !tkv->len || !out || !out->eta || !out->path || !out->bonus_row ||
@@ -562,20 +571,22 @@ int mtad_accept_spd(mtad_ctx* c, const mtad_tree* tree, const float* logits, con
 
 int mtad_kv_commit(mtad_ctx* c, mtad_kv* tkv, mtad_kv* dkv, const mtad_tree* tree, const mtad_accept_out* acc, mtad_state* st,
                    void* stream) {
-  if (!c || !kv_ok(tkv) || (dkv && !kv_ok(dkv)) || !tree_ok(tree) || !acc || !acc->eta || !acc->path || !acc->bonus_tok || !st ||
-      !st->root_tok || !st->catchup_tok || !st->catchup_cnt)
+  if (!c || (!tkv && !dkv) || (tkv && !kv_ok(tkv)) || (dkv && !kv_ok(dkv)) || !tree_ok(tree) || !acc || !acc->eta || !acc->path ||
+      !acc->bonus_tok || !st || !st->root_tok || !st->catchup_tok || !st->catchup_cnt)
     return MTAD_EINVAL;
   if (tree->M < 1 || tree->M > MTAD_MAX_ROWS) return MTAD_ESHAPE;
   hipStream_t s = (hipStream_t)stream;
   const int B = c->cfg.batch, gamma = c->cfg.gamma, beam = c->cfg.beam;
-  HIP_TRY(c, launch_kv_gather(c->tshape.dtype, view_of(tkv, &c->tshape), c->tshape.n_layers, B, acc->eta, acc->path, tree->src_beam,
-                              st->catchup_cnt, tree->M, gamma, beam, 0, s));
+  if (tkv)
+    HIP_TRY(c, launch_kv_gather(c->tshape.dtype, view_of(tkv, &c->tshape), c->tshape.n_layers, B, acc->eta, acc->path, tree->src_beam,
+                                st->catchup_cnt, tree->M, gamma, beam, 0, s));
   if (dkv)
     HIP_TRY(c, launch_kv_gather(c->dshape.dtype, view_of(dkv, &c->dshape), c->dshape.n_layers, B, acc->eta, acc->path, tree->src_beam,
                                 st->catchup_cnt, tree->M, gamma, beam, 1, s));
   const AcceptView av{acc->eta, acc->path, acc->bonus_row, acc->bonus_tok, acc->out_tok, acc->out_cnt};
-  HIP_TRY(c, launch_commit_state(tkv->len, dkv ? dkv->len : nullptr, tview(tree), av, st->root_tok, st->catchup_tok, st->catchup_cnt, B,
-                                 gamma, tkv->page_size * tkv->max_pages, dkv ? dkv->page_size * dkv->max_pages : 0, s));
+  HIP_TRY(c, launch_commit_state(tkv ? tkv->len : nullptr, dkv ? dkv->len : nullptr, tview(tree), av, st->root_tok, st->catchup_tok,
+                                 st->catchup_cnt, B, gamma, tkv ? tkv->page_size * tkv->max_pages : 0,
+                                 dkv ? dkv->page_size * dkv->max_pages : 0, s));
   return MTAD_OK;
 }
 

@@ -203,6 +203,14 @@ class Engine:
         self.accept_spd_phase(seed, stream)
         self.commit_phase(stream)
 
+    def iteration_mtjd(self, sample_beam=False, seed=0, stream=None):
+        """One step of multi-token joint decoding (Section 3.1; an engine whose draft model IS the target, mode "mtad"): gamma
+        beam steps on that model, the chain of the most likely final beam is the output (`out_tok`, `out_cnt` = gamma), and
+        its cache (`dkv`) takes the tokens.  The engine's target cache is not used."""
+        self.draft_phase(sample_beam, seed, stream)
+        mb.mtad_accept_chain(self.ctx, self.tree, self.acc, stream)
+        mb.mtad_kv_commit(self.ctx, None, self.dkv.desc, self.tree, self.acc, self.state, stream)
+
     def iteration_autoregressive(self, sample=True, seed=0, stream=None):
         """One token of plain decoding with the target alone (the baseline MTAD is measured against, Section 2.2): a target
         pass over the root row, the token drawn from that row like a bonus token, the root's K/V committed.  The draft

@@ -185,6 +185,54 @@ def run_autoregressive(tshape, wt, prompt, new_tokens, *, sample=True, seed=0, w
     return out
 
 
+def run_mtjd(tshape, wt, prompt, steps, *, K, beam, sample_beam=False, seed=0, warp=None, device="cuda:0"):
+    """Multi-token joint decoding (beam sampling on the target itself) on the HIP path against the oracle, step by step."""
+    from paper_2407_09722_amd.engine import DeviceModel, Engine
+    prompt = np.asarray(prompt, np.int32)
+    B, n0 = prompt.shape
+    dtype = tshape.dtype
+    tm = DeviceModel(tshape, wt, device)
+    eng = Engine(tm, tm, batch=B, gamma=K, beam=beam, mode="mtad", max_context=n0 + steps * K + 2 * K + 16, prefill_rows=16,
+                 device=device, warp=warp)
+    lm = DecoderLM(tshape, wt)
+    sp = [CachedSession(lm, list(prompt[s])) for s in range(B)]
+    eng.prefill(prompt)
+    _, atol = logit_tolerance(dtype)
+    margin_tol = max(atol, 1e-4) * 2
+    out = {"tokens": [[] for _ in range(B)], "excused": 0}
+    alive = [True] * B
+    for it in range(steps):
+        eng.iteration_mtjd(sample_beam, seed)
+        torch.cuda.synchronize()
+        g = {k: getattr(eng, k).cpu().numpy() for k in ("h_tok", "h_parent", "h_cum", "out_tok", "out_cnt", "catchup_tok", "catchup_cnt")}
+        dlen = eng.dkv.len.cpu().numpy()
+        for s in range(B):
+            if not alive[s]:
+                continue
+            tr = mtad.iteration_mtjd(sp[s], K=K, beam=beam, stochastic=sample_beam, seed=seed, seq_index=s, dt=np.float32, warp=warp)
+            h = tr["hist"]
+            for i in range(K):
+                same = np.array_equal(g["h_tok"][s, i], h["tok"][i]) and np.array_equal(g["h_parent"][s, i], h["parent"][i])
+                if not same:
+                    assert h["margin"][i] < margin_tol or _near_tie(h["score"][i], margin_tol) or h["warp_margin"][i] < margin_tol, \
+                        f"seq {s} step {it} beam step {i}: survivors differ, margin {h['margin'][i]}"
+                    alive[s] = False
+                    break
+                close(g["h_cum"][s, i], h["score"][i], dtype, f"cum_logq step {i}")
+            if not alive[s]:
+                out["excused"] += 1
+                continue
+            assert g["out_cnt"][s] == K and list(g["out_tok"][s, :K]) == tr["emitted"]
+            pend = sp[s].context[sp[s].n_cached:]
+            assert dlen[s] == sp[s].n_cached and g["catchup_cnt"][s] == len(pend) and list(g["catchup_tok"][s, :len(pend)]) == pend
+            _check_kv(eng.dkv, s, sp[s], dtype)
+            out["tokens"][s] += tr["emitted"]
+    status = _status(eng)
+    eng.close()
+    assert status == 0
+    return out
+
+
 def _near_tie(scores, tol):
     s = np.sort(np.asarray(scores, np.float64))
     return len(s) > 1 and np.min(np.diff(s)) < tol

@@ -4,7 +4,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from tests._parity import run_autoregressive, run_pair
+from tests._parity import run_autoregressive, run_mtjd, run_pair
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -224,3 +224,16 @@ def test_vanilla_speculative_decoding_partial_acceptance():
     print(f"   eta histogram {np.bincount(st['eta'], minlength=5)}", flush=True)
     assert st["excused"] == 0
     assert len(set(st["eta"])) >= 3
+
+
+@pytest.mark.parametrize("kind,K,beam,sample", [("fp32", 4, 3, False), ("bf16", 3, 4, True), ("bf16_hd128", 1, 1, True), ("fp32", 2, 8, False)])
+def test_multi_token_joint_decoding_matches(kind, K, beam, sample):
+    """Section 3.1 as the paper runs it: K beam steps on the target model itself, the chain of the best final beam is emitted
+    whole and committed to that model's cache (beam history, emitted block, cache rows and pending token are compared)."""
+    ts = SMALL[kind][0]
+    wt = _weights(ts, 37, "target", boost=4.0)
+    prompt = np.random.default_rng(7).integers(0, ts.vocab, (2, 13)).astype(np.int32)
+    st = run_mtjd(ts, wt, prompt, 5, K=K, beam=beam, sample_beam=sample, seed=3)
+    if kind == "fp32":
+        assert st["excused"] == 0 and all(len(t) == 5 * K for t in st["tokens"])
+    assert sum(len(t) for t in st["tokens"]) >= 2 * K
