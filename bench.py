@@ -44,6 +44,101 @@ def target_gemm_shapes(shape):
     return per_layer, (shape.vocab, d)
 
 
+class PowerSampler:
+    """Board power from the amdgpu hwmon sensor (microwatts), sampled by a thread; energy = trapezoid integral."""
+
+    def __init__(self, hz=20.0):
+        import glob
+        import threading
+        paths = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")) + \
+            sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
+        self.path = paths[0] if paths else None
+        self.dt = 1.0 / hz
+        self.samples = []
+        self._stop = threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _read(self):
+        with open(self.path) as f:
+            return float(f.read().strip()) * 1e-6
+
+    def _run(self):
+        while not self._stop.is_set():
+            try:
+                self.samples.append((time.perf_counter(), self._read()))
+            except (OSError, ValueError):
+                pass
+            self._stop.wait(self.dt)
+
+    def __enter__(self):
+        self.samples = []
+        self.t0 = time.perf_counter()
+        if self.path:
+            self.samples.append((self.t0, self._read()))
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self.t1 = time.perf_counter()
+        self._stop.set()
+        if self.path:
+            self._thread.join()
+            self.samples.append((self.t1, self._read()))
+
+    def joules(self):
+        s = self.samples
+        return sum((b[0] - a[0]) * (a[1] + b[1]) / 2 for a, b in zip(s, s[1:]))
+
+
+def measure_energy(eng, w, tau, prompt, tm, dm, Engine, torch, dev, seconds=3.0):
+    """Joules per iteration of MTAD, vanilla speculative decoding and plain decoding: each runs for about `seconds` while the
+    board power sensor is sampled at 20 Hz."""
+    if PowerSampler().path is None:
+        return {"error": "no power sensor under /sys/class/drm/card*/device/hwmon"}
+
+    def run(step, tokens_of, n_probe=5):
+        for _ in range(n_probe):
+            step()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n_probe):
+            step()
+        torch.cuda.synchronize()
+        n = max(20, int(seconds / max((time.perf_counter() - t) / n_probe, 1e-4)))
+        n0 = tokens_of()
+        with PowerSampler() as ps:
+            for _ in range(n):
+                step()
+            torch.cuda.synchronize()
+        toks = tokens_of() - n0
+        e = ps.joules()
+        return {"iterations": n, "seconds": round(ps.t1 - ps.t0, 3), "mean_W": round(e / (ps.t1 - ps.t0), 1),
+                "J_per_iteration": round(e / n, 4), "tokens": toks, "J_per_token": round(e / max(toks, 1), 4),
+                "power_samples": len(ps.samples)}
+
+    cap = lambda n_it, per: w.prompt_len + (n_it + 16) * per + 64
+    # sized for the longest run: iterations are a few milliseconds, so a 3 s run is at most ~2000 of them
+    n_max = 2500
+    out = {"sensor": PowerSampler().path, "sample_hz": 20, "seconds_per_method": seconds}
+    e1 = Engine(tm, dm, batch=w.batch, gamma=w.gamma, beam=w.beam, mode=w.mode, max_context=cap(n_max, w.gamma + 1), device=dev)
+    e1.prefill(prompt)
+    out["mtad"] = run(lambda: e1.iteration(tau, seed=w.seed), lambda: int(e1.tkv.len.sum().item()))
+    e1.prefill(prompt)
+    out["autoregressive"] = run(lambda: e1.iteration_autoregressive(seed=w.seed), lambda: int(e1.tkv.len.sum().item()))
+    e1.close()
+    e2 = Engine(tm, dm, batch=w.batch, gamma=w.gamma, beam=1, mode="mtad", max_context=cap(n_max, w.gamma + 1), device=dev)
+    e2.prefill(prompt)
+    out["speculative_decoding"] = run(lambda: e2.iteration_spd(seed=w.seed), lambda: int(e2.tkv.len.sum().item()))
+    e2.close()
+    out["projection"] = {
+        "J_per_token_mtad": round(out["mtad"]["J_per_iteration"] / w.batch / 3.17, 4),
+        "J_per_token_speculative_decoding": round(out["speculative_decoding"]["J_per_iteration"] / w.batch / 2.02, 4),
+        "J_per_token_autoregressive": round(out["autoregressive"]["J_per_iteration"] / w.batch, 4),
+        "note": "joules per iteration / the tokens per iteration the paper reports for its Llama-2 pair (MTAD 3.17, SpD 2.02): a "
+                "projection; the measured J_per_token above are for independent random models (about one token per iteration)"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +149,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tree-verify", action="store_true", help="skip the C4-shaped verify-step measurement")
     ap.add_argument("--no-baselines", action="store_true", help="skip plain decoding and vanilla speculative decoding")
+    ap.add_argument("--no-energy", action="store_true", help="skip the board-power measurement (about 10 s)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (requests are independent; more GPUs would each run this "
@@ -305,6 +401,12 @@ def main():
                                    "independent random models, which accept almost nothing"},
         }
 
+    # --- energy per token (the paper's second headline, Section 5 "energy consumption"): board power from the driver's sensor,
+    #     sampled while each method runs for a few seconds, integrated over the run
+    energy = None
+    if not args.no_energy and baselines is not None:
+        energy = measure_energy(eng, w, tau, prompt, tm, dm, Engine, torch, dev)
+
     # --- the oracle on the host cores, bounded sample ---------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -327,7 +429,7 @@ def main():
                                "block-efficiency table): a labelled projection, not a measurement"},
         "tau0": {"tokens_per_s": round(tokens0 / dt0, 2), "tokens_per_iteration": round(tokens0 / K / w.batch, 3),
                  "ms_per_step": round(dt0 / K * 1e3, 4)},
-        "warped": warped, "baselines": baselines, "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
+        "warped": warped, "baselines": baselines, "energy": energy, "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
         "device_status": status, "weights_setup_s": round(t_weights, 1),
     }
     print(json.dumps(out))
