@@ -150,6 +150,8 @@ def main():
     ap.add_argument("--no-tree-verify", action="store_true", help="skip the C4-shaped verify-step measurement")
     ap.add_argument("--no-baselines", action="store_true", help="skip plain decoding and vanilla speculative decoding")
     ap.add_argument("--no-energy", action="store_true", help="skip the board-power measurement (about 10 s)")
+    ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: time and energy of one target pass at each "
+                    "(Section 4's observation that a run costs about the same for any small batch); not part of the default run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (requests are independent; more GPUs would each run this "
@@ -407,6 +409,32 @@ def main():
     if not args.no_energy and baselines is not None:
         energy = measure_energy(eng, w, tau, prompt, tm, dm, Engine, torch, dev)
 
+    # --- one target pass at several batch sizes (Section 4: the time and energy of a run barely depend on a small batch) ---------
+    batch_sweep = None
+    if args.batch_sweep:
+        batch_sweep = []
+        for nb in [int(x) for x in args.batch_sweep.split(",") if x]:
+            if nb * M > 256:
+                batch_sweep.append({"batch": nb, "error": "more than 256 rows in a pass"})
+                continue
+            eb = Engine(tm, dm, batch=nb, gamma=w.gamma, beam=w.beam, mode=w.mode, max_context=w.prompt_len + 64, device=dev,
+                        prefill_rows=max(M, min(64, 256 // nb)))
+            eb.prefill(np.repeat(prompt[:1], nb, axis=0))
+            eb.draft_phase(seed=w.seed)
+            for _ in range(3):
+                eb.verify_phase()
+            torch.cuda.synchronize()
+            n_it = max(50, int(2.0 / (verify_ms * 1e-3)))
+            with PowerSampler() as ps:
+                for _ in range(n_it):
+                    eb.verify_phase()
+                torch.cuda.synchronize()
+            sec = ps.t1 - ps.t0
+            batch_sweep.append({"batch": nb, "rows": nb * M, "ms_per_pass": round(sec / n_it * 1e3, 4),
+                                "J_per_pass": round(ps.joules() / n_it, 4) if ps.path else None,
+                                "ms_per_pass_per_sequence": round(sec / n_it * 1e3 / nb, 4)})
+            eb.close()
+
     # --- the oracle on the host cores, bounded sample ---------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -429,7 +457,7 @@ def main():
                                "block-efficiency table): a labelled projection, not a measurement"},
         "tau0": {"tokens_per_s": round(tokens0 / dt0, 2), "tokens_per_iteration": round(tokens0 / K / w.batch, 3),
                  "ms_per_step": round(dt0 / K * 1e3, 4)},
-        "warped": warped, "baselines": baselines, "energy": energy, "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
+        "warped": warped, "baselines": baselines, "energy": energy, "batch_sweep": batch_sweep, "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
         "device_status": status, "weights_setup_s": round(t_weights, 1),
     }
     print(json.dumps(out))
