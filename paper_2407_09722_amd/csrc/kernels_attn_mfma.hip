@@ -45,7 +45,8 @@ struct MfmaAttnSmem {
       _Float16 v[AW][ATK][VS];         // V tile of each wave
       _Float16 q[2][NRG * 16][VS];     // query rows, hi and lo halves
     } a;
-    float o[AW][NRG * 16][HD + 4];     // per-wave outputs for the final merge (padded rows: the 16 rows of a store land in different banks)
+    // per-wave outputs for the final merge, MRG row groups at a time (padded rows: the 16 rows of a store land in different banks)
+    float o[AW][(NRG <= 2 ? NRG : 1) * 16][HD + 4];
   };
   float m[AW][NRG * 16], l[AW][NRG * 16];
   int last;
@@ -114,24 +115,32 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const kv16_t* kbase = (const kv16_t*)kv.k + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
   const kv16_t* vbase = (const kv16_t*)kv.v + (int64_t)layer * kv.layer_stride + (int64_t)g * HD;
 
-  // K and V of the wave's first tile are requested before the queries are staged.  The loads are unconditional (keys past
-  // the end read token 0 of page 0): their scores are masked, and their V rows are zeroed so that they contribute exact zeros
-  KFrag kf[2][2][KS], vf[2][NV];
-  auto load_kv = [&](KFrag (&kfs)[2][KS], KFrag (&vfs)[NV], int tok32) {
+  // One register set for K and one for V: a tile's V registers are free once the tile is in LDS and its K registers once the
+  // score product has been issued, and the next tile's requests go out at those points (V, needed first, first).  The
+  // loads are unconditional (keys past the end read token 0 of page 0): their scores are masked, and their V rows are
+  // zeroed so that they contribute exact zeros.  The first tile is requested before the queries are staged.
+  KFrag kf[2][KS], vf[NV];
+  auto load_k = [&](int tok32) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
       const int tk = max(0, __shfl(tok32, blk * 16 + srow, 64));
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kfs[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
+      for (int ks = 0; ks < KS; ++ks) kf[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
     }
+  };
+  auto load_v = [&](int tok32) {
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int tk = __shfl(tok32, j * KPL + lane / CH, 64);
       const uint4 v = *(const uint4*)(vbase + (int64_t)max(0, tk) * tok_stride + (lane % CH) * 8);
-      vfs[j].u = tk >= 0 ? v : make_uint4(0, 0, 0, 0);
+      vf[j].u = tk >= 0 ? v : make_uint4(0, 0, 0, 0);
     }
   };
-  if (wave < n_tiles) load_kv(kf[0], vf[0], lookup(wave));
+  if (wave < n_tiles) {
+    const int tok = lookup(wave);
+    load_v(tok);
+    load_k(tok);
+  }
 
   // queries of the item as half hi / lo terms in LDS (rows beyond the item are zero)
   for (int i = t; i < RBK * (HD / 4); i += AW * 64) {
@@ -157,10 +166,13 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     for (int db = 0; db < DB; ++db) acc[rg][db] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto process = [&](const KFrag (&kfs)[2][KS], const KFrag (&vfs)[NV], int ti) {
+  auto process = [&](int ti) {
+    const bool more = ti + AW < n_tiles;                    // uniform over the wave
+    const int tok_next = more ? lookup(ti + AW) : -1;       // the page-table read of the next tile starts here
     // V tile -> wave-private LDS copy
 #pragma unroll
-    for (int j = 0; j < NV; ++j) *(uint4*)&sm.a.v[wave][j * KPL + lane / CH][(lane % CH) * 8] = vfs[j].u;
+    for (int j = 0; j < NV; ++j) *(uint4*)&sm.a.v[wave][j * KPL + lane / CH][(lane % CH) * 8] = vf[j].u;
+    if (more) load_v(tok_next);
 
     // S^T = K Q^T: lane (sg4, srow) gets keys blk*16 + sg4*4 + i of row rg*16 + srow
     floatx4 s2[NRG][2];
@@ -176,10 +188,11 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         const half8 ql = *(const half8*)&sm.a.q[1][rg * 16 + srow][ks * 32 + sg4 * 8];
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfs[blk][ks].h, qh, s2[rg][blk], 0, 0, 0);
-          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kfs[blk][ks].h, ql, s2[rg][blk], 0, 0, 0);
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, qh, s2[rg][blk], 0, 0, 0);
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, ql, s2[rg][blk], 0, 0, 0);
         }
       }
+    if (more) load_k(tok_next);  // the score product has read its K operands
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the V tile is in LDS (the wave reads what other lanes wrote)
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -238,19 +251,8 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the V tile has been read before the next one overwrites it
   };
-  // two register sets: while a tile is worked on, the next tile's loads are in flight; the sets swap by register moves so
-  // that the tile code exists once (a wave runs it only a few times: its size is paid for in instruction fetches)
 #pragma unroll 1
-  for (int ti = wave; ti < n_tiles; ti += AW) {
-    if (ti + AW < n_tiles) load_kv(kf[1], vf[1], lookup(ti + AW));
-    process(kf[0], vf[0], ti);
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[0][blk][ks].u = kf[1][blk][ks].u;
-#pragma unroll
-    for (int j = 0; j < NV; ++j) vf[0][j].u = vf[1][j].u;
-  }
+  for (int ti = wave; ti < n_tiles; ti += AW) process(ti);
   // ---- the waves meet in LDS (the buffer aliases the V tiles and the queries)
   const int mrow = t / TPR, md = (t % TPR) * DPT;  // merge role: row within a row group, first of DPT dims
   const int64_t lo_plane = (int64_t)B * R * n_heads * HD;
@@ -275,41 +277,46 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       sm.l[wave][rg * 16 + srow] = l_run[rg];
     }
   }
-  __syncthreads();  // everyone is done with the tiles
+  constexpr int MRG = NRG <= 2 ? NRG : 1;  // row groups the merge buffer holds at a time
 #pragma unroll
-  for (int rg = 0; rg < NRG; ++rg)
+  for (int rg0 = 0; rg0 < NRG; rg0 += MRG) {
+    __syncthreads();  // everyone is done with the tiles (first pass) / with the previous row groups' buffer
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-      *(float4*)&sm.o[wave][rg * 16 + srow][db * 16 + sg4 * 4] = make_float4(acc[rg][db][0], acc[rg][db][1], acc[rg][db][2], acc[rg][db][3]);
-  __syncthreads();
+    for (int rm = 0; rm < MRG; ++rm)
 #pragma unroll
-  for (int rg = 0; rg < NRG; ++rg) {
-    const int r = rg * 16 + mrow;
-    float M = -INFINITY;
+      for (int db = 0; db < DB; ++db)
+        *(float4*)&sm.o[wave][rm * 16 + srow][db * 16 + sg4 * 4] =
+            make_float4(acc[rg0 + rm][db][0], acc[rg0 + rm][db][1], acc[rg0 + rm][db][2], acc[rg0 + rm][db][3]);
+    __syncthreads();
 #pragma unroll
-    for (int w2 = 0; w2 < AW; ++w2) M = fmaxf(M, sm.m[w2][r]);
-    float L = 0.f, o[DPT];
+    for (int rm = 0; rm < MRG; ++rm) {
+      const int r = (rg0 + rm) * 16 + mrow;
+      float M = -INFINITY;
 #pragma unroll
-    for (int x = 0; x < DPT; ++x) o[x] = 0.f;
+      for (int w2 = 0; w2 < AW; ++w2) M = fmaxf(M, sm.m[w2][r]);
+      float L = 0.f, o[DPT];
 #pragma unroll
-    for (int w2 = 0; w2 < AW; ++w2) {  // wave order (deterministic)
-      const float mw = sm.m[w2][r];
-      const float e = (mw == -INFINITY) ? 0.f : expf(mw - M);
-      L += sm.l[w2][r] * e;
+      for (int x = 0; x < DPT; ++x) o[x] = 0.f;
 #pragma unroll
-      for (int x4 = 0; x4 < DPT; x4 += 4) {
-        const float4 v = *(const float4*)&sm.o[w2][r][md + x4];
-        o[x4] += v.x * e; o[x4 + 1] += v.y * e; o[x4 + 2] += v.z * e; o[x4 + 3] += v.w * e;
+      for (int w2 = 0; w2 < AW; ++w2) {  // wave order (deterministic)
+        const float mw = sm.m[w2][r];
+        const float e = (mw == -INFINITY) ? 0.f : expf(mw - M);
+        L += sm.l[w2][r] * e;
+#pragma unroll
+        for (int x4 = 0; x4 < DPT; x4 += 4) {
+          const float4 v = *(const float4*)&sm.o[w2][rm * 16 + mrow][md + x4];
+          o[x4] += v.x * e; o[x4 + 1] += v.y * e; o[x4 + 2] += v.z * e; o[x4 + 3] += v.w * e;
+        }
       }
-    }
-    if (r < nrows) {
-      if (eff == 1) {  // nothing to exchange: this workgroup saw every key
-        store_out(r, o, L);
-      } else {  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]); device-scope write-through stores
-        float* p = partial + ((((int64_t)seq * n_heads + pair_head(r)) * R + pair_row(r)) * n_splits + split) * (HD + 2);
+      if (r < nrows) {
+        if (eff == 1) {  // nothing to exchange: this workgroup saw every key
+          store_out(r, o, L);
+        } else {  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]); device-scope write-through stores
+          float* p = partial + ((((int64_t)seq * n_heads + pair_head(r)) * R + pair_row(r)) * n_splits + split) * (HD + 2);
 #pragma unroll
-        for (int x = 0; x < DPT; x += 2) st8<true>(p + 2 + md + x, make_uint2(__float_as_uint(o[x]), __float_as_uint(o[x + 1])));
-        if (t % TPR == 0) st8<true>(p, make_uint2(__float_as_uint(M), __float_as_uint(L)));
+          for (int x = 0; x < DPT; x += 2) st8<true>(p + 2 + md + x, make_uint2(__float_as_uint(o[x]), __float_as_uint(o[x + 1])));
+          if (t % TPR == 0) st8<true>(p, make_uint2(__float_as_uint(M), __float_as_uint(L)));
+        }
       }
     }
   }
@@ -327,7 +334,7 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   __syncthreads();
   if (!sm.last) return;
   // all row groups' loads of a batch of splits are issued together: the exchange is latency, not volume
-  constexpr int SB = 8;  // splits per batch
+  constexpr int SB = NRG <= 2 ? 8 : 4;  // splits per batch
   float M2[NRG], L2[NRG], o2[NRG][DPT];
   const float* pp[NRG];
 #pragma unroll
@@ -412,6 +419,8 @@ hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd
   if (kv.n_kv_heads < 1 || n_heads % kv.n_kv_heads) return hipErrorInvalidValue;
   const int pairs = n_heads / kv.n_kv_heads * R;  // (query head, row) pairs that share a KV head
   if (hd == 128 && pairs <= 16) return run_mfma<128, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
+  if (hd == 128 && pairs > 32 && pairs <= 48)  // one item instead of two that would each read K and V
+    return run_mfma<128, 3, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (hd == 128) return run_mfma<128, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (hd == 64 && pairs <= 16) return run_mfma<64, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (hd == 64) return run_mfma<64, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
