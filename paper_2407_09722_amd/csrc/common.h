@@ -24,6 +24,16 @@ __device__ __forceinline__ void split_bf16(float x, bf16_t& hi, bf16_t& lo) {
   lo = f32_to_bf16(x - bf16_to_f32(hi));
 }
 
+// Element offset of activation (plane, row, feature k) of a pass of R rows and K features.  ncg == 0: two planes
+// [2][R][K].  ncg > 0 (= ceil(R / 8)): operand-fragment order [K/32][ncg][64 lanes][8], the B operand of
+// v_mfma_f32_16x16x32_bf16 for 8 rows at a time: lane (k%32)/8 * 16 + plane * 8 + row % 8 of fragment (k / 32, row / 8)
+// holds 8 consecutive features.  Products of passes with more than 8 rows read this order (whole cache lines per
+// fragment instead of 64-byte pieces of 16 rows); whatever produces their input writes it.
+__host__ __device__ __forceinline__ int64_t act_offset(int ncg, int R, int K, int plane, int row, int k) {
+  if (ncg == 0) return ((int64_t)plane * R + row) * K + k;
+  return ((((int64_t)(k >> 5) * ncg + (row >> 3)) * 64 + ((k >> 3) & 3) * 16 + plane * 8 + (row & 7)) << 3) + (k & 7);
+}
+
 // Device-scope ("coherent") accesses for data that workgroups of ONE kernel hand to each other.  The XCDs' L2
 // caches are not coherent with each other; relaxed device-scope atomics compile to write-through stores and
 // cache-bypassing loads, which avoids flushing or invalidating whole caches.  COH = false: plain accesses (data
@@ -88,10 +98,10 @@ struct RowDesc {
 };
 
 // ---- launchers (kernels_*.hip) ----------------------------------------------------------------
-// h = E[tok]; bf16 models also get the first RMSNorm's input: planes [2][rows][d] of h*g0 and ssq[rows] = sum h^2;
+// h = E[tok]; bf16 models also get the first RMSNorm's input: h*g0 as two bf16 terms (layout: act_offset with ncg) and ssq[rows] = sum h^2;
 // and the rotary table of the rows' positions, table[rows][head_dim/2] = (cos, sin)
 hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, const float* g0,
-                        void* planes, float* ssq, const int32_t* pos, float2* table, int head_dim, float theta, hipStream_t s);
+                        void* planes, float* ssq, const int32_t* pos, float2* table, int head_dim, float theta, int ncg, hipStream_t s);
 // out = rmsnorm(h) * g, written as hi/lo bf16 planes [2][rows][d] (dtype 1) or f32 [rows][d] (dtype 0)
 hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, int rows, int d, float eps, hipStream_t s);
 // rotate q (in place in qkv, float32), rotate k and write k, v to the cache in its storage type
@@ -100,11 +110,11 @@ hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowD
 // q: [rows][q_stride] float32 with head h at column h*head_dim; counters: zeroed ints [B][n_heads][ceil(R/8)]
 // (bf16 models work on chunks of 8 rows, float32 models on chunks of 16)
 hipError_t launch_attention(int dtype, const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
-                            float* partial, int n_splits, int* counters, void* out, hipStream_t s);
-// bf16 models (kernels_attn_mfma.hip): half-precision cache, output = bf16 hi / lo planes; n_splits = upper bound on the
-// key splits (the kernel uses fewer for short contexts)
+                            float* partial, int n_splits, int* counters, void* out, int ncg, hipStream_t s);
+// bf16 models (kernels_attn_mfma.hip): half-precision cache, output = bf16 hi / lo terms (layout: act_offset with ncg);
+// n_splits = upper bound on the key splits (the kernel uses fewer for short contexts)
 hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
-                                 float* partial, int n_splits, int* counters, void* out, hipStream_t s);
+                                 float* partial, int n_splits, int* counters, void* out, int ncg, hipStream_t s);
 // lse[row] from per-strip (max, sum exp) partials [rows][NP]
 hipError_t launch_lse_finish(const float* lse_part, float* lse, int rows, int NP, hipStream_t s);
 // lse as above for B*M rows, plus logp_cond[s][c] = logits[s][parent(c)][tok(c)] - lse[s][parent(c)] (0 for c = 0)

@@ -9,8 +9,9 @@ enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
 
 struct GemmArgs {
   const bf16_t* W;   // tile-packed [N/16][K/32][64 lanes][8]
-  const bf16_t* X;   // two bf16 planes [2][R][K]: activation = hi + lo
+  const bf16_t* X;   // activation = hi + lo, two bf16 terms: planes [2][R][K] (ncg == 0) or operand-fragment order (act_offset)
   int R, N, K;
+  int ncg;           // 0, or ceil(R / 8): X, planes_out and act_out are in operand-fragment order
   int row0;          // first row handled by this launch (set by the launcher; 64 rows per launch)
   // rows are multiplied by 1/sqrt(sum_p ssq[m][p] / K + eps) when ssq != null (fused RMSNorm of the input)
   const float* ssq;

@@ -60,8 +60,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int nt, floatx4
         split_bf16(hn.y * gn.y, hi.y, lo.y);
         split_bf16(hn.z * gn.z, hi.z, lo.z);
         split_bf16(hn.w * gn.w, hi.w, lo.w);
-        st8<COH>(a.planes_out + (int64_t)m * a.N + n, *(uint2*)&hi);
-        st8<COH>(a.planes_out + (int64_t)R * a.N + (int64_t)m * a.N + n, *(uint2*)&lo);
+        st8<COH>(a.planes_out + act_offset(a.ncg, R, a.N, 0, m, n), *(uint2*)&hi);
+        st8<COH>(a.planes_out + act_offset(a.ncg, R, a.N, 1, m, n), *(uint2*)&lo);
       }
       float q = hn.x * hn.x + hn.y * hn.y + hn.z * hn.z + hn.w * hn.w;
       q += __shfl_xor(q, 16, 64);
@@ -84,9 +84,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int nt, floatx4
             const float gate = s[e] * inv, up = t[e] * inv;
             split_bf16(gate / (1.0f + expf(-gate)) * up, hip[e], lop[e]);
           }
-          const int64_t o = (int64_t)m * f + nt * 8 + i0;
-          st8<COH>(a.act_out + o, *(uint2*)&hi);
-          st8<COH>(a.act_out + (int64_t)R * f + o, *(uint2*)&lo);
+          st8<COH>(a.act_out + act_offset(a.ncg, R, f, 0, m, nt * 8 + i0), *(uint2*)&hi);
+          st8<COH>(a.act_out + act_offset(a.ncg, R, f, 1, m, nt * 8 + i0), *(uint2*)&lo);
         } else {  // EPI_QKV
           const int hd = a.kv.head_dim, half = hd >> 1, tph = hd >> 4;
           const int head = nt / tph, i = (nt % tph) * 8 + i0;

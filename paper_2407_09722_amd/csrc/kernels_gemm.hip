@@ -79,16 +79,43 @@ __device__ __forceinline__ void gemm_load_w(Frag (&w)[U], const char* strip, int
     if (kt + u * GW < KT) w[u].n = __builtin_nontemporal_load((const uintx4*)(base + (size_t)u * (GW << 10) + voff));
 }
 
+// Activation fragments of k tiles kt + u*GW for NG row groups.  X + xoff is this lane's 16 bytes of (row group 0, k tile 0);
+// a k tile is kstride bytes further, a row group gstride bytes (plane layout: 64 and 16 K; fragment order: 1024 x the
+// pass's row groups and 1024).
 template <int NG, int U>
-__device__ __forceinline__ void gemm_load_b(Frag (&b)[U][NG], const char* X, unsigned xoff, int K, int KT, int kt, int rows_here, int c) {
+__device__ __forceinline__ void gemm_load_b(Frag (&b)[U][NG], const char* X, unsigned xoff, size_t kstride, size_t gstride, int KT, int kt,
+                                            int rows_here, int c) {
 #pragma unroll
   for (int u = 0; u < U; ++u)
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
       b[u][g].u = make_uint4(0, 0, 0, 0);
-      const char* base = X + ((size_t)g * 8 * K + (size_t)(kt + u * GW) * 32) * 2;
+      const char* base = X + (size_t)g * gstride + (size_t)(kt + u * GW) * kstride;
       if (kt + u * GW < KT && g * 8 + (c & 7) < rows_here) b[u][g].u = *(const uint4*)(base + xoff);
     }
+}
+
+// (X base of the launch's first row, lane offset, k tile stride, row group stride) for either activation layout
+struct ActAddr {
+  const char* X;
+  unsigned xoff;
+  size_t kstride, gstride;
+};
+__device__ __forceinline__ ActAddr act_addr(const GemmArgs& a, int lane) {
+  const int c = lane & 15, kg = lane >> 4;
+  ActAddr r;
+  if (a.ncg == 0) {
+    r.X = (const char*)a.X + (size_t)a.row0 * a.K * 2;
+    r.xoff = (unsigned)((((size_t)(c >> 3) * a.R + (c & 7)) * a.K + kg * 8) * 2);  // plane c/8, row c%8, k group kg
+    r.kstride = 64;
+    r.gstride = (size_t)16 * a.K;
+  } else {
+    r.X = (const char*)a.X + (size_t)(a.row0 >> 3) * 1024;  // launches start at multiples of 8 rows
+    r.xoff = (unsigned)lane * 16u;
+    r.kstride = (size_t)a.ncg * 1024;
+    r.gstride = 1024;
+  }
+  return r;
 }
 
 template <int NG, int EPI, int TAG>
@@ -107,14 +134,13 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
   // (wave-uniform base) + (32-bit lane offset): the scalar-base addressing mode, one offset register per stream
   const char* strip = (const char*)a.W + (((size_t)nt * KT) << 10);
   const unsigned voff = (unsigned)lane * 16u;
-  const char* X = (const char*)a.X + (size_t)row0 * K * 2;
-  const unsigned xoff = (unsigned)((((size_t)(c >> 3) * R + (c & 7)) * K + kg * 8) * 2);  // plane c/8, row c%8, k group kg
+  const ActAddr xa = act_addr(a, lane);
 
   constexpr int span = U * GW;
   Frag w[2][U], b[2][U][NG];
-  gemm_load_b<NG, U>(b[0], X, xoff, K, KT, wave, rows_here, c);
+  gemm_load_b<NG, U>(b[0], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, wave, rows_here, c);
   gemm_load_w<U>(w[0], strip, KT, wave, voff);
-  gemm_load_b<NG, U>(b[1], X, xoff, K, KT, wave + span, rows_here, c);
+  gemm_load_b<NG, U>(b[1], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, wave + span, rows_here, c);
   gemm_load_w<U>(w[1], strip, KT, wave + span, voff);
 
   floatx4 acc[NG];
@@ -132,7 +158,7 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
           for (int g = 0; g < NG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[h][u].v, b[h][u][g].v, acc[g], 0, 0, 0);
         }
       if (k0 + 2 * span < KT) {
-        gemm_load_b<NG, U>(b[h], X, xoff, K, KT, k0 + 2 * span, rows_here, c);
+        gemm_load_b<NG, U>(b[h], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, k0 + 2 * span, rows_here, c);
         gemm_load_w<U>(w[h], strip, KT, k0 + 2 * span, voff);
       }
     }
@@ -173,8 +199,7 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
   const char* strip0 = (const char*)a.W + (((size_t)nt0 * KT_all) << 10);
   const size_t strip_bytes = (size_t)KT_all << 10;
   const unsigned voff = (unsigned)lane * 16u;
-  const char* X = (const char*)a.X + (size_t)row0 * K * 2;
-  const unsigned xoff = (unsigned)((((size_t)(c >> 3) * R + (c & 7)) * K + kg * 8) * 2);
+  const ActAddr xa = act_addr(a, lane);
 
   Frag w[2][SM], b[2][1][NG];
   auto load_w = [&](Frag (&ws)[SM], int kt) {
@@ -182,9 +207,9 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
     for (int s2 = 0; s2 < SM; ++s2)
       if (s2 < ns && kt < KT) ws[s2].n = __builtin_nontemporal_load((const uintx4*)(strip0 + s2 * strip_bytes + ((size_t)kt << 10) + voff));
   };
-  gemm_load_b<NG, 1>(b[0], X, xoff, K, KT, k_lo + wave, rows_here, c);
+  gemm_load_b<NG, 1>(b[0], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, k_lo + wave, rows_here, c);
   load_w(w[0], k_lo + wave);
-  gemm_load_b<NG, 1>(b[1], X, xoff, K, KT, k_lo + wave + GW, rows_here, c);
+  gemm_load_b<NG, 1>(b[1], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, k_lo + wave + GW, rows_here, c);
   load_w(w[1], k_lo + wave + GW);
 
   floatx4 acc[SM][NG];
@@ -206,7 +231,7 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
           }
       }
       if (k0 + 2 * GW < KT) {
-        gemm_load_b<NG, 1>(b[h], X, xoff, K, KT, k0 + 2 * GW, rows_here, c);
+        gemm_load_b<NG, 1>(b[h], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, k0 + 2 * GW, rows_here, c);
         load_w(w[h], k0 + 2 * GW);
       }
     }
@@ -407,7 +432,7 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
 // the 7B- and 13B-shaped products: it wins from 65 rows up everywhere, and from 25 rows up for products wide enough
 // to give every compute unit a workgroup of 8 strips.
 static bool use_tiled(const GemmArgs& a) {
-  if (!a.xfrag || a.xfrag_elems < gemm_tiled_xfrag_elems(a.R, a.K)) return false;  // needs its scratch
+  if (!a.ncg && (!a.xfrag || a.xfrag_elems < gemm_tiled_xfrag_elems(a.R, a.K))) return false;  // needs fragment order or its scratch
   return a.R >= 65 || (a.R >= 25 && gemm_tiled_wide(a.N));
 }
 

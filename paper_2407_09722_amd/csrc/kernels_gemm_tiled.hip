@@ -102,11 +102,20 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   const unsigned voff = (unsigned)lane * 16u;
   static_assert(TW % SK == 0, "a wave stages the same k tile of every fragment it takes");
   const int xkk = wave % SK;  // (i*TW + wave) % SK for every i
-  const char* const XF = (const char*)a.xfrag;
+  // activations in operand-fragment order: the pass's own buffer when its producer wrote that order (a.ncg row groups per
+  // k tile, this launch's first one at row0 / 8), else the scratch copy xfrag_kernel made of this launch's rows (NCG per
+  // k tile).  Column groups beyond the pass's last one read that last one: their columns are never stored.
+  const char* const XF = a.ncg ? (const char*)a.X + (size_t)(row0 >> 3) * 1024 : (const char*)a.xfrag;
+  const int xncg = a.ncg ? a.ncg : NCG;
+  const int cg_last = a.ncg ? a.ncg - (row0 >> 3) - 1 : NCG - 1;
+  unsigned xsrc[FPW];
+#pragma unroll
+  for (int i = 0; i < FPW; ++i) xsrc[i] = (unsigned)min((i * TW + wave) / SK, cg_last) * 1024u + voff;
   auto load_x = [&](uintx4 (&xr)[FPW], int t) {  // stage t of this workgroup's range
     const int kt = min((st_lo + t) * SK + xkk, KT_all - 1);
+    const char* base = XF + (size_t)kt * xncg * 1024;
 #pragma unroll
-    for (int i = 0; i < FPW; ++i) xr[i] = *(const uintx4*)(XF + ((((size_t)kt * NCG + (i * TW + wave) / SK) * 64) << 4) + voff);
+    for (int i = 0; i < FPW; ++i) xr[i] = *(const uintx4*)(base + xsrc[i]);
   };
   const char* const W = (const char*)a.W;
   auto load_w = [&](Frag (&wr)[WPW], int t) {
@@ -326,7 +335,7 @@ hipError_t run_shape(const GemmArgs& a, hipStream_t s) {
   static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
   if (attr != hipSuccess) return attr;
   const int NT = a.N >> 4, tiles = (NT + Sh::TN - 1) / Sh::TN;
-  {  // this pass's activations in fragment order
+  if (!a.ncg) {  // this launch's activations in fragment order (a pass that already holds them that way needs no copy)
     const int64_t frags = (int64_t)(a.K >> 5) * Sh::NCG;
     if ((size_t)frags * 512 > a.xfrag_elems) return hipErrorInvalidValue;
     const int rows = a.R - a.row0 < Sh::NCG * 8 ? a.R - a.row0 : Sh::NCG * 8;

@@ -41,7 +41,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok, float* __restrict__ h, int d,
                                                     int vocab, const float* __restrict__ g0, bf16_t* __restrict__ planes,
                                                     float* __restrict__ ssq, const int32_t* __restrict__ pos, float2* __restrict__ table,
-                                                    int half, float theta) {
+                                                    int half, float theta, int ncg) {
   __shared__ float sh[4];
   const int row = blockIdx.x;
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
@@ -54,7 +54,6 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
   int t = tok[row];
   if (t < 0 || t >= vocab) t = 0;  // inactive rows carry no meaningful token
   const T* e = E + (int64_t)t * d;
-  const int64_t lo_plane = (int64_t)gridDim.x * d;
   float ss = 0.f;
   for (int i = threadIdx.x * 4; i < d; i += blockDim.x * 4) {  // d is a multiple of 4 (checked at create)
     float v[4];
@@ -77,8 +76,8 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
       ss += v[1] * v[1];
       ss += v[2] * v[2];
       ss += v[3] * v[3];
-      *(ushort4*)(planes + (int64_t)row * d + i) = hi;
-      *(ushort4*)(planes + lo_plane + (int64_t)row * d + i) = lo;
+      *(ushort4*)(planes + act_offset(ncg, (int)gridDim.x, d, 0, row, i)) = hi;
+      *(ushort4*)(planes + act_offset(ncg, (int)gridDim.x, d, 1, row, i)) = lo;
     }
   }
   if (planes) {
@@ -88,14 +87,14 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
 }
 
 hipError_t launch_embed(int dtype, const void* E, const int32_t* tok, float* h, int rows, int d, int vocab, const float* g0,
-                        void* planes, float* ssq, const int32_t* pos, float2* table, int head_dim, float theta, hipStream_t s) {
+                        void* planes, float* ssq, const int32_t* pos, float2* table, int head_dim, float theta, int ncg, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (dtype == 1)
     hipLaunchKernelGGL((embed_kernel<bf16_t>), dim3(rows), dim3(256), 0, s, (const bf16_t*)E, tok, h, d, vocab, g0, (bf16_t*)planes, ssq, pos,
-                       table, head_dim / 2, theta);
+                       table, head_dim / 2, theta, ncg);
   else
     hipLaunchKernelGGL((embed_kernel<float>), dim3(rows), dim3(256), 0, s, (const float*)E, tok, h, d, vocab, nullptr, nullptr, nullptr, pos,
-                       table, head_dim / 2, theta);
+                       table, head_dim / 2, theta, 0);
   return hipGetLastError();
 }
 

@@ -170,7 +170,7 @@ __global__ __launch_bounds__(PT) void pass_kernel(const PassArgs* args) {
     } else {
       GemmArgs a;
       a.W = (const bf16_t*)st->W; a.N = st->N; a.K = st->K; a.layer = st->layer;
-      a.R = rows; a.row0 = 0; a.eps = A->eps;
+      a.R = rows; a.row0 = 0; a.ncg = 0; a.eps = A->eps;  // activations as planes
       const bool normed = kind == STEP_QKV || kind == STEP_GATE_UP || kind == STEP_HEAD;  // input = planes of h*gain
       a.X = st->X;
       a.ssq = normed ? A->ssq : nullptr;

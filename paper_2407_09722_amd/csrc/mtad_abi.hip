@@ -30,6 +30,7 @@ struct mtad_ctx {
   float* gemm_part;  // k-split partial sums of the product kernel (products with few strips, more than 8 rows)
   int* gemm_cnt;
   int gemm_cnt_n;
+  int pass_ncg;    // activation layout of the pass in flight (0 planes, else row groups of the fragment order): its lm_head reads it
   int warp_k;      // > 0: next-token distributions of both models are warped (mtad_set_warp)
   float warp_p;
   bf16_t* gemm_xfrag;  // scratch of the many-row product kernel: a pass's activations in operand-fragment order
@@ -110,8 +111,9 @@ void carve(mtad_ctx* c, char* base) {
   Carver k(base);
   c->status = k.take<uint32_t>(64);
   c->h = k.take<float>(rows * dmax);
-  c->xn = k.take<float>(rows * imax(imax(dmax, hhd), fmax));
-  c->xg = k.take<float>(rows * dmax);
+  const size_t rows8 = (rows + 7) / 8 * 8;  // operand-fragment order holds whole groups of 8 rows
+  c->xn = k.take<float>(rows8 * imax(imax(dmax, hhd), fmax));
+  c->xg = k.take<float>(rows8 * dmax);
   c->ssq = k.take<float>(rows * (size_t)(dmax / 16 + 1));
   c->lse_part = k.take<float>(rows * (size_t)(imax(t.vocab, d.vocab) / 16 + 1) * 2);
   c->attn_cnt_n = (size_t)c->cfg.batch * imax(t.n_heads, d.n_heads) * (size_t)((c->Rmax + 7) / 8);
@@ -227,13 +229,13 @@ int decoder_pass_f32(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R,
   const KvView kvv = view_of(kv, m);
   const int n_splits = splits_for(c, m, R);
   const void* const* W = m->weights;
-  HIP_TRY(c, launch_embed(0, W[0], c->rd.tok, c->h, rows, d, m->vocab, nullptr, nullptr, nullptr, c->rd.pos, c->rope, hd, m->rope_theta, s));
+  HIP_TRY(c, launch_embed(0, W[0], c->rd.tok, c->h, rows, d, m->vocab, nullptr, nullptr, nullptr, c->rd.pos, c->rope, hd, m->rope_theta, 0, s));
   for (int l = 0; l < m->n_layers; ++l) {
     const void* const* L = W + 1 + 6 * l;
     HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)L[0], c->xn, rows, d, m->rms_eps, s));
     HIP_TRY(c, launch_gemm_f32(L[1], c->xn, c->qkv, rows, qkvw, d, qkvw, false, s));
     HIP_TRY(c, launch_rope_kv(0, c->qkv, c->rope, c->rd, kvv, l, B, R, H, c->status, s));
-    HIP_TRY(c, launch_attention(0, c->qkv, qkvw, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->attn_cnt, c->xn, s));
+    HIP_TRY(c, launch_attention(0, c->qkv, qkvw, c->rd, kvv, l, B, R, H, c->partial, n_splits, c->attn_cnt, c->xn, 0, s));
     HIP_TRY(c, launch_gemm_f32(L[2], c->xn, c->h, rows, d, H * hd, d, true, s));
     HIP_TRY(c, launch_rmsnorm(0, c->h, (const float*)L[3], c->xn, rows, d, m->rms_eps, s));
     HIP_TRY(c, launch_gemm_f32(L[4], c->xn, c->gu, rows, 2 * f, d, 2 * f, false, s));
@@ -259,8 +261,12 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
   const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
+  // passes of more than 8 rows keep their activations in operand-fragment order (act_offset); the persistent kernel and
+  // passes of one row group use planes
+  const int ncg = (!persistent && rows > 8) ? (rows + 7) / 8 : 0;
+  c->pass_ncg = ncg;
   HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, c->rd.pos, c->rope, hd, m->rope_theta,
-                          s));
+                          ncg, s));
   if (persistent) {  // every layer (and the lm_head) in one launch
     // step list of this model: built on the host, uploaded when it differs from both cached lists
     PassStep built[pass_steps(PASS_MAX_LAYERS, true)];
@@ -299,6 +305,7 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.R = rows;
+    a.ncg = ncg;
     a.eps = m->rms_eps;
     a.part = c->gemm_part;
     a.counters = c->gemm_cnt;
@@ -310,7 +317,7 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     a.q_out = c->qkv; a.rope = c->rope; a.slot = c->rd.slot; a.kv = kvv; a.layer = l; a.Rseq = R; a.n_heads = H; a.status = c->status;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_QKV, tag, s));
     HIP_TRY(c, launch_attention(1, c->qkv, H * hd, c->rd, kvv, l, B, R, H, c->partial, imin(32, (c->cfg.max_context + 127) / 128), c->attn_cnt,
-                                c->xn, s));
+                                c->xn, ncg, s));
     // o projection + residual; prepares the FFN's normalised input
     a.W = (const bf16_t*)L[2]; a.X = (const bf16_t*)c->xn; a.N = d; a.K = H * hd;
     a.ssq = nullptr; a.NP = 0;
@@ -346,6 +353,7 @@ int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* ls
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.W = (const bf16_t*)W[tail + 1]; a.X = (const bf16_t*)c->xg; a.R = rows; a.N = m->vocab; a.K = m->d_model;
+    a.ncg = c->pass_ncg;
     a.ssq = c->ssq; a.NP = m->d_model / 16; a.eps = m->rms_eps;
     a.Y = logits; a.ldy = m->vocab; a.lse_part = c->lse_part;
     a.part = c->gemm_part; a.counters = c->gemm_cnt; a.xfrag = c->gemm_xfrag; a.xfrag_elems = c->gemm_xfrag_n;
