@@ -261,9 +261,9 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
   const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
-  // passes of more than 8 rows keep their activations in operand-fragment order (act_offset); the persistent kernel and
-  // passes of one row group use planes
-  const int ncg = (!persistent && rows > 8) ? (rows + 7) / 8 : 0;
+  // one kernel per step: activations in operand-fragment order (act_offset), whole cache lines per fragment; the
+  // persistent kernel reads planes
+  const int ncg = persistent ? 0 : (rows + 7) / 8;
   c->pass_ncg = ncg;
   HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, c->rd.pos, c->rope, hd, m->rope_theta,
                           ncg, s));
