@@ -7,9 +7,9 @@
 // round-robin to the waves; every wave runs its own online softmax over its tiles, with the K and V of the next tile in
 // flight, and the waves merge through LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup,
 // which writes the attention output itself: no exchange through global memory.  Longer contexts are cut into splits
-// (at least one tile per wave each, at most as many as fill the machine once) and the workgroup that arrives last
-// merges the splits in split order (same partial layout and protocol as the generic kernel), with the loads of all
-// its rows in flight together: that exchange is a chain of memory latencies, not volume.
+// (at least one tile per wave each, at most as many as fill the machine once); every split leaves (max, sum, output)
+// per row in global memory (same partial layout as the generic kernel) and a small second kernel, one wave per row,
+// merges them in split order.
 //
 // Both products run on the matrix cores, transposed, so that every operand is cheap to fetch:
 //   S^T = K Q^T   A operand = 8 consecutive dims of one key per lane = 16 contiguous bytes of a cache row, loaded from
@@ -49,7 +49,6 @@ struct MfmaAttnSmem {
     float o[AW][(NRG <= 2 ? NRG : 1) * 16][HD + 4];
   };
   float m[AW][NRG * 16], l[AW][NRG * 16];
-  int last;
 };
 
 __device__ __forceinline__ float xmax(float v, int off) { return fmaxf(v, __shfl_xor(v, off, 64)); }
@@ -60,6 +59,18 @@ __device__ __forceinline__ int token_index(const KvView& kv, int seq, int pos) {
   int page = kv.page_table[(int64_t)seq * kv.max_pages + pos / kv.page_size];
   page = (page < 0 || page >= kv.n_pages) ? 0 : page;
   return page * kv.page_size + pos % kv.page_size;
+}
+
+// Keys of sequence seq (committed + speculative) and the key splits used for it.  Every workgroup of the attention
+// kernel and of the merge kernel derives the same numbers: as many splits as the launch offers, but a split is worth its
+// exchange only if it gives every wave a tile (measured at 512 and 2048 keys).
+constexpr int ATTN_WAVES = 4;
+__device__ __forceinline__ int attn_keys(const KvView& kv, const RowDesc& rd, int seq) {
+  const int nspec = max(0, min(rd.nspec[seq], 64));
+  return min(kv.len[seq] + nspec, kv_capacity(kv));
+}
+__device__ __forceinline__ int attn_splits(int ktot, int n_splits, int want_splits) {
+  return max(1, min(min(n_splits, want_splits), ktot / (ATTN_WAVES * ATK)));
 }
 
 template <int HD, int NRG, int AW>
@@ -88,13 +99,10 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   const int pair0 = chunk * RBK, nrows = min(RBK, G * R - pair0);
   auto pair_head = [&](int r) { return g * G + (pair0 + r) / R; };  // query head and tree row of pair r of this item
   auto pair_row = [&](int r) { return (pair0 + r) % R; };
+  static_assert(AW == ATTN_WAVES, "attn_splits() assumes this many waves");
   const int len = kv.len[seq];
-  const int nspec = max(0, min(rd.nspec[seq], 64));
-  const int ktot = min(len + nspec, kv_capacity(kv));
-
-  // splits actually used for this sequence (all workgroups agree on this): as many as fill the machine once, but a
-  // split is worth its exchange only if it gives every wave a tile (measured at 512 and 2048 keys)
-  const int eff = max(1, min(min(n_splits, want_splits), ktot / (AW * ATK)));
+  const int ktot = attn_keys(kv, rd, seq);
+  const int eff = attn_splits(ktot, n_splits, want_splits);  // splits actually used for this sequence
   if (split >= eff) return;
   int per = (ktot + eff - 1) / eff;
   per = ((per + ATK - 1) / ATK) * ATK;
@@ -310,76 +318,76 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
       if (r < nrows) {
         if (eff == 1) {  // nothing to exchange: this workgroup saw every key
           store_out(r, o, L);
-        } else {  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]); device-scope write-through stores
+        } else {  // partial[seq][head][row][split][HD+2] = (m, l, acc[HD]) for the merge kernel
           float* p = partial + ((((int64_t)seq * n_heads + pair_head(r)) * R + pair_row(r)) * n_splits + split) * (HD + 2);
 #pragma unroll
-          for (int x = 0; x < DPT; x += 2) st8<true>(p + 2 + md + x, make_uint2(__float_as_uint(o[x]), __float_as_uint(o[x + 1])));
-          if (t % TPR == 0) st8<true>(p, make_uint2(__float_as_uint(M), __float_as_uint(L)));
+          for (int x = 0; x < DPT; x += 2) st8<false>(p + 2 + md + x, make_uint2(__float_as_uint(o[x]), __float_as_uint(o[x + 1])));
+          if (t % TPR == 0) st8<false>(p, make_uint2(__float_as_uint(M), __float_as_uint(L)));
         }
       }
     }
   }
-  if (eff == 1) return;
+}
 
-  // the workgroup that arrives last merges the splits of its rows (split order: deterministic)
-  __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
-  __syncthreads();
-  if (t == 0) {
-    int* c = counters + ((int64_t)seq * KVH + g) * n_chunks + chunk;
-    const int prev = __hip_atomic_fetch_add(c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    sm.last = (prev == eff - 1);
-    if (sm.last) __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
-  }
-  __syncthreads();
-  if (!sm.last) return;
-  // all row groups' loads of a batch of splits are issued together: the exchange is latency, not volume
-  constexpr int SB = NRG <= 2 ? 8 : 4;  // splits per batch
-  float M2[NRG], L2[NRG], o2[NRG][DPT];
-  const float* pp[NRG];
+// Merge of the key splits, a kernel of its own: one wave per (sequence, query head, row) adds the eff partial results in
+// split order (deterministic) with all their loads in flight together, and writes the normalised row as bf16 hi / lo
+// terms.  As a separate launch it is spread over the whole machine and costs about the same for any number of
+// splits, where the last workgroup of an item merging inside the attention kernel (the first design: 3.3 us of 13.1 at
+// 4 splits and 5 rows, 8 us of 28 at 8 splits and 17 rows) made more splits cost more than they gained.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_merge_kernel(RowDesc rd, KvView kv, int B, int R, int n_heads, const float* __restrict__ partial,
+                                                         int n_splits, int want_splits, bf16_t* __restrict__ out, int ncg) {
+  constexpr int DPL = HD / 64;  // output dims per lane
+  const int lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);  // (seq, head, row)
+  if (item >= B * n_heads * R) return;
+  const int row = item % R, head = (item / R) % n_heads, seq = item / (R * n_heads);
+  const int eff = attn_splits(attn_keys(kv, rd, seq), n_splits, want_splits);
+  if (eff == 1) return;  // the attention kernel wrote the output itself
+  const float* pp = partial + (((int64_t)seq * n_heads + head) * R + row) * n_splits * (HD + 2);
+  float M = -INFINITY, L = 0.f, o[DPL];
 #pragma unroll
-  for (int rg = 0; rg < NRG; ++rg) {
-    const int r = (rg * 16 + mrow < nrows) ? rg * 16 + mrow : 0;  // threads without a row read pair 0 and drop it
-    pp[rg] = partial + (((int64_t)seq * n_heads + pair_head(r)) * R + pair_row(r)) * n_splits * (HD + 2);
-    M2[rg] = -INFINITY;
-    L2[rg] = 0.f;
-#pragma unroll
-    for (int x = 0; x < DPT; ++x) o2[rg][x] = 0.f;
-  }
+  for (int x = 0; x < DPL; ++x) o[x] = 0.f;
+  constexpr int SB = 8;  // splits per batch
   for (int s0 = 0; s0 < eff; s0 += SB) {
-    unsigned long long ml[NRG][SB];
-    uint4 oo[NRG][SB][DPT / 4];
+    float2 ml[SB];
+    float ov[SB][DPL];
 #pragma unroll
-    for (int rg = 0; rg < NRG; ++rg)
-#pragma unroll
-      for (int j = 0; j < SB; ++j) {
-        const float* ps = pp[rg] + (int64_t)min(s0 + j, eff - 1) * (HD + 2);
-        ml[rg][j] = __hip_atomic_load((const unsigned long long*)ps, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int x4 = 0; x4 < DPT / 4; ++x4) oo[rg][j][x4] = ld16<true>(ps + 2 + md + x4 * 4);
+    for (int j = 0; j < SB; ++j) {
+      const float* ps = pp + (int64_t)min(s0 + j, eff - 1) * (HD + 2);
+      ml[j] = *(const float2*)ps;
+      if constexpr (DPL == 2) {
+        const float2 v = *(const float2*)(ps + 2 + lane * 2);
+        ov[j][0] = v.x;
+        ov[j][1] = v.y;
+      } else {
+        ov[j][0] = ps[2 + lane];
       }
+    }
 #pragma unroll
-    for (int rg = 0; rg < NRG; ++rg)
+    for (int j = 0; j < SB; ++j) {
+      const float mj = ml[j].x, lj = ml[j].y;
+      if (s0 + j >= eff || mj == -INFINITY) continue;
+      const float Mn = fmaxf(M, mj);
+      const float ws = (M == -INFINITY) ? 0.f : expf(M - Mn), wj = expf(mj - Mn);
+      L = L * ws + lj * wj;
 #pragma unroll
-      for (int j = 0; j < SB; ++j) {
-        const float mj = __uint_as_float((uint32_t)ml[rg][j]), lj = __uint_as_float((uint32_t)(ml[rg][j] >> 32));
-        if (s0 + j >= eff || mj == -INFINITY) continue;
-        const float Mn = fmaxf(M2[rg], mj);
-        const float ws = (M2[rg] == -INFINITY) ? 0.f : expf(M2[rg] - Mn), wj = expf(mj - Mn);
-        L2[rg] = L2[rg] * ws + lj * wj;
-#pragma unroll
-        for (int x4 = 0; x4 < DPT / 4; ++x4) {
-          const uint4 v = oo[rg][j][x4];
-          o2[rg][x4 * 4] = o2[rg][x4 * 4] * ws + __uint_as_float(v.x) * wj;
-          o2[rg][x4 * 4 + 1] = o2[rg][x4 * 4 + 1] * ws + __uint_as_float(v.y) * wj;
-          o2[rg][x4 * 4 + 2] = o2[rg][x4 * 4 + 2] * ws + __uint_as_float(v.z) * wj;
-          o2[rg][x4 * 4 + 3] = o2[rg][x4 * 4 + 3] * ws + __uint_as_float(v.w) * wj;
-        }
-        M2[rg] = Mn;
-      }
+      for (int x = 0; x < DPL; ++x) o[x] = o[x] * ws + ov[j][x] * wj;
+      M = Mn;
+    }
   }
+  typedef bf16_t bf16xd __attribute__((ext_vector_type(DPL)));
+  bf16xd hi, lo;
 #pragma unroll
-  for (int rg = 0; rg < NRG; ++rg)
-    if (rg * 16 + mrow < nrows) store_out(rg * 16 + mrow, o2[rg], L2[rg]);
+  for (int x = 0; x < DPL; ++x) {
+    bf16_t h, l;
+    split_bf16((L > 0.f) ? o[x] / L : 0.f, h, l);
+    hi[x] = h;
+    lo[x] = l;
+  }
+  const int arow = seq * R + row, ak = head * HD + lane * DPL;
+  *(bf16xd*)(out + act_offset(ncg, B * R, n_heads * HD, 0, arow, ak)) = hi;
+  *(bf16xd*)(out + act_offset(ncg, B * R, n_heads * HD, 1, arow, ak)) = lo;
 }
 
 template <int HD, int NRG, int AW>
@@ -393,7 +401,7 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
   static const hipError_t attr = lds > 64 * 1024 ? hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
                                                  : hipSuccess;
   if (attr != hipSuccess) return attr;
-  // aim at one workgroup per compute unit: more splits cost more in the exchange than they gain (measured at 2048 keys)
+  // splits: enough workgroups to fill the machine once (twice and four times over measured no faster at 512, 2048 and 4096 keys)
   static const int n_cus = [] {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
@@ -404,6 +412,10 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
   const int gx = n_splits < want ? n_splits : want;
   hipLaunchKernelGGL(kern, dim3(gx, KVH * n_chunks, B), dim3(AW * 64), lds, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale,
                      partial, n_splits, counters, (bf16_t*)out, want, ncg);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || gx == 1) return e;  // one split: every workgroup wrote its output
+  hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3((B * n_heads * R + 3) / 4), dim3(256), 0, s, rd, kv, B, R, n_heads, (const float*)partial,
+                     n_splits, want, (bf16_t*)out, ncg);
   return hipGetLastError();
 }
 
