@@ -430,7 +430,8 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
 
 // Passes of many rows stage both operands through LDS (kernels_gemm_tiled.hip).  Measured against the kernels above at
 // the 7B- and 13B-shaped products: it wins from 65 rows up everywhere, and from 25 rows up for products wide enough
-// to give every compute unit a workgroup of 8 strips.
+// to give every compute unit a workgroup of 8 strips (at 17 rows it loses also with activations that are already in
+// fragment order: C4 verify 4.50 against 4.24 ms).
 static bool use_tiled(const GemmArgs& a) {
   if (!a.ncg && (!a.xfrag || a.xfrag_elems < gemm_tiled_xfrag_elems(a.R, a.K))) return false;  // needs fragment order or its scratch
   return a.R >= 65 || (a.R >= 25 && gemm_tiled_wide(a.N));

@@ -261,9 +261,10 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
   const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
-  // one kernel per step: activations in operand-fragment order (act_offset), whole cache lines per fragment; the
-  // persistent kernel reads planes
-  const int ncg = persistent ? 0 : (rows + 7) / 8;
+  // one kernel per step, 5 rows or more: activations in operand-fragment order (act_offset), 8 whole cache lines per
+  // fragment of 8 rows; with fewer rows two planes touch fewer lines (2 half lines per row: plain decoding, 1 row, is
+  // 10 % faster on planes; 5 rows are 2 % faster in fragment order); the persistent kernel reads planes
+  const int ncg = (persistent || rows < 5) ? 0 : (rows + 7) / 8;
   c->pass_ncg = ncg;
   HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, c->rd.pos, c->rope, hd, m->rope_theta,
                           ncg, s));
