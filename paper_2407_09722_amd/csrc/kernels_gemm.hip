@@ -170,6 +170,79 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
   if (wave < NG) gemm_finish_group<NG, EPI>(a, nt, wave, red, inv_s, rows_here, lane);
 }
 
+// The same kernel for S strips per workgroup: the activation fragments of a k tile are loaded once and multiplied with
+// the S weight tiles of that k tile, so the L2 -> compute-unit traffic of the fragments per weight byte is 1/S of the
+// one-strip kernel's (which spends 12 to 15 % of its time on them at 5 rows: measured by knocking the loads out).
+// U tiles per batch and strip, two batches in flight as above; the S strips are reduced and finished one after the
+// other through the same LDS buffer.  Used with S = 3, U = 2 for 4 to 8 rows.
+template <int NG, int EPI, int TAG, int S, int U>
+__global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((S + NG) * U * 8 + S * NG * 4 > 100 ? 2 : 4))) void gemm_bf16_strips_kernel(GemmArgs a) {
+  __shared__ floatx4 red[GW * NG * 64];
+  __shared__ float inv_s[NG * 8];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int K = a.K, KT = K >> 5, NT = a.N >> 4;
+  const int R = a.R, row0 = a.row0;
+  const int rows_here = min(NG * 8, R - row0);
+  const int c = lane & 15;
+  const int nt0 = blockIdx.x * S, ns = min(S, NT - nt0);
+  const size_t strip_bytes = (size_t)KT << 10;
+  const char* strip0 = (const char*)a.W + (size_t)nt0 * strip_bytes;
+  const unsigned voff = (unsigned)lane * 16u;
+  const ActAddr xa = act_addr(a, lane);
+
+  constexpr int span = U * GW;
+  Frag w[2][U][S], b[2][U][NG];
+  auto load_w = [&](Frag (&ws)[U][S], int kt) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int s2 = 0; s2 < S; ++s2)
+        if (kt + u * GW < KT)  // a strip past the last one reads the last one again: never finished
+          ws[u][s2].n = __builtin_nontemporal_load((const uintx4*)(strip0 + (size_t)min(s2, ns - 1) * strip_bytes + ((size_t)(kt + u * GW) << 10) + voff));
+  };
+  gemm_load_b<NG, U>(b[0], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, wave, rows_here, c);
+  load_w(w[0], wave);
+  gemm_load_b<NG, U>(b[1], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, wave + span, rows_here, c);
+  load_w(w[1], wave + span);
+
+  floatx4 acc[S][NG];
+#pragma unroll
+  for (int s2 = 0; s2 < S; ++s2)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) acc[s2][g] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kt = wave; kt < KT; kt += 2 * span) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k0 = kt + h * span;
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (k0 + u * GW < KT) {
+#pragma unroll
+          for (int s2 = 0; s2 < S; ++s2)
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[s2][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[h][u][s2].v, b[h][u][g].v, acc[s2][g], 0, 0, 0);
+        }
+      if (k0 + 2 * span < KT) {
+        gemm_load_b<NG, U>(b[h], xa.X, xa.xoff, xa.kstride, xa.gstride, KT, k0 + 2 * span, rows_here, c);
+        load_w(w[h], k0 + 2 * span);
+      }
+    }
+  }
+  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
+#pragma unroll
+  for (int s2 = 0; s2 < S; ++s2) {
+    if (s2 < ns) {  // uniform over the workgroup
+      if (s2 > 0) __syncthreads();  // the previous strip's sums have been read
+#pragma unroll
+      for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[s2][g];
+      __syncthreads();
+      if (wave < NG) gemm_finish_group<NG, EPI>(a, nt0 + s2, wave, red, inv_s, rows_here, lane);
+    }
+  }
+}
+
 // Several strips per workgroup, for passes of more than 8 rows.  With NG row groups a weight tile needs NG activation
 // fragments of its own size from L2; a workgroup that works on S strips at once loads the fragments of a k tile
 // once and uses them for S weight tiles, so the L2 -> compute-unit traffic per weight byte drops from 1 + NG to
@@ -343,6 +416,16 @@ static hipError_t run_tag(const GemmArgs& a, int tag, hipStream_t s) {
   return run_one<NG, EPI, 0>(a, s);
 }
 
+template <int NG, int EPI, int S, int U>
+static hipError_t run_strips(const GemmArgs& a, int tag, hipStream_t s) {
+  const int NT = a.N / 16;
+  const dim3 grid((NT + S - 1) / S), block(GW * 64);
+  if (tag == 1) hipLaunchKernelGGL((gemm_bf16_strips_kernel<NG, EPI, 1, S, U>), grid, block, 0, s, a);
+  else if (tag == 2) hipLaunchKernelGGL((gemm_bf16_strips_kernel<NG, EPI, 2, S, U>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((gemm_bf16_strips_kernel<NG, EPI, 0, S, U>), grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
 template <int NG, int EPI>
 static hipError_t run_multi(const GemmArgs& a, int S, int KS, hipStream_t s) {
   const int NT = a.N / 16;
@@ -417,7 +500,12 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
       if (e != hipSuccess) return e;
       continue;
     }
-    if (ng <= 1) e = run_tag<1, EPI>(a, tag, s);
+    // 4 to 8 rows and at least two strips per compute unit: three strips per workgroup share the activation fragments
+    // (measured on the 7B-shaped QKV, gate/up and lm_head products: 6, 10 and 4 % faster at 5 rows, 17, 19 and 15 % at 8;
+    // slower at 1 row; two, four, five or six strips per workgroup all slower than three; no gain at 9 to 24 rows over
+    // the kernel below that already shares fragments there)
+    if (ng <= 1 && a.R - r0 >= 4 && a.N / 16 >= 2 * device_cus()) e = run_strips<1, EPI, 3, 2>(a, tag, s);
+    else if (ng <= 1) e = run_tag<1, EPI>(a, tag, s);
     else if (ng <= 2) e = run_tag<2, EPI>(a, tag, s);
     else if (ng <= 3) e = run_tag<3, EPI>(a, tag, s);
     else if (ng <= 4) e = run_tag<4, EPI>(a, tag, s);
