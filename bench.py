@@ -295,7 +295,8 @@ def main():
         traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]   # HBM bytes per launch
     kname = "gemm_f32_kernel"
     if dt_id:
-        kname = ("gemm_bf16_kernel (skinny weight-streaming GEMM, all target matrices)" if rows <= 8 else
+        kname = ("gemm_bf16_strips_kernel / gemm_bf16_kernel (the weight-streaming products of all target matrices: three strips per workgroup "
+                 "where the product has at least two strips per compute unit, else one)" if rows <= 8 else
                  "gemm_bf16_multi_kernel / gemm_bf16_kernel (several strips per workgroup)" if rows < 65 else
                  "gemm_bf16_tiled_kernel (operands staged through LDS)")
     roofline = {"kernel": kname,
