@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--no-energy", action="store_true", help="skip the board-power measurement (about 10 s)")
     ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: time and energy of one target pass at each "
                     "(Section 4's observation that a run costs about the same for any small batch); not part of the default run")
+    ap.add_argument("--gamma-beam-sweep", default="", help="'g1,g2,..xb1,b2,..': time of one iteration at each draft length gamma and beam "
+                    "width (the axes of the paper's ablation, Section 5.3); not part of the default run")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (requests are independent; more GPUs would each run this "
@@ -239,7 +241,7 @@ def main():
     # --- verify step alone, HIP events on the launch stream --------------------------------------------------
     eng.prefill(prompt)
     eng.draft_phase(seed=w.seed)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     for _ in range(3):
         eng.verify_phase()
     ev[0].record(stream)
@@ -436,6 +438,36 @@ def main():
                                 "ms_per_pass_per_sequence": round(sec / n_it * 1e3 / nb, 4)})
             eb.close()
 
+    # --- one iteration at several draft lengths and beam widths (Section 5.3 varies both; its speed peaks where the growing
+    #     draft and verify cost overtakes the longer accepted blocks) -------------------------------------------------------
+    gb_sweep = None
+    if args.gamma_beam_sweep:
+        gs, bs = (tuple(int(x) for x in part.split(",") if x) for part in args.gamma_beam_sweep.split("x"))
+        gb_sweep = []
+        for g in gs:
+            for b in bs:
+                rows = w.batch * ((g + 1) if w.mode == "mtad" else (b * g + 1))
+                if (g + 1) + (g - 1) * b > 64 or rows > 256:   # the library's limits (include/mtad.h: MTAD_MAX_ROWS)
+                    gb_sweep.append({"gamma": g, "beam": b, "error": "more than 64 draft rows per iteration or 256 rows per pass"})
+                    continue
+                eg = Engine(tm, dm, batch=w.batch, gamma=g, beam=b, mode=w.mode, max_context=w.prompt_len + 256, device=dev)
+                eg.prefill(prompt)
+                for i in range(3):
+                    eg.iteration(tau, seed=w.seed + i)
+                n_it = 20
+                ev[0].record(stream)
+                for i in range(n_it):
+                    eg.draft_phase(seed=w.seed + i)
+                ev[1].record(stream)
+                for i in range(n_it):
+                    eg.iteration(tau, seed=w.seed + 100 + i)
+                ev[2].record(stream)
+                torch.cuda.synchronize()
+                gb_sweep.append({"gamma": g, "beam": b, "verify_rows": rows, "ms_per_iteration": round(ev[1].elapsed_time(ev[2]) / n_it, 4),
+                                 "ms_draft_phase": round(ev[0].elapsed_time(ev[1]) / n_it, 4)})
+                status |= mb.mtad_device_status(eg.ctx)
+                eg.close()
+
     # --- the oracle on the host cores, bounded sample ---------------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -458,7 +490,7 @@ def main():
                                "block-efficiency table): a labelled projection, not a measurement"},
         "tau0": {"tokens_per_s": round(tokens0 / dt0, 2), "tokens_per_iteration": round(tokens0 / K / w.batch, 3),
                  "ms_per_step": round(dt0 / K * 1e3, 4)},
-        "warped": warped, "baselines": baselines, "energy": energy, "batch_sweep": batch_sweep, "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
+        "warped": warped, "baselines": baselines, "energy": energy, "batch_sweep": batch_sweep, "gamma_beam_sweep": gb_sweep, "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
         "device_status": status, "weights_setup_s": round(t_weights, 1),
     }
     print(json.dumps(out))
