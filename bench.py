@@ -264,7 +264,8 @@ def main():
     dt_id = 1 if w.target.dtype == "bf16" else 0
     kmax = max(k for _, k in per_layer + [head])
     nmax = max(n for n, _ in per_layer + [head])
-    X = torch.zeros(2 * rows * kmax, dtype=torch.int16 if dt_id else torch.float32, device=dev)
+    x_order = mb.MTAD_X_FRAGMENTS if (dt_id and rows >= 2) else mb.MTAD_X_PLANES   # as the kernel-per-step passes keep their activations
+    X = torch.zeros(2 * ((rows + 7) // 8 * 8) * kmax, dtype=torch.int16 if dt_id else torch.float32, device=dev)
     Y = torch.zeros(rows * nmax, dtype=torch.float32, device=dev)
     launches = []
     for l in range(w.target.n_layers):
@@ -276,7 +277,7 @@ def main():
 
     def replay():
         for Wt, n, k in launches:
-            mb.mtad_k_gemm(dt_id, Wt, X, Y, rows, n, k, n, False, ctx=eng.ctx)   # the pass's own kernel choice
+            mb.mtad_k_gemm(dt_id, Wt, X, Y, rows, n, k, n, False, ctx=eng.ctx, x_order=x_order)   # the pass's own kernel choice and layout
     replay()
     reps = max(3, min(20, K // 3))
     ev[0].record(stream)

@@ -19,7 +19,7 @@ MTAD_MAX_ROWS, MTAD_MAX_BEAM = 64, 8
 EXPORTS = ["mtad_create", "mtad_destroy", "mtad_workspace_bytes", "mtad_bind_workspace", "mtad_strerror",
            "mtad_last_hip_error", "mtad_device_status", "mtad_set_persistent", "mtad_set_warp", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
            "mtad_verify_tree", "mtad_accept", "mtad_accept_spd", "mtad_accept_chain", "mtad_kv_commit",
-           "mtad_k_gemm", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_copy"]
+           "mtad_k_gemm", "mtad_k_gemm_x", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_copy"]
 
 i32, u64, f32, vp = C.c_int32, C.c_uint64, C.c_float, C.c_void_p
 
@@ -93,6 +93,7 @@ def lib():
         L.mtad_accept_spd.argtypes = [vp, P(mtad_tree), vp, vp, i32, P(mtad_kv), u64, P(mtad_accept_out), vp]
         L.mtad_kv_commit.argtypes = [vp, P(mtad_kv), P(mtad_kv), P(mtad_tree), P(mtad_accept_out), P(mtad_state), vp]
         L.mtad_k_gemm.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.mtad_k_gemm_x.argtypes = [vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp]
         L.mtad_k_rmsnorm.argtypes = [i32, vp, vp, vp, i32, i32, f32, vp]
         L.mtad_k_row_lse.argtypes = [vp, vp, i32, i32, vp]
         L.mtad_k_warp_rows.argtypes = [vp, vp, i32, i32, i32, f32, vp]
@@ -161,6 +162,7 @@ def mtad_device_status(ctx, stream=None) -> int:
 
 
 MTAD_PACK_PLAIN, MTAD_PACK_QKV, MTAD_PACK_GATE_UP = 0, 1, 2
+MTAD_X_PLANES, MTAD_X_FRAGMENTS = 0, 1
 
 
 def mtad_pack_matrix(kind, src, dst, N, K, head_dim=0, stream=None):
@@ -204,8 +206,12 @@ def mtad_kv_commit(ctx, tkv, dkv, tree, acc, st, stream=None):
                                                  C.byref(acc), C.byref(st), _stream_ptr(stream)))
 
 
-def mtad_k_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate=False, stream=None, ctx=None):
-    _check("mtad_k_gemm", lib().mtad_k_gemm(ctx, dtype, ptr(W), ptr(X), ptr(Y), R, N, K, ldy, int(accumulate), _stream_ptr(stream)))
+def mtad_k_gemm(dtype, W, X, Y, R, N, K, ldy, accumulate=False, stream=None, ctx=None, x_order=0):
+    if x_order:
+        _check("mtad_k_gemm_x", lib().mtad_k_gemm_x(ctx, dtype, ptr(W), ptr(X), ptr(Y), R, N, K, ldy, int(accumulate), x_order, _stream_ptr(stream)))
+    else:
+        _check("mtad_k_gemm", lib().mtad_k_gemm(ctx, dtype, ptr(W), ptr(X), ptr(Y), R, N, K, ldy, int(accumulate), _stream_ptr(stream)))
+
 
 
 def mtad_k_rmsnorm(dtype, h, g, out, rows, d, eps, stream=None):

@@ -261,10 +261,11 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
   const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
-  // one kernel per step, 5 rows or more: activations in operand-fragment order (act_offset), 8 whole cache lines per
-  // fragment of 8 rows; with fewer rows two planes touch fewer lines (2 half lines per row: plain decoding, 1 row, is
-  // 10 % faster on planes; 5 rows are 2 % faster in fragment order); the persistent kernel reads planes
-  const int ncg = (persistent || rows < 5) ? 0 : (rows + 7) / 8;
+  // one kernel per step, 2 rows or more: activations in operand-fragment order (act_offset), whole cache lines per
+  // fragment, without the unused row slots up to 8 rows (C3 verify, 5 rows: 3.20 ms on planes, 3.14 ms with 8-row
+  // fragments, 2.98 ms with 5-row fragments on the three-strip product kernel; 2 to 4 rows 1 to 3 % faster than on
+  // planes; one row, plain decoding, 1 % slower); the persistent kernel reads planes
+  const int ncg = (persistent || rows < 2) ? 0 : (rows + 7) / 8;
   c->pass_ncg = ncg;
   HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, c->rd.pos, c->rope, hd, m->rope_theta,
                           ncg, s));
@@ -636,8 +637,15 @@ static size_t gemm_split_floats_cap(const mtad_ctx* c) {
 
 int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float* Y, int32_t R, int32_t N, int32_t K, int32_t ldy, int32_t accumulate,
                 void* stream) {
+  return mtad_k_gemm_x(c, dtype, W, X, Y, R, N, K, ldy, accumulate, MTAD_X_PLANES, stream);
+}
+
+int mtad_k_gemm_x(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float* Y, int32_t R, int32_t N, int32_t K, int32_t ldy,
+                  int32_t accumulate, int32_t x_order, void* stream) {
   if (!W || !X || !Y || R < 1 || N < 1 || K < 1 || ldy < N) return MTAD_EINVAL;
   if (dtype != 0 && dtype != 1) return MTAD_EINVAL;
+  if (x_order != MTAD_X_PLANES && x_order != MTAD_X_FRAGMENTS) return MTAD_EINVAL;
+  if (dtype == 0 && x_order != MTAD_X_PLANES) return MTAD_EINVAL;
   if (dtype == 1 && ((N % 16) || (K % 32) || (ldy % 4) || R > 256)) return MTAD_ESHAPE;
   if (dtype == 0 && (K % 4)) return MTAD_ESHAPE;
   if (dtype == 0) return launch_gemm_f32(W, X, Y, R, N, K, ldy, accumulate != 0, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
@@ -645,6 +653,7 @@ int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float*
   memset(&a, 0, sizeof(a));
   a.W = (const bf16_t*)W; a.X = (const bf16_t*)X; a.R = R; a.N = N; a.K = K;
   a.Y = Y; a.ldy = ldy; a.accumulate = accumulate != 0;
+  a.ncg = x_order == MTAD_X_FRAGMENTS ? (R + 7) / 8 : 0;
   if (c && c->ws && gemm_split_floats(N) > 0 && gemm_split_floats(N) <= gemm_split_floats_cap(c)) {  // k split needs the workspace
     a.part = c->gemm_part;
     a.counters = c->gemm_cnt;

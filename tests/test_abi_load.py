@@ -67,4 +67,6 @@ def test_strerror_and_host_validation(lib):
     # hot calls validate before launching: null context / null buffers
     assert lib.mtad_k_gemm(None, 1, None, None, None, 5, 64, 64, 64, 0, None) == mb.MTAD_EINVAL
     assert lib.mtad_k_gemm(None, 1, C.c_void_p(256), C.c_void_p(256), C.c_void_p(256), 5, 60, 64, 64, 0, None) == mb.MTAD_ESHAPE
+    assert lib.mtad_k_gemm_x(None, 1, C.c_void_p(256), C.c_void_p(256), C.c_void_p(256), 5, 64, 64, 64, 0, 7, None) == mb.MTAD_EINVAL    # no such order
+    assert lib.mtad_k_gemm_x(None, 0, C.c_void_p(256), C.c_void_p(256), C.c_void_p(256), 5, 64, 64, 64, 0, 1, None) == mb.MTAD_EINVAL    # float32 has planes only
     assert lib.mtad_bind_workspace(None, None, 0) == mb.MTAD_EINVAL

@@ -19,7 +19,23 @@ def _bits(x):
     return torch.from_numpy(si.f32_to_bf16_bits(x).view(np.int16)).to(DEV)
 
 
-def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None, ctx=None):
+def _fragment_order(planes):
+    """[2][R][K] bfloat16 bit planes -> the operand-fragment order mtad_k_gemm_x documents (written out from that text)."""
+    _, R, K = planes.shape
+    G = (R + 7) // 8
+    rows = R if R <= 8 else 8 * G
+    out = np.zeros(2 * rows * K, dtype=planes.dtype)
+    plane, r, k = np.meshgrid(np.arange(2), np.arange(R), np.arange(K), indexing="ij")
+    kt, kg, e = k // 32, (k % 32) // 8, k % 8
+    if R <= 8:
+        off = ((((kt * 4 + kg) * 2 + plane) * R + r) * 8) + e
+    else:
+        off = (((kt * G + r // 8) * 64 + kg * 16 + plane * 8 + r % 8) * 8) + e
+    out[off.ravel()] = planes.ravel()
+    return out
+
+
+def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None, ctx=None, x_order=0):
     g = np.random.default_rng(seed)
     W = (g.standard_normal((N, K)) * 0.05).astype(np.float32)
     X = g.standard_normal((R, K)).astype(np.float32)
@@ -29,13 +45,15 @@ def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None, ctx=None):
         hi = si.bf16_bits_to_f32(si.f32_to_bf16_bits(X))
         lo = si.bf16_bits_to_f32(si.f32_to_bf16_bits(X - hi))
         Wrow, Xd = _bits(W), _bits(np.stack([hi, lo]))                   # activation = hi + lo planes
+        if x_order:
+            Xd = torch.from_numpy(_fragment_order(Xd.cpu().numpy().reshape(2, R, K))).to(DEV)
         Wd = torch.empty_like(Wrow)
         mb.mtad_pack_matrix(mb.MTAD_PACK_PLAIN, Wrow, Wd, N, K)          # the layout the kernel streams
         W, X = si.bf16_bits_to_f32(si.f32_to_bf16_bits(W)), hi.astype(np.float64) + lo
     else:
         Wd, Xd = torch.from_numpy(W).to(DEV), torch.from_numpy(X).to(DEV)
     Yd = torch.from_numpy(Y0).to(DEV)
-    mb.mtad_k_gemm(dtype, Wd, Xd, Yd, R, N, K, ldy, accumulate, ctx=ctx)
+    mb.mtad_k_gemm(dtype, Wd, Xd, Yd, R, N, K, ldy, accumulate, ctx=ctx, x_order=x_order)
     torch.cuda.synchronize()
     got = Yd.cpu().numpy().astype(np.float64)
     want = Y0.astype(np.float64)
@@ -83,6 +101,25 @@ def test_gemm_bf16_with_context_workspace(R, N, K):
     for rep in range(2):
         print(f"gemm bf16 k-split R={R} N={N} K={K} rep {rep}", flush=True)
         _gemm_case(mb, R, N, K, 1, seed=R + N + rep, ctx=ctx)
+    mb.mtad_destroy(ctx)
+
+
+@pytest.mark.parametrize("R,N,K", [(1, 64, 96), (2, 8208, 160), (5, 12288, 4096), (5, 4096, 11008), (8, 22016, 256), (7, 48, 1056),
+                                   (9, 4096, 4096), (17, 12288, 4096), (24, 4112, 64), (41, 8192, 96), (64, 4096, 1024),
+                                   (25, 16400, 288), (100, 4112, 1056), (164, 5120, 5120), (190, 48, 1056)])
+def test_gemm_bf16_fragment_order_input(R, N, K):
+    """The activation layouts of the kernel-per-step passes (fragments without unused row slots up to 8 rows, whole 8-row
+    fragments beyond) through every product kernel: one strip, three strips, several strips, k split, LDS-staged."""
+    mb = _mb()
+    shape = si.ModelShape(1, 4096, 32, 32, 128, 11008, 32000, "bf16")
+    draft = si.ModelShape(1, 5120, 40, 40, 128, 8192, 32000, "bf16")
+    desc = lambda s: mb.mtad_model(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 1, s.rms_eps, s.rope_theta, None)
+    ctx = mb.mtad_create(mb.mtad_config(1, 4, 4, 1, 64, 256), desc(shape), desc(draft))
+    ws = torch.empty(mb.mtad_workspace_bytes(ctx), dtype=torch.uint8, device=DEV)
+    mb.mtad_bind_workspace(ctx, ws)
+    print(f"gemm bf16 fragment order R={R} N={N} K={K}", flush=True)
+    _gemm_case(mb, R, N, K, 1, seed=R * 3 + N, ctx=ctx, x_order=mb.MTAD_X_FRAGMENTS)
+    _gemm_case(mb, R, N, K, 1, seed=R * 3 + N + 1, x_order=mb.MTAD_X_FRAGMENTS)      # without a context: the skinny kernels only
     mb.mtad_destroy(ctx)
 
 
