@@ -178,11 +178,12 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
 // The same kernel for S strips per workgroup: the activation fragments of a k tile are loaded once and multiplied with
 // the S weight tiles of that k tile, so the L2 -> compute-unit traffic of the fragments per weight byte is 1/S of the
 // one-strip kernel's (which spends 12 to 15 % of its time on them at 5 rows: measured by knocking the loads out).
-// U tiles per batch and strip, two batches in flight as above; the S strips are reduced and finished one after the
-// other through the same LDS buffer.  Used with S = 3, U = 2 for 4 to 8 rows.
+// U tiles per batch and strip, two batches in flight as above; the S strips are reduced and finished at the
+// same time by different waves.  Used with S = 3, U = 2 for 4 to 8 rows.
 template <int NG, int EPI, int TAG, int S, int U>
 __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((S + NG) * U * 8 + S * NG * 4 > 100 ? 2 : 4))) void gemm_bf16_strips_kernel(GemmArgs a) {
-  __shared__ floatx4 red[GW * NG * 64];
+  static_assert(S * NG <= GW, "one wave finishes one (strip, row group)");
+  __shared__ floatx4 red[S * GW * NG * 64];
   __shared__ float inv_s[NG * 8];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -236,15 +237,16 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((S + NG
     }
   }
   gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
+  // all strips' sums to LDS at once; wave s2 * NG + g then finishes row group g of strip s2, the strips side by side
+  // (one after the other, each epilogue's dependent loads, the rotary table, cache slots and residual rows, added up)
 #pragma unroll
-  for (int s2 = 0; s2 < S; ++s2) {
-    if (s2 < ns) {  // uniform over the workgroup
-      if (s2 > 0) __syncthreads();  // the previous strip's sums have been read
+  for (int s2 = 0; s2 < S; ++s2)
 #pragma unroll
-      for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[s2][g];
-      __syncthreads();
-      if (wave < NG) gemm_finish_group<NG, EPI>(a, nt0 + s2, wave, red, inv_s, rows_here, lane);
-    }
+    for (int g = 0; g < NG; ++g) red[((s2 * GW + wave) * NG + g) * 64 + lane] = acc[s2][g];
+  __syncthreads();
+  if (wave < S * NG) {
+    const int s2 = wave / NG, g = wave % NG;
+    if (s2 < ns) gemm_finish_group<NG, EPI>(a, nt0 + s2, g, red + s2 * GW * NG * 64, inv_s, rows_here, lane);
   }
 }
 
