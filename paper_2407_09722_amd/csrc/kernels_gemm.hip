@@ -319,6 +319,11 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
   gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);  // after the stream (see the single-strip kernel)
   // partial sums of (group, strip s2, row group g, range ks): 64 lanes x 4 floats
   float* const mypart = a.part ? a.part + ((((size_t)blockIdx.x * SM) * NG) * KS) * 256 : nullptr;
+  // The strips are reduced through LDS one after the other; (strip s2, row group g) = item s2 * NG + g goes to wave
+  // item % GW, which keeps the sum and runs its epilogue after the last reduction, so that the epilogues of all items
+  // (dependent loads of rotary table, cache slots, residual rows) overlap instead of queueing behind NG waves.
+  constexpr int HELD = (SM * NG + GW - 1) / GW;
+  floatx4 held[HELD];
 #pragma unroll
   for (int s2 = 0; s2 < SM; ++s2) {
     if (s2 < ns) {  // uniform over the workgroup
@@ -326,19 +331,30 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
 #pragma unroll
       for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[s2][g];
       __syncthreads();
-      if (wave < NG) {
-        const floatx4 sum = gemm_sum_waves<NG>(wave, red, lane);
-        if (KS == 1) {
-          gemm_finish_sum<EPI>(a, nt0 + s2, wave, sum, inv_s, rows_here, lane);
-        } else {
-          float* p = mypart + ((((size_t)s2 * NG + wave) * KS + ks) * 64 + lane) * 4;
-          st8<true>(p, make_uint2(__float_as_uint(sum[0]), __float_as_uint(sum[1])));
-          st8<true>(p + 2, make_uint2(__float_as_uint(sum[2]), __float_as_uint(sum[3])));
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const int item = s2 * NG + g;
+        if (wave == item % GW) {
+          const floatx4 sum = gemm_sum_waves<NG>(g, red, lane);
+          if (KS == 1) {
+            held[item / GW] = sum;
+          } else {
+            float* p = mypart + ((((size_t)s2 * NG + g) * KS + ks) * 64 + lane) * 4;
+            st8<true>(p, make_uint2(__float_as_uint(sum[0]), __float_as_uint(sum[1])));
+            st8<true>(p + 2, make_uint2(__float_as_uint(sum[2]), __float_as_uint(sum[3])));
+          }
         }
       }
     }
   }
-  if (KS == 1) return;
+  if (KS == 1) {
+#pragma unroll
+    for (int h = 0; h < HELD; ++h) {
+      const int item = h * GW + wave, s2 = item / NG, g = item % NG;
+      if (item < SM * NG && s2 < ns) gemm_finish_sum<EPI>(a, nt0 + s2, g, held[h], inv_s, rows_here, lane);
+    }
+    return;
+  }
   // the workgroup that arrives last for this group of strips adds the ranges in order and finishes
   __builtin_amdgcn_s_waitcnt(0);  // the stores have been acknowledged
   __syncthreads();
