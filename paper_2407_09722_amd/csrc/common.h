@@ -111,14 +111,14 @@ hipError_t launch_rmsnorm(int dtype, const float* h, const float* g, void* out, 
 // rotate q (in place in qkv, float32), rotate k and write k, v to the cache in its storage type
 hipError_t launch_rope_kv(int dtype, float* qkv, const float2* table, const RowDesc& rd, KvView kv, int layer, int B, int R,
                           int n_heads, uint32_t* status, hipStream_t s);
-// q: [rows][q_stride] float32 with head h at column h*head_dim; counters: zeroed ints [B][n_heads][ceil(R/8)]
-// (bf16 models work on chunks of 8 rows, float32 models on chunks of 16)
+// q: [rows][q_stride] float32 with head h at column h*head_dim; counters: zeroed ints [B][n_heads][ceil(R/16)], used by
+// the float32 kernel only (its last workgroup per item merges the key splits; bf16 models merge in a kernel of their own)
 hipError_t launch_attention(int dtype, const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
                             float* partial, int n_splits, int* counters, void* out, int ncg, hipStream_t s);
 // bf16 models (kernels_attn_mfma.hip): half-precision cache, output = bf16 hi / lo terms (layout: act_offset with ncg);
 // n_splits = upper bound on the key splits (the kernel uses fewer for short contexts)
 hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
-                                 float* partial, int n_splits, int* counters, void* out, int ncg, hipStream_t s);
+                                 float* partial, int n_splits, void* out, int ncg, hipStream_t s);
 // lse[row] from per-strip (max, sum exp) partials [rows][NP]
 hipError_t launch_lse_finish(const float* lse_part, float* lse, int rows, int NP, hipStream_t s);
 // lse as above for B*M rows, plus logp_cond[s][c] = logits[s][parent(c)][tok(c)] - lse[s][parent(c)] (0 for c = 0)

@@ -42,7 +42,7 @@ hipError_t launch_attention(int dtype, const float* q, int q_stride, const RowDe
                             float* partial, int n_splits, int* counters, void* out, int ncg, hipStream_t s) {
   if (B * R <= 0) return hipSuccess;
   const int hd = kv.head_dim;
-  if (dtype == 1) return launch_attention_mfma(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, ncg, s);
+  if (dtype == 1) return launch_attention_mfma(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, out, ncg, s);
   if (dtype == 0 && hd == 128) return run_attn<float, 128>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   if (dtype == 0 && hd == 64) return run_attn<float, 64>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, s);
   return hipErrorInvalidValue;

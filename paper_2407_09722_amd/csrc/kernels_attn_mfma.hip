@@ -76,7 +76,7 @@ __device__ __forceinline__ int attn_splits(int ktot, int n_splits, int want_spli
 template <int HD, int NRG, int AW>
 __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) void tree_attn_mfma_kernel(const float* __restrict__ q, int q_stride, RowDesc rd, KvView kv, int layer,
                                                                int R, int n_heads, int n_chunks, float scale, float* __restrict__ partial,
-                                                               int n_splits, int* __restrict__ counters, bf16_t* __restrict__ out, int want_splits, int ncg) {
+                                                               int n_splits, bf16_t* __restrict__ out, int want_splits, int ncg) {
   constexpr int KS = HD / 32;    // k-steps of the score product
   constexpr int DB = HD / 16;    // 16-dim blocks of the output
   constexpr int CH = HD / 8;     // 16-byte chunks of a cache row
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(RowDesc rd, KvView kv, 
 
 template <int HD, int NRG, int AW>
 hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvView& kv, int layer, int B, int R, int n_heads, float* partial,
-                    int n_splits, int* counters, void* out, int ncg, hipStream_t s) {
+                    int n_splits, void* out, int ncg, hipStream_t s) {
   const int KVH = kv.n_kv_heads, G = n_heads / KVH;
   const int n_chunks = (G * R + NRG * 16 - 1) / (NRG * 16);  // chunks of (query head, row) pairs per KV head
   const float scale = 1.0f / sqrtf((float)HD);
@@ -411,7 +411,7 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
   const int want = items >= n_cus ? 1 : (n_cus + items - 1) / items;
   const int gx = n_splits < want ? n_splits : want;
   hipLaunchKernelGGL(kern, dim3(gx, KVH * n_chunks, B), dim3(AW * 64), lds, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale,
-                     partial, n_splits, counters, (bf16_t*)out, want, ncg);
+                     partial, n_splits, (bf16_t*)out, want, ncg);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || gx == 1) return e;  // one split: every workgroup wrote its output
   hipLaunchKernelGGL((attn_merge_kernel<HD>), dim3((B * n_heads * R + 3) / 4), dim3(256), 0, s, rd, kv, B, R, n_heads, (const float*)partial,
@@ -425,16 +425,16 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
 // bf16 models: q float32 [B*R][q_stride], half-precision cache, output = bf16 hi / lo planes [2][B*R][n_heads*hd].
 // Passes of up to 16 rows per sequence use 16-row work items, larger ones 32-row items (K and V are read once per item).
 hipError_t launch_attention_mfma(const float* q, int q_stride, const RowDesc& rd, KvView kv, int layer, int B, int R, int n_heads,
-                                 float* partial, int n_splits, int* counters, void* out, int ncg, hipStream_t s) {
+                                 float* partial, int n_splits, void* out, int ncg, hipStream_t s) {
   const int hd = kv.head_dim;
   if (kv.n_kv_heads < 1 || n_heads % kv.n_kv_heads) return hipErrorInvalidValue;
   const int pairs = n_heads / kv.n_kv_heads * R;  // (query head, row) pairs that share a KV head
-  if (hd == 128 && pairs <= 16) return run_mfma<128, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, ncg, s);
+  if (hd == 128 && pairs <= 16) return run_mfma<128, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, out, ncg, s);
   if (hd == 128 && pairs > 32 && pairs <= 48)  // one item instead of two that would each read K and V
-    return run_mfma<128, 3, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, ncg, s);
-  if (hd == 128) return run_mfma<128, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, ncg, s);
-  if (hd == 64 && pairs <= 16) return run_mfma<64, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, ncg, s);
-  if (hd == 64) return run_mfma<64, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, counters, out, ncg, s);
+    return run_mfma<128, 3, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, out, ncg, s);
+  if (hd == 128) return run_mfma<128, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, out, ncg, s);
+  if (hd == 64 && pairs <= 16) return run_mfma<64, 1, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, out, ncg, s);
+  if (hd == 64) return run_mfma<64, 2, 4>(q, q_stride, rd, kv, layer, B, R, n_heads, partial, n_splits, out, ncg, s);
   return hipErrorInvalidValue;
 }
 
