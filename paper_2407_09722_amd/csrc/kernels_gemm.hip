@@ -179,7 +179,7 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
 // the S weight tiles of that k tile, so the L2 -> compute-unit traffic of the fragments per weight byte is 1/S of the
 // one-strip kernel's (which spends 12 to 15 % of its time on them at 5 rows: measured by knocking the loads out).
 // U tiles per batch and strip, two batches in flight as above; the S strips are reduced and finished at the
-// same time by different waves.  Used with S = 3, U = 2 for 4 to 8 rows.
+// same time by different waves.  Used with S = 3 for 4 to 8 rows (U = 2) and 9 to 16 rows (U = 1).
 template <int NG, int EPI, int TAG, int S, int U>
 __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((S + NG) * U * 8 + S * NG * 4 > 100 ? 2 : 4))) void gemm_bf16_strips_kernel(GemmArgs a) {
   static_assert(S * NG <= GW, "one wave finishes one (strip, row group)");
@@ -513,6 +513,13 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
     if (ng >= 2 && a.part && a.counters && a.N / 16 <= SPLIT_MAX_STRIPS && ((a.K >> 5) >= SPLIT_KS * GW * 8 || (ng >= 7 && (a.K >> 5) >= SPLIT_KS * GW * 2))) {
       S = smax < SPLIT_S ? smax : SPLIT_S;  // share the fragments between strips, keep every compute unit busy by cutting k
       KS = SPLIT_KS;
+    }
+    // 9 to 16 rows, no k split, at least two strips per compute unit: the three-strip kernel with two row groups, whose
+    // six epilogues run side by side (C3 target at 9 and 12 rows: 3.47 -> 3.39 ms per pass)
+    if (KS == 1 && ng == 2 && a.N / 16 >= 2 * device_cus()) {
+      e = run_strips<2, EPI, 3, 1>(a, tag, s);
+      if (e != hipSuccess) return e;
+      continue;
     }
     if (S > 1) {
       if (ng <= 2) e = run_multi<2, EPI>(a, S, KS, s);
