@@ -179,10 +179,9 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
 // the S weight tiles of that k tile, so the L2 -> compute-unit traffic of the fragments per weight byte is 1/S of the
 // one-strip kernel's (which spends 12 to 15 % of its time on them at 5 rows: measured by knocking the loads out).
 // U tiles per batch and strip, two batches in flight as above; the S strips are reduced and finished at the
-// same time by different waves.  Used with S = 3 for 4 to 8 rows (U = 2) and 9 to 16 rows (U = 1).
+// same time by different waves.  Used with S = 3 for 4 to 8 rows (U = 2) and 9 to 24 rows (U = 1).
 template <int NG, int EPI, int TAG, int S, int U>
 __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((S + NG) * U * 8 + S * NG * 4 > 100 ? 2 : 4))) void gemm_bf16_strips_kernel(GemmArgs a) {
-  static_assert(S * NG <= GW, "one wave finishes one (strip, row group)");
   __shared__ floatx4 red[S * GW * NG * 64];
   __shared__ float inv_s[NG * 8];
   const int lane = threadIdx.x & 63;
@@ -244,8 +243,8 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((S + NG
 #pragma unroll
     for (int g = 0; g < NG; ++g) red[((s2 * GW + wave) * NG + g) * 64 + lane] = acc[s2][g];
   __syncthreads();
-  if (wave < S * NG) {
-    const int s2 = wave / NG, g = wave % NG;
+  for (int item = wave; item < S * NG; item += GW) {  // (a ninth item falls to wave 0 again)
+    const int s2 = item / NG, g = item % NG;
     if (s2 < ns) gemm_finish_group<NG, EPI>(a, nt0 + s2, g, red + s2 * GW * NG * 64, inv_s, rows_here, lane);
   }
 }
@@ -514,10 +513,11 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
       S = smax < SPLIT_S ? smax : SPLIT_S;  // share the fragments between strips, keep every compute unit busy by cutting k
       KS = SPLIT_KS;
     }
-    // 9 to 16 rows, no k split, at least two strips per compute unit: the three-strip kernel with two row groups, whose
-    // six epilogues run side by side (C3 target at 9 and 12 rows: 3.47 -> 3.39 ms per pass)
-    if (KS == 1 && ng == 2 && a.N / 16 >= 2 * device_cus()) {
-      e = run_strips<2, EPI, 3, 1>(a, tag, s);
+    // 9 to 24 rows, no k split, at least two strips per compute unit: the three-strip kernel with two or three row
+    // groups, whose epilogues run side by side (C3 target at 9 and 12 rows: 3.47 -> 3.39 ms per pass; C4, 17 rows:
+    // 4.22 -> 4.12 ms)
+    if (KS == 1 && (ng == 2 || ng == 3) && a.N / 16 >= 2 * device_cus()) {
+      e = ng == 2 ? run_strips<2, EPI, 3, 1>(a, tag, s) : run_strips<3, EPI, 3, 1>(a, tag, s);
       if (e != hipSuccess) return e;
       continue;
     }

@@ -73,8 +73,8 @@ def _gemm_case(mb, R, N, K, dtype, seed, accumulate=False, ldy=None, ctx=None, x
                                    # 4 to 8 rows and at least two strips per compute unit: three strips per workgroup; strip
                                    # counts that leave the last workgroup one or two strips, odd k tile counts
                                    (5, 22016, 4096), (8, 8208, 160), (4, 8224, 96), (7, 8240, 1056), (6, 32000, 352),
-                                   # 9 to 16 rows on the same kernel with two row groups
-                                   (10, 12288, 4096), (16, 8208, 160), (9, 8224, 96), (13, 32000, 352),
+                                   # 9 to 24 rows on the same kernel with two or three row groups
+                                   (10, 12288, 4096), (16, 8208, 160), (9, 8224, 96), (13, 32000, 352), (17, 22016, 4096), (24, 8240, 96), (19, 8208, 1056),
                                    # many rows: activations staged through LDS, 4 or 8 strips per workgroup, 8 / 16 / 24 column groups
                                    (164, 16400, 256), (64, 16384, 160), (128, 16384, 96), (70, 16, 32), (190, 48, 1056), (77, 2000, 352), (25, 16400, 288), (32, 32000, 2048)])
 def test_gemm_bf16_matches_float64(R, N, K):
