@@ -512,6 +512,8 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
     if (ng >= 2 && a.part && a.counters && a.N / 16 <= SPLIT_MAX_STRIPS && ((a.K >> 5) >= SPLIT_KS * GW * 8 || (ng >= 7 && (a.K >> 5) >= SPLIT_KS * GW * 2))) {
       S = smax < SPLIT_S ? smax : SPLIT_S;  // share the fragments between strips, keep every compute unit busy by cutting k
       KS = SPLIT_KS;
+      if (ng <= 3) S = KS = 2;  // 9 to 24 rows: two strips and two ranges (C4 verify 4.12 -> 4.05 ms; 3 x 2, 4 x 2, 2 x 3 and 2 x 4
+                                // slower; the same cut for the o projection, 128 k tiles, slower too)
     }
     // 9 to 24 rows, no k split, at least two strips per compute unit: the three-strip kernel with two or three row
     // groups, whose epilogues run side by side (C3 target at 9 and 12 rows: 3.47 -> 3.39 ms per pass; C4, 17 rows:
