@@ -21,8 +21,11 @@ constexpr int GW = 8;  // waves per workgroup of the stand-alone product kernel
 // Epilogue of one row group of one strip.  s: this lane's four sums (packed features kg*4 .. +3 of strip nt, row m;
 // hi and lo already folded), live: the lane holds a real row, inv: the row's fused-RMSNorm factor (1 if none).
 // Every lane of the wave must call it (it shuffles).
-template <int EPI, bool COH = false>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int nt, floatx4 s, int m, bool live, float inv, int kg) {
+// pre_h, pre_gn: the RESID epilogue's residual row and next-norm gain for this lane if the kernel requested them ahead
+// (HAVE_PRE), else they are loaded here.
+template <int EPI, bool COH = false, bool HAVE_PRE = false>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int nt, floatx4 s, int m, bool live, float inv, int kg,
+                                              float4 pre_h = float4{0.f, 0.f, 0.f, 0.f}, float4 pre_gn = float4{0.f, 0.f, 0.f, 0.f}) {
   const int NT = a.N >> 4, R = a.R;
     if constexpr (EPI == EPI_STORE) {
       const int n = nt * 16 + kg * 4;
@@ -51,10 +54,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int nt, floatx4
       float4 hn = make_float4(0.f, 0.f, 0.f, 0.f);
       if (live) {
         float4* hp = (float4*)(a.h + (int64_t)m * a.N + n);
-        const float4 p = *hp;
+        const float4 p = HAVE_PRE ? pre_h : *hp;
         hn = make_float4(p.x + s[0], p.y + s[1], p.z + s[2], p.w + s[3]);
         *hp = hn;
-        const float4 gn = *(const float4*)(a.g_next + n);
+        const float4 gn = HAVE_PRE ? pre_gn : *(const float4*)(a.g_next + n);
         ushort4 hi, lo;
         split_bf16(hn.x * gn.x, hi.x, lo.x);
         split_bf16(hn.y * gn.y, hi.y, lo.y);
@@ -157,9 +160,10 @@ __device__ __forceinline__ void gemm_finish_sum(const GemmArgs& a, int nt, int g
 }
 
 // Both steps for a workgroup that holds a strip's whole reduction dimension.
-template <int NG, int EPI, bool COH = false, int NWAVES = GW>
+template <int NG, int EPI, bool COH = false, int NWAVES = GW, bool HAVE_PRE = false>
 __device__ __forceinline__ void gemm_finish_group(const GemmArgs& a, int nt, int g, const floatx4* red, const float* inv_s,
-                                                  int rows_here, int lane) {
+                                                  int rows_here, int lane, float4 pre_h = float4{0.f, 0.f, 0.f, 0.f},
+                                                  float4 pre_gn = float4{0.f, 0.f, 0.f, 0.f}) {
   const int c = lane & 15, kg = lane >> 4;
   floatx4 s = gemm_sum_waves<NG, NWAVES>(g, red, lane);
 #pragma unroll
@@ -167,7 +171,7 @@ __device__ __forceinline__ void gemm_finish_group(const GemmArgs& a, int nt, int
   const int mrel = g * 8 + (c & 7);
   const bool live = c < 8 && mrel < rows_here;
   const float inv = (a.ssq && live) ? inv_s[mrel] : 1.0f;
-  gemm_epilogue<EPI, COH>(a, nt, s, a.row0 + mrel, live, inv, kg);
+  gemm_epilogue<EPI, COH, HAVE_PRE>(a, nt, s, a.row0 + mrel, live, inv, kg, pre_h, pre_gn);
 }
 
 // Row factors of a fused RMSNorm into inv_s[0 .. rows_here): 1/sqrt(sum of the producer's partial sums of squares / K + eps).

@@ -124,7 +124,7 @@ __device__ __forceinline__ ActAddr act_addr(const GemmArgs& a, int lane) {
 }
 
 template <int NG, int EPI, int TAG>
-__global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1 ? 6 : 4))) void gemm_bf16_kernel(GemmArgs a) {
+__global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((NG <= 1 && EPI != EPI_RESID) ? 6 : 4))) void gemm_bf16_kernel(GemmArgs a) {
   constexpr int U = (NG <= 2) ? 4 : (NG <= 4 ? 2 : 1);  // weight tiles per batch and wave
   __shared__ floatx4 red[GW * NG * 64];
   __shared__ float inv_s[NG * 8];
@@ -151,6 +151,16 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
   floatx4 acc[NG];
 #pragma unroll
   for (int g = 0; g < NG; ++g) acc[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+  // RESID: the finishing wave requests its residual values and the next norm's gain now.  Products with this epilogue
+  // (o, down) have about one workgroup per compute unit, so nothing else covers that latency after the stream.
+  float4 pre_h = float4{0.f, 0.f, 0.f, 0.f}, pre_gn = pre_h;
+  if constexpr (EPI == EPI_RESID) {
+    const int mrel = wave * 8 + (c & 7);
+    if (wave < NG && c < 8 && mrel < rows_here) {
+      pre_h = *(const float4*)(a.h + (int64_t)(row0 + mrel) * a.N + nt * 16 + kg * 4);
+      pre_gn = *(const float4*)(a.g_next + nt * 16 + kg * 4);
+    }
+  }
 
   for (int kt = wave; kt < KT; kt += 2 * span) {
 #pragma unroll
@@ -172,7 +182,7 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu(NG <= 1
   for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[g];
   gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);  // after the stream: its loads are L2 hits by now for most workgroups
   __syncthreads();
-  if (wave < NG) gemm_finish_group<NG, EPI>(a, nt, wave, red, inv_s, rows_here, lane);
+  if (wave < NG) gemm_finish_group<NG, EPI, false, GW, EPI == EPI_RESID>(a, nt, wave, red, inv_s, rows_here, lane, pre_h, pre_gn);
 }
 
 // The same kernel for S strips per workgroup: the activation fragments of a k tile are loaded once and multiplied with
