@@ -254,11 +254,33 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   __syncthreads();  // the row factors are in place
   const bool owner = wk == 0;
   const int own = ws * WCQ + wc;
+  // The epilogues of a tile's 4 strips x C column groups are shared between its KP waves: strip si goes to wave si % KP.
+  // One wave running all of them queued up to 24 chains of dependent loads (rotary table, cache slots, residual rows)
+  // behind each other while its partner waves had already left.
   if (KS == 1) {
-    if (!owner) return;
+    if constexpr (KP > 1) {
+      floatx4* const red = reinterpret_cast<floatx4*>(lds_raw);  // free again: the sums were read before the barrier above
+      if (owner) {
+#pragma unroll
+        for (int si = 0; si < 4; ++si)
+          if (si % KP != 0) {
+#pragma unroll
+            for (int j = 0; j < C; ++j) red[((own * 4 + si) * C + j) * 64 + lane] = acc[si][j];
+          }
+      }
+      __syncthreads();
+      if (!owner) {
+#pragma unroll
+        for (int si = 0; si < 4; ++si)
+          if (si % KP == wk) {
+#pragma unroll
+            for (int j = 0; j < C; ++j) acc[si][j] = red[((own * 4 + si) * C + j) * 64 + lane];
+          }
+      }
+    }
 #pragma unroll
     for (int si = 0; si < 4; ++si)
-      if (nt0 + si < NT) {
+      if (si % KP == wk && nt0 + si < NT) {
 #pragma unroll
         for (int j = 0; j < C; ++j)
           if (j < cv) gemm_finish_sum<EPI>(a, nt0 + si, j * WCQ + wc, acc[si][j], inv_s, rows_here, lane);
@@ -287,10 +309,10 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
     if (last_s) __hip_atomic_store(a.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
   }
   __syncthreads();
-  if (!last_s || !owner) return;
+  if (!last_s) return;
 #pragma unroll
   for (int si = 0; si < 4; ++si)
-    if (nt0 + si < NT) {
+    if (si % KP == wk && nt0 + si < NT) {  // the tile's KP waves share its strips
 #pragma unroll
       for (int j = 0; j < C; ++j)
         if (j < cv) {
