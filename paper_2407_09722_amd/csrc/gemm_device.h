@@ -147,16 +147,31 @@ __device__ __forceinline__ floatx4 gemm_sum_waves(int g, const floatx4* red, int
   return s;
 }
 
+// The RESID epilogue's inputs of (strip nt, row group g) for this lane: residual values and next-norm gain (zeros for
+// lanes without a row).  Requested for several epilogues at once, their latencies overlap instead of adding up.
+__device__ __forceinline__ void gemm_resid_inputs(const GemmArgs& a, int nt, int g, int rows_here, int lane, float4& h, float4& gn) {
+  const int c = lane & 15, kg = lane >> 4;
+  const int mrel = g * 8 + (c & 7);
+  h = float4{0.f, 0.f, 0.f, 0.f};
+  gn = h;
+  if (c < 8 && mrel < rows_here) {
+    const int n = nt * 16 + kg * 4;
+    h = *(const float4*)(a.h + (int64_t)(a.row0 + mrel) * a.N + n);
+    gn = *(const float4*)(a.g_next + n);
+  }
+}
+
 // hi + lo fold of a row group's sums, then the epilogue.
-template <int EPI, bool COH = false>
-__device__ __forceinline__ void gemm_finish_sum(const GemmArgs& a, int nt, int g, floatx4 s, const float* inv_s, int rows_here, int lane) {
+template <int EPI, bool COH = false, bool HAVE_PRE = false>
+__device__ __forceinline__ void gemm_finish_sum(const GemmArgs& a, int nt, int g, floatx4 s, const float* inv_s, int rows_here, int lane,
+                                                float4 pre_h = float4{0.f, 0.f, 0.f, 0.f}, float4 pre_gn = float4{0.f, 0.f, 0.f, 0.f}) {
   const int c = lane & 15, kg = lane >> 4;
 #pragma unroll
   for (int i = 0; i < 4; ++i) s[i] += __shfl_xor(s[i], 8, 64);  // columns c and c + 8 are the hi and lo terms of one row
   const int mrel = g * 8 + (c & 7);
   const bool live = c < 8 && mrel < rows_here;
   const float inv = (a.ssq && live) ? inv_s[mrel] : 1.0f;
-  gemm_epilogue<EPI, COH>(a, nt, s, a.row0 + mrel, live, inv, kg);
+  gemm_epilogue<EPI, COH, HAVE_PRE>(a, nt, s, a.row0 + mrel, live, inv, kg, pre_h, pre_gn);
 }
 
 // Both steps for a workgroup that holds a strip's whole reduction dimension.

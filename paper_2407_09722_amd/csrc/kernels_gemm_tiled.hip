@@ -281,9 +281,18 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
 #pragma unroll
     for (int si = 0; si < 4; ++si)
       if (si % KP == wk && nt0 + si < NT) {
+        if constexpr (EPI == EPI_RESID) {  // the strip's residual inputs for all column groups first: one latency, not C
+          float4 ph[C], pg[C];
 #pragma unroll
-        for (int j = 0; j < C; ++j)
-          if (j < cv) gemm_finish_sum<EPI>(a, nt0 + si, j * WCQ + wc, acc[si][j], inv_s, rows_here, lane);
+          for (int j = 0; j < C; ++j) gemm_resid_inputs(a, nt0 + si, j * WCQ + wc, j < cv ? rows_here : 0, lane, ph[j], pg[j]);
+#pragma unroll
+          for (int j = 0; j < C; ++j)
+            if (j < cv) gemm_finish_sum<EPI, false, true>(a, nt0 + si, j * WCQ + wc, acc[si][j], inv_s, rows_here, lane, ph[j], pg[j]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < C; ++j)
+            if (j < cv) gemm_finish_sum<EPI>(a, nt0 + si, j * WCQ + wc, acc[si][j], inv_s, rows_here, lane);
+        }
       }
     return;
   }
@@ -313,6 +322,11 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
 #pragma unroll
   for (int si = 0; si < 4; ++si)
     if (si % KP == wk && nt0 + si < NT) {  // the tile's KP waves share its strips
+      float4 ph[C], pg[C];
+      if constexpr (EPI == EPI_RESID) {  // the residual inputs of all column groups are requested with the partial sums
+#pragma unroll
+        for (int j = 0; j < C; ++j) gemm_resid_inputs(a, nt0 + si, j * WCQ + wc, j < cv ? rows_here : 0, lane, ph[j], pg[j]);
+      }
 #pragma unroll
       for (int j = 0; j < C; ++j)
         if (j < cv) {
@@ -322,7 +336,8 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
             const uint4 v = ld16<true>(p + (size_t)k2 * range_stride);
             sum[0] += __uint_as_float(v.x); sum[1] += __uint_as_float(v.y); sum[2] += __uint_as_float(v.z); sum[3] += __uint_as_float(v.w);
           }
-          gemm_finish_sum<EPI>(a, nt0 + si, j * WCQ + wc, sum, inv_s, rows_here, lane);
+          if constexpr (EPI == EPI_RESID) gemm_finish_sum<EPI, false, true>(a, nt0 + si, j * WCQ + wc, sum, inv_s, rows_here, lane, ph[j], pg[j]);
+          else gemm_finish_sum<EPI>(a, nt0 + si, j * WCQ + wc, sum, inv_s, rows_here, lane);
         }
     }
 }
