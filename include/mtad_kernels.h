@@ -30,10 +30,10 @@ int mtad_k_gemm(mtad_ctx *ctx, int32_t dtype, const void *W, const void *X, floa
  * x_order MTAD_X_PLANES is mtad_k_gemm; MTAD_X_FRAGMENTS is the B-operand fragment order of the 16x16x32 bfloat16
  * matrix instruction, 8 rows at a time.  With kt = k / 32, kg = (k % 32) / 8, e = k % 8 and plane 0 = hi, 1 = lo, the
  * element (plane, r, k) lies at
- *   R <= 8:  ((((kt * 4 + kg) * 2 + plane) * R + r) * 8 + e                                   (K/32 fragments of 128 R bytes)
- *   R >  8:  ((((kt * G + r / 8) * 64 + kg * 16 + plane * 8 + r % 8) * 8 + e,  G = ceil(R / 8)   (K/32 * G fragments of 1 KiB;
+ *   R <= 24: ((((kt * 4 + kg) * 2 + plane) * R + r) * 8 + e                                   (128 R bytes per k tile)
+ *   R >  24: ((((kt * G + r / 8) * 64 + kg * 16 + plane * 8 + r % 8) * 8 + e,  G = ceil(R / 8)   (K/32 * G fragments of 1 KiB;
  *            the buffer holds G * 8 rows, the slots of rows past R are not read into results).
- * A product then reads whole cache lines per fragment.  X: device, 4 * K * (R <= 8 ? R : 8 * G) bytes.  Other arguments, errors
+ * A product then reads whole cache lines per fragment.  X: device, 4 * K * (R <= 24 ? R : 8 * G) bytes.  Other arguments, errors
  * and kernel choice as mtad_k_gemm; with 25 rows or more and a context's workspace the many-row kernel reads X directly. */
 enum { MTAD_X_PLANES = 0, MTAD_X_FRAGMENTS = 1 };
 int mtad_k_gemm_x(mtad_ctx *ctx, int32_t dtype, const void *W, const void *X, float *Y, int32_t R, int32_t N, int32_t K, int32_t ldy,

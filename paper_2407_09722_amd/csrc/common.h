@@ -27,14 +27,17 @@ __device__ __forceinline__ void split_bf16(float x, bf16_t& hi, bf16_t& lo) {
 // Element offset of activation (plane, row, feature k) of a pass of R rows and K features.  ncg == 0: two planes
 // [2][R][K].  ncg > 0 (= ceil(R / 8)): operand-fragment order, the B operand of v_mfma_f32_16x16x32_bf16 for 8 rows at a
 // time, where lane (k%32)/8 * 16 + plane * 8 + row % 8 holds 8 consecutive features of fragment (k / 32, row / 8):
-//   R > 8   [K/32][ncg][64 lanes][8]: whole fragments, the slots of rows past R unused;
-//   R <= 8  [K/32][4 k groups][2 planes][R rows][8]: the same order with the unused row slots left out, so a fragment
-//           is 128 R bytes = R whole cache lines (5 lines at 5 rows instead of 8).
+//   R > 24   [K/32][ncg][64 lanes][8]: whole fragments, the slots of rows past R unused (the many-row kernel copies
+//            them to LDS line by line);
+//   R <= 24  [K/32][4 k groups][2 planes][R rows][8]: the same order with the unused row slots left out: a k tile's
+//            fragments are 128 R contiguous bytes (5 cache lines at 5 rows instead of 8, 17 at 17 rows instead of 24);
+//            row group g of a (k group, plane) block starts 128 g bytes into it.
 // Products read this order (whole cache lines per fragment instead of 64-byte pieces of 16 rows); whatever produces
 // their input writes it.
+constexpr int ACT_COMPACT_ROWS = 24;  // passes of up to this many rows leave the unused row slots out
 __host__ __device__ __forceinline__ int64_t act_offset(int ncg, int R, int K, int plane, int row, int k) {
   if (ncg == 0) return ((int64_t)plane * R + row) * K + k;
-  if (R <= 8) return ((((int64_t)(k >> 5) * 4 + ((k >> 3) & 3)) * 2 + plane) * R + row) * 8 + (k & 7);
+  if (R <= ACT_COMPACT_ROWS) return ((((int64_t)(k >> 5) * 4 + ((k >> 3) & 3)) * 2 + plane) * R + row) * 8 + (k & 7);
   return ((((int64_t)(k >> 5) * ncg + (row >> 3)) * 64 + ((k >> 3) & 3) * 16 + plane * 8 + (row & 7)) << 3) + (k & 7);
 }
 

@@ -109,11 +109,11 @@ __device__ __forceinline__ ActAddr act_addr(const GemmArgs& a, int lane) {
     r.xoff = (unsigned)((((size_t)(c >> 3) * a.R + (c & 7)) * a.K + kg * 8) * 2);  // plane c/8, row c%8, k group kg
     r.kstride = 64;
     r.gstride = (size_t)16 * a.K;
-  } else if (a.R <= 8) {  // fragments without the unused row slots (act_offset): one row group, row0 = 0
+  } else if (a.R <= ACT_COMPACT_ROWS) {  // fragments without the unused row slots (act_offset); one launch, row0 = 0
     r.X = (const char*)a.X;
     r.xoff = (unsigned)(((kg * 2 + (c >> 3)) * a.R + (c & 7)) * 16);  // lanes of rows past R are never loaded
     r.kstride = (size_t)a.R * 128;
-    r.gstride = 0;
+    r.gstride = 128;  // the next 8 rows of the same (k group, plane)
   } else {
     r.X = (const char*)a.X + (size_t)(a.row0 >> 3) * 1024;  // launches start at multiples of 8 rows
     r.xoff = (unsigned)lane * 16u;

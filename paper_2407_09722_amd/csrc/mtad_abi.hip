@@ -262,7 +262,7 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const int tail = 1 + 6 * m->n_layers;
   const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
   // one kernel per step, 2 rows or more: activations in operand-fragment order (act_offset), whole cache lines per
-  // fragment, without the unused row slots up to 8 rows (C3 verify, 5 rows: 3.20 ms on planes, 3.14 ms with 8-row
+  // fragment, without the unused row slots up to 24 rows (C3 verify, 5 rows: 3.20 ms on planes, 3.14 ms with 8-row
   // fragments, 2.98 ms with 5-row fragments on the three-strip product kernel; 2 to 4 rows 1 to 3 % faster than on
   // planes; one row, plain decoding, 1 % slower); the persistent kernel reads planes
   const int ncg = (persistent || rows < 2) ? 0 : (rows + 7) / 8;

@@ -23,11 +23,11 @@ def _fragment_order(planes):
     """[2][R][K] bfloat16 bit planes -> the operand-fragment order mtad_k_gemm_x documents (written out from that text)."""
     _, R, K = planes.shape
     G = (R + 7) // 8
-    rows = R if R <= 8 else 8 * G
+    rows = R if R <= 24 else 8 * G
     out = np.zeros(2 * rows * K, dtype=planes.dtype)
     plane, r, k = np.meshgrid(np.arange(2), np.arange(R), np.arange(K), indexing="ij")
     kt, kg, e = k // 32, (k % 32) // 8, k % 8
-    if R <= 8:
+    if R <= 24:
         off = ((((kt * 4 + kg) * 2 + plane) * R + r) * 8) + e
     else:
         off = (((kt * G + r // 8) * 64 + kg * 16 + plane * 8 + r % 8) * 8) + e
