@@ -373,18 +373,17 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
     if (last_s) __hip_atomic_store(a.counters + blockIdx.x, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next launch
   }
   __syncthreads();
-  if (!last_s || wave >= NG) return;
-#pragma unroll
-  for (int s2 = 0; s2 < SM; ++s2) {
-    if (s2 < ns) {
-      const float* p = mypart + ((((size_t)s2 * NG + wave) * KS) * 64 + lane) * 4;
-      floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
-      for (int k2 = 0; k2 < KS; ++k2) {
-        const uint4 v = ld16<true>(p + (size_t)k2 * 256);
-        sum[0] += __uint_as_float(v.x); sum[1] += __uint_as_float(v.y); sum[2] += __uint_as_float(v.z); sum[3] += __uint_as_float(v.w);
-      }
-      gemm_finish_sum<EPI>(a, nt0 + s2, wave, sum, inv_s, rows_here, lane);
+  if (!last_s) return;
+  // (strip s2, row group g) = item s2 * NG + g goes to wave item % GW, as above: all waves share the merges
+  for (int item = wave; item < ns * NG; item += GW) {
+    const int s2 = item / NG, g = item % NG;
+    const float* p = mypart + ((((size_t)s2 * NG + g) * KS) * 64 + lane) * 4;
+    floatx4 sum = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int k2 = 0; k2 < KS; ++k2) {
+      const uint4 v = ld16<true>(p + (size_t)k2 * 256);
+      sum[0] += __uint_as_float(v.x); sum[1] += __uint_as_float(v.y); sum[2] += __uint_as_float(v.z); sum[3] += __uint_as_float(v.w);
     }
+    gemm_finish_sum<EPI>(a, nt0 + s2, g, sum, inv_s, rows_here, lane);
   }
 }
 
