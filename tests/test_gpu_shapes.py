@@ -42,6 +42,18 @@ def test_c4_widths_tree_of_17_rows():
         assert all(ev[3] < 5e-3 for ev in st["events"] if ev[0] == "beam step") and all(ev[-1] < 5e-3 for ev in st["events"] if ev[0] != "beam step")
 
 
+@pytest.mark.parametrize("gamma,beam,mode", [(8, 2, "mtad"), (4, 3, "mmtad"), (7, 2, "mtad"), (3, 1, "mtad")])
+def test_c3_widths_other_row_counts(gamma, beam, mode):
+    """The same widths at 9 rows (two row groups on the three-strip product kernel), 13 rows (tree), 8 rows (a full row
+    group) and 4 rows (the fewest rows that kernel takes): every fused epilogue at those shapes against the oracle."""
+    w, wt, wd = _pair("C3", 1, 1, 96)
+    print(f"C3-L1 gamma={gamma} beam={beam} {mode}", flush=True)
+    st = run_pair(w.target, w.draft, wt, wd, si.make_prompt(w), 4, gamma=gamma, beam=beam, mode=mode, tau=0.0, seed=w.seed, max_iters=2)
+    print(f"C3-L1 gamma={gamma} beam={beam} {mode}: max logit err {st['max_logit_err']:.2e}, parted: {st['events']}")
+    assert st["iters"] >= 1
+    assert all(ev[3] < 5e-3 for ev in st["events"] if ev[0] == "beam step") and all(ev[-1] < 5e-3 for ev in st["events"] if ev[0] != "beam step")
+
+
 def test_c5_widths_batch4_tree_of_41_rows_gqa_draft():
     """13B-shaped target (d 5120, 40 heads), GQA draft (32 heads, 4 kv heads), batch 4, 8 beams x gamma 5 = 40 nodes + root."""
     w, wt, wd = _pair("C5", 1, 1, 70)
