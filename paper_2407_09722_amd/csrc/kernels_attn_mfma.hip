@@ -223,13 +223,13 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         }
       tmax = xmax(xmax(tmax, 16), 32);
       const float m_new = fmaxf(m_run[rg], tmax);
-      const float alpha = (m_run[rg] == -INFINITY) ? 0.f : expf(m_run[rg] - m_new);
+      const float alpha = (m_run[rg] == -INFINITY) ? 0.f : __expf(m_run[rg] - m_new);
       float psum = 0.f;
 #pragma unroll
       for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float pv = (s2[rg][blk][i] == -INFINITY) ? 0.f : expf(s2[rg][blk][i] - m_new);
+          const float pv = (s2[rg][blk][i] == -INFINITY) ? 0.f : __expf(s2[rg][blk][i] - m_new);
           psum += pv;
           const _Float16 hi = (_Float16)pv;
           ph[rg][blk * 4 + i] = hi;
