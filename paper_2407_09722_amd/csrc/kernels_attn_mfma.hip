@@ -207,20 +207,33 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     // visibility, scale, running softmax per row; probabilities become the B operand of the second product
     half8 ph[NRG], pl[NRG];
+    // a tile that lies inside the committed context (all but the last one or two) is visible to every row: no mask
+    const bool plain = kbeg + (ti + 1) * ATK <= min(len, kend);  // uniform over the wave
 #pragma unroll
     for (int rg = 0; rg < NRG; ++rg) {
       float tmax = -INFINITY;
+      if (plain) {
 #pragma unroll
-      for (int blk = 0; blk < 2; ++blk)
+        for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int kj = kbeg + ti * ATK + blk * 16 + sg4 * 4 + i;
-          bool vis = kj < kend;
-          if (vis && kj >= len) vis = (rmask[rg] >> (kj - len)) & 1ull;
-          const float sv = vis ? s2[rg][blk][i] * scale : -INFINITY;
-          s2[rg][blk][i] = sv;
-          tmax = fmaxf(tmax, sv);
-        }
+          for (int i = 0; i < 4; ++i) {
+            const float sv = s2[rg][blk][i] * scale;
+            s2[rg][blk][i] = sv;
+            tmax = fmaxf(tmax, sv);
+          }
+      } else {
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int kj = kbeg + ti * ATK + blk * 16 + sg4 * 4 + i;
+            bool vis = kj < kend;
+            if (vis && kj >= len) vis = (rmask[rg] >> (kj - len)) & 1ull;
+            const float sv = vis ? s2[rg][blk][i] * scale : -INFINITY;
+            s2[rg][blk][i] = sv;
+            tmax = fmaxf(tmax, sv);
+          }
+      }
       tmax = xmax(xmax(tmax, 16), 32);
       const float m_new = fmaxf(m_run[rg], tmax);
       const float alpha = (m_run[rg] == -INFINITY) ? 0.f : __expf(m_run[rg] - m_new);
