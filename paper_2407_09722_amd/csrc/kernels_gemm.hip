@@ -180,7 +180,7 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((NG <= 
   }
 #pragma unroll
   for (int g = 0; g < NG; ++g) red[(wave * NG + g) * 64 + lane] = acc[g];
-  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);  // after the stream: its loads are L2 hits by now for most workgroups
+  gemm_row_factors<false, (NG > 1 ? NG : 1)>(a, inv_s, rows_here, wave, lane, GW);  // after the stream: its loads are L2 hits by now for most workgroups
   __syncthreads();
   if (wave < NG) gemm_finish_group<NG, EPI, false, GW, EPI == EPI_RESID>(a, nt, wave, red, inv_s, rows_here, lane, pre_h, pre_gn);
 }
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((S + NG
       }
     }
   }
-  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);
+  gemm_row_factors<false, (NG > 1 ? NG : 1)>(a, inv_s, rows_here, wave, lane, GW);
   // all strips' sums to LDS at once; wave s2 * NG + g then finishes row group g of strip s2, the strips side by side
   // (one after the other, each epilogue's dependent loads, the rotary table, cache slots and residual rows, added up)
 #pragma unroll
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(GW * 64) void gemm_bf16_multi_kernel(GemmArgs a, in
       }
     }
   }
-  gemm_row_factors(a, inv_s, rows_here, wave, lane, GW);  // after the stream (see the single-strip kernel)
+  gemm_row_factors<false, (NG > 1 ? 8 : 1)>(a, inv_s, rows_here, wave, lane, GW);  // after the stream (see the single-strip kernel)
   // partial sums of (group, strip s2, row group g, range ks): 64 lanes x 4 floats
   float* const mypart = a.part ? a.part + ((((size_t)blockIdx.x * SM) * NG) * KS) * 256 : nullptr;
   // The strips are reduced through LDS one after the other; (strip s2, row group g) = item s2 * NG + g goes to wave

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(TW * 64) void gemm_bf16_tiled_kernel(GemmArgs a) {
   }
   if (!late) __syncthreads();
 
-  gemm_row_factors(a, inv_s, rows_here, wave, lane, TW);
+  gemm_row_factors<false, 8>(a, inv_s, rows_here, wave, lane, TW);
   if constexpr (KP > 1) {  // the waves of one accumulator tile add their sums in wave order
     floatx4* const red = reinterpret_cast<floatx4*>(lds_raw);  // [OWN][4*C][64], over the slabs (all consumed)
     const int own = ws * WCQ + wc;
