@@ -7,7 +7,8 @@
 // round-robin to the waves; every wave runs its own online softmax over its tiles, with the K and V of the next tile in
 // flight, and the waves merge through LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup,
 // which writes the attention output itself: no exchange through global memory.  Longer contexts are cut into splits
-// (at least one tile per wave each, at most as many as fill the machine once); every split leaves (max, sum, output)
+// (at least one tile per wave each, at most as many as fill the machine once, or every resident slot where once is an
+// uneven fill); every split leaves (max, sum, output)
 // per row in global memory (same partial layout as the generic kernel) and a small second kernel, one wave per row,
 // merges them in split order.
 //
@@ -63,14 +64,19 @@ __device__ __forceinline__ int token_index(const KvView& kv, int seq, int pos) {
 
 // Keys of sequence seq (committed + speculative) and the key splits used for it.  Every workgroup of the attention
 // kernel and of the merge kernel derives the same numbers: as many splits as the launch offers, but a split is worth its
-// exchange only if it gives every wave a tile (measured at 512 and 2048 keys).
+// exchange only if it gives every wave a tile (measured at 512 and 2048 keys).  want_splits = fill_splits +
+// (more_splits << 8): fill_splits give every compute unit a workgroup; more_splits, offered when that leaves some
+// compute units with two workgroups and the rest with one, fill every resident slot and are taken only where every
+// wave still gets four tiles.
 constexpr int ATTN_WAVES = 4;
 __device__ __forceinline__ int attn_keys(const KvView& kv, const RowDesc& rd, int seq) {
   const int nspec = max(0, min(rd.nspec[seq], 64));
   return min(kv.len[seq] + nspec, kv_capacity(kv));
 }
 __device__ __forceinline__ int attn_splits(int ktot, int n_splits, int want_splits) {
-  return max(1, min(min(n_splits, want_splits), ktot / (ATTN_WAVES * ATK)));
+  const int fill = min(want_splits & 255, ktot / (ATTN_WAVES * ATK));
+  const int more = min(want_splits >> 8, ktot / (4 * ATTN_WAVES * ATK));
+  return max(1, min(n_splits, max(fill, more)));
 }
 
 template <int HD, int NRG, int AW>
@@ -414,15 +420,28 @@ hipError_t run_mfma(const float* q, int q_stride, const RowDesc& rd, const KvVie
   static const hipError_t attr = lds > 64 * 1024 ? hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
                                                  : hipSuccess;
   if (attr != hipSuccess) return attr;
-  // splits: enough workgroups to fill the machine once (twice and four times over measured no faster at 512, 2048 and 4096 keys)
+  // splits: enough workgroups to fill the machine once (twice and four times over measured no faster at 512, 2048 and 4096
+  // keys when once is an even fill)
   static const int n_cus = [] {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
     return cus > 0 ? cus : 256;
   }();
   const int items = KVH * n_chunks * B;
-  const int want = items >= n_cus ? 1 : (n_cus + items - 1) / items;
-  const int gx = n_splits < want ? n_splits : want;
+  const int fill = items >= n_cus ? 1 : (n_cus + items - 1) / items;
+  // an uneven fill (C5's target pass: 160 items x 2 splits on 256 compute units) runs as long as the compute units that
+  // hold two workgroups; splits up to the number of resident slots shorten every workgroup instead (41 rows x 40 heads x
+  // 4 sequences at 4096 keys: 99 -> 80 us with 3 splits)
+  static const int per_cu = [&] {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void*)kern, AW * 64, lds) != hipSuccess) n = 1;
+    return n > 0 ? n : 1;
+  }();
+  const int more = (items * fill > n_cus && per_cu >= 2) ? (n_cus * per_cu) / items : 0;
+  const int fill8 = fill < 255 ? fill : 255, more8 = more < 255 ? more : 255;
+  const int want = fill8 | (more8 << 8);
+  const int widest = fill8 > more8 ? fill8 : more8;
+  const int gx = n_splits < widest ? n_splits : widest;
   hipLaunchKernelGGL(kern, dim3(gx, KVH * n_chunks, B), dim3(AW * 64), lds, s, q, q_stride, rd, kv, layer, R, n_heads, n_chunks, scale,
                      partial, n_splits, (bf16_t*)out, want, ncg);
   hipError_t e = hipGetLastError();
