@@ -52,8 +52,36 @@ struct MfmaAttnSmem {
   float m[AW][NRG * 16], l[AW][NRG * 16];
 };
 
-__device__ __forceinline__ float xmax(float v, int off) { return fmaxf(v, __shfl_xor(v, off, 64)); }
-__device__ __forceinline__ float xsum(float v, int off) { return v + __shfl_xor(v, off, 64); }
+// Exchange with lane ^ 16 or lane ^ 32 through the row / half swap instructions of gfx950 (vector ALU, no LDS round trip:
+// the softmax of a tile waits for four such exchanges per row group).  Swapping a register with its own copy leaves the
+// even rows (lower half) in one result and the odd rows (upper half) in the other, each duplicated: every lane then
+// holds its own value and its partner's.
+template <int OFF>
+__device__ __forceinline__ void lane_pair(float v, float& a, float& b) {
+  static_assert(OFF == 16 || OFF == 32, "row or half swap");
+  const unsigned u = __float_as_uint(v);
+  if constexpr (OFF == 16) {
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+  } else {
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+  }
+}
+template <int OFF>
+__device__ __forceinline__ float xmax(float v) {
+  float a, b;
+  lane_pair<OFF>(v, a, b);
+  return fmaxf(a, b);
+}
+template <int OFF>
+__device__ __forceinline__ float xsum(float v) {
+  float a, b;
+  lane_pair<OFF>(v, a, b);
+  return a + b;
+}
 
 // physical token index (page * page_size + offset) of logical position pos; pages outside the pool read page 0
 __device__ __forceinline__ int token_index(const KvView& kv, int seq, int pos) {
@@ -240,7 +268,7 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
             tmax = fmaxf(tmax, sv);
           }
       }
-      tmax = xmax(xmax(tmax, 16), 32);
+      tmax = xmax<32>(xmax<16>(tmax));
       const float m_new = fmaxf(m_run[rg], tmax);
       const float alpha = (m_run[rg] == -INFINITY) ? 0.f : __expf(m_run[rg] - m_new);
       float psum = 0.f;
@@ -254,7 +282,7 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
           ph[rg][blk * 4 + i] = hi;
           pl[rg][blk * 4 + i] = (_Float16)(pv - (float)hi);
         }
-      psum = xsum(xsum(psum, 16), 32);
+      psum = xsum<32>(xsum<16>(psum));
       l_run[rg] = l_run[rg] * alpha + psum;
       m_run[rg] = m_new;
 #pragma unroll
