@@ -65,6 +65,24 @@ def test_c5_widths_batch4_tree_of_41_rows_gqa_draft():
     assert all(ev[3] < 5e-3 for ev in st["events"] if ev[0] == "beam step") and all(ev[-1] < 5e-3 for ev in st["events"] if ev[0] != "beam step")
 
 
+@pytest.mark.parametrize("mode", ["mtad", "mmtad"])
+def test_long_context_with_more_key_splits_than_compute_units_need(mode):
+    """12 heads of 128 x 8 sequences = 96 attention work items: three key splits already give every compute unit a
+    workgroup, unevenly (288 on 256), so a context of more than 2048 keys is cut into four (the splits that fill the
+    resident slots), with 5 rows (one row group per item) and with 17 (two)."""
+    t = si.ModelShape(1, 1536, 12, 12, 128, 1536, 1024, "bf16")
+    d = si.ModelShape(1, 256, 4, 4, 64, 512, 1024, "bf16")
+    w = si.Workload("long", t, d, seed=11, batch=8, prompt_len=2100, new_tokens=4, gamma=4, beam=4, mode=mode, tau=0.0)
+    wt = si.make_weights(t, w.seed, "target", threads=16)
+    wd = si.make_weights(d, w.seed, "draft", threads=16)
+    print(f"long context {mode}", flush=True)
+    st = run_pair(t, d, wt, wd, si.make_prompt(w), 4, gamma=w.gamma, beam=w.beam, mode=mode, tau=0.0, seed=w.seed, max_iters=2,
+                  prefill_rows=32)  # 8 sequences x 32 rows: the most a pass holds
+    print(f"long context {mode}: max logit err {st['max_logit_err']:.2e}, parted: {st['events']}")
+    assert st["iters"] >= 1
+    assert all(ev[3] < 5e-3 for ev in st["events"] if ev[0] == "beam step") and all(ev[-1] < 5e-3 for ev in st["events"] if ev[0] != "beam step")
+
+
 # ---- decision kernels on the oracle's float32 inputs: integers must be identical -------------------------------------
 
 def _engine(B, gamma, beam, mode, V):
