@@ -102,7 +102,10 @@ __device__ __forceinline__ int attn_keys(const KvView& kv, const RowDesc& rd, in
   return min(kv.len[seq] + nspec, kv_capacity(kv));
 }
 __device__ __forceinline__ int attn_splits(int ktot, int n_splits, int want_splits) {
-  const int fill = min(want_splits & 255, ktot / (ATTN_WAVES * ATK));
+  // from two splits on, one more for a remainder: it keeps every wave at one tile (C3, 516 keys: 5 splits of 4 tiles
+  // instead of 4 splits of 5, whose first wave runs a second tile after the first)
+  constexpr int WK = ATTN_WAVES * ATK;
+  const int fill = min(want_splits & 255, ktot < 2 * WK ? 1 : (ktot + WK - 1) / WK);
   const int more = min(want_splits >> 8, ktot / (4 * ATTN_WAVES * ATK));
   return max(1, min(n_splits, max(fill, more)));
 }
