@@ -23,6 +23,8 @@
 // The running output, maximum and sum of a row all live in the lanes of that row: no exchange inside the tile loop.
 #include "common.h"
 
+#include <type_traits>
+
 namespace mtad {
 
 namespace {
@@ -164,27 +166,38 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
   // score product has been issued, and the next tile's requests go out at those points (V, needed first, first).  The
   // loads are unconditional (keys past the end read token 0 of page 0): their scores are masked, and their V rows are
   // zeroed so that they contribute exact zeros.  The first tile is requested before the queries are staged.
-  KFrag kf[2][KS], vf[NV];
-  auto load_k = [&](int tok32) {
+  // Where the registers allow it (DEEP) there are two such sets and a wave has two tiles in flight: with one set the
+  // requests of a tile go out only when the tile before has arrived, so every tile of a wave pays a full memory latency.
+  constexpr bool DEEP = HD == 64 || NRG == 1;
+  constexpr int NSET = DEEP ? 2 : 1, AHEAD = NSET * AW;
+  constexpr std::integral_constant<int, 0> SET0{};
+  constexpr std::integral_constant<int, NSET - 1> SET1{};
+  KFrag kf[NSET][2][KS], vf[NSET][NV];
+  auto load_k = [&](auto set, int tok32) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk) {
       const int tk = max(0, __shfl(tok32, blk * 16 + srow, 64));
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
+      for (int ks = 0; ks < KS; ++ks) kf[set()][blk][ks].u = *(const uint4*)(kbase + (int64_t)tk * tok_stride + ks * 32 + sg4 * 8);
     }
   };
-  auto load_v = [&](int tok32) {
+  auto load_v = [&](auto set, int tok32) {
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
       const int tk = __shfl(tok32, j * KPL + lane / CH, 64);
       const uint4 v = *(const uint4*)(vbase + (int64_t)max(0, tk) * tok_stride + (lane % CH) * 8);
-      vf[j].u = tk >= 0 ? v : make_uint4(0, 0, 0, 0);
+      vf[set()][j].u = tk >= 0 ? v : make_uint4(0, 0, 0, 0);
     }
   };
   if (wave < n_tiles) {
     const int tok = lookup(wave);
-    load_v(tok);
-    load_k(tok);
+    load_v(SET0, tok);
+    load_k(SET0, tok);
+  }
+  if (DEEP && wave + AW < n_tiles) {
+    const int tok = lookup(wave + AW);
+    load_v(SET1, tok);
+    load_k(SET1, tok);
   }
 
   // queries of the item as half hi / lo terms in LDS (rows beyond the item are zero)
@@ -211,13 +224,13 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     for (int db = 0; db < DB; ++db) acc[rg][db] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto process = [&](int ti) {
-    const bool more = ti + AW < n_tiles;                    // uniform over the wave
-    const int tok_next = more ? lookup(ti + AW) : -1;       // the page-table read of the next tile starts here
+  auto process = [&](auto set, int ti) {                    // tile ti, whose K and V are in (or on the way to) register set `set`
+    const bool more = ti + AHEAD < n_tiles;                 // uniform over the wave
+    const int tok_next = more ? lookup(ti + AHEAD) : -1;    // the page-table read of the set's next tile starts here
     // V tile -> wave-private LDS copy
 #pragma unroll
-    for (int j = 0; j < NV; ++j) *(uint4*)&sm.a.v[wave][j * KPL + lane / CH][(lane % CH) * 8] = vf[j].u;
-    if (more) load_v(tok_next);
+    for (int j = 0; j < NV; ++j) *(uint4*)&sm.a.v[wave][j * KPL + lane / CH][(lane % CH) * 8] = vf[set()][j].u;
+    if (more) load_v(set, tok_next);
 
     // S^T = K Q^T: lane (sg4, srow) gets keys blk*16 + sg4*4 + i of row rg*16 + srow
     floatx4 s2[NRG][2];
@@ -233,11 +246,11 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         const half8 ql = *(const half8*)&sm.a.q[1][rg * 16 + srow][ks * 32 + sg4 * 8];
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
-          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, qh, s2[rg][blk], 0, 0, 0);
-          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[blk][ks].h, ql, s2[rg][blk], 0, 0, 0);
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[set()][blk][ks].h, qh, s2[rg][blk], 0, 0, 0);
+          s2[rg][blk] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[set()][blk][ks].h, ql, s2[rg][blk], 0, 0, 0);
         }
       }
-    if (more) load_k(tok_next);  // the score product has read its K operands
+    if (more) load_k(set, tok_next);  // the score product has read its K operands
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the V tile is in LDS (the wave reads what other lanes wrote)
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -310,7 +323,10 @@ __global__ __launch_bounds__(AW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     __builtin_amdgcn_wave_barrier();  // the V tile has been read before the next one overwrites it
   };
 #pragma unroll 1
-  for (int ti = wave; ti < n_tiles; ti += AW) process(ti);
+  for (int ti = wave; ti < n_tiles; ti += AHEAD) {
+    process(SET0, ti);
+    if (DEEP && ti + AW < n_tiles) process(SET1, ti + AW);
+  }
   // ---- the waves meet in LDS (the buffer aliases the V tiles and the queries)
   const int mrow = t / TPR, md = (t % TPR) * DPT;  // merge role: row within a row group, first of DPT dims
   typedef bf16_t bf16xd __attribute__((ext_vector_type(DPT)));
