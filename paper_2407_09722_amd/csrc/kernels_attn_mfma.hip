@@ -4,8 +4,8 @@
 // Work item = (key split, KV head, chunk of 16 or 32 (query head, row) pairs, sequence) = one workgroup of AW waves (4 in
 // all configurations used; 8 measured no faster).  The query heads that share a KV head are rows of the same item, so a
 // grouped-query model reads K and V once for all of them.  The keys of the item are cut into 32-key tiles dealt
-// round-robin to the waves; every wave runs its own online softmax over its tiles, with the K and V of the next tile in
-// flight, and the waves merge through LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup,
+// round-robin to the waves; every wave runs its own online softmax over its tiles, with the K and V of the next tile
+// (the next two, where the registers allow a second set) in flight, and the waves merge through LDS at the end.  A context of fewer than 2 x waves x 32 keys is one workgroup,
 // which writes the attention output itself: no exchange through global memory.  Longer contexts are cut into splits
 // (at least one tile per wave each, at most as many as fill the machine once, or every resident slot where once is an
 // uneven fill); every split leaves (max, sum, output)
