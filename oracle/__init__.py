@@ -10,10 +10,19 @@ Only tests, the smoke check and the benchmark's cpu_baseline leg may import it. 
 shares no code with the HIP path and does not import it.
 
 Pins (tests/test_oracle_*.py):
-  lm.DecoderLM          incremental/tree-masked form == full recompute; hand-computed
-                        one-layer case; logit spread closed form.  The decoder
-                        architecture itself is fixed by the workload description, not by
-                        the paper: "parity unpinned" by the paper for the architecture.
+  lm.DecoderLM          an independently written decoder from torch library routines
+                        (rms_norm, complex-number rotary, scaled_dot_product_attention,
+                        silu), float32 and bfloat16 forms; incremental/tree-masked form ==
+                        full recompute; causality, rotary shift invariance, sibling order;
+                        logit spread closed form.  The decoder architecture itself is fixed
+                        by the workload description, not by the paper: "parity unpinned"
+                        by the paper for the architecture.
+  lm.DecoderLM._rp      hi == library bfloat16(x), lo == library bfloat16(x - hi),
+                        |x - (hi + lo)| <= 2^-16 |x|.
+  lm.DecoderLM._rkv     == library half precision (range limit 65504 included).
+                        Why these two and not one bfloat16 term: the self-noise test
+                        (one-term contract: the oracle against a 1e-7 perturbed copy of
+                        itself ends more than 2e-2 apart; this contract: below 5e-3).
   mtad.beam_search      brute force over all |V|^gamma sequences; width 1 == greedy;
                         stochastic width 1 == ancestral sampling (chi-square).
   mtad.verify           tree form == per-branch sequential decoding == enumeration.
