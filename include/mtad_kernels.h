@@ -59,6 +59,20 @@ int mtad_k_beam_topb(mtad_ctx *ctx, const float *logits, const float *lse, mtad_
                      const int32_t *catchup_cnt, const int32_t *len, int32_t rows_per_seq, int32_t vocab,
                      int32_t sample_beam, uint64_t seed, void *stream);
 
+/* mtad_k_beam_topb for callers that cannot allocate device memory or bind a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results; the shapes a context would carry
+ * (batch, gamma, beam) are arguments, and the scratch of the two-stage selection (the stage-1 winners) lives in a
+ * device array inside the library: 256 KiB per GPU, present from the first call on that GPU until the process ends.  The
+ * call allocates nothing and only enqueues work on `stream`.
+ * Limits: batch <= MTAD_STATIC_TOPB_MAX_BATCH (MTAD_ECAP beyond it), beam <= MTAD_MAX_BEAM, rows_per_seq >= gamma + 1 at
+ * step 0 and >= beam afterwards (the rows the kernels read), vocab >= beam.
+ * All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU (different streams or
+ * threads) race; calls on one stream, or otherwise ordered, are safe, and nothing has to be cleared between them. */
+#define MTAD_STATIC_TOPB_MAX_BATCH 64
+int mtad_k_beam_topb_static(const float *logits, const float *lse, mtad_beam *hist, int32_t batch, int32_t gamma, int32_t beam,
+                            int32_t step, const int32_t *catchup_cnt, const int32_t *len, int32_t rows_per_seq, int32_t vocab,
+                            int32_t sample_beam, uint64_t seed, void *stream);
+
 /* Streaming copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned).  It moves exactly `bytes` in
  * and `bytes` out, which makes it the reference for scaling the hardware's byte counters and for the bandwidth
  * that perfectly coalesced traffic reaches on the device (the paper's cost model, Section 4, prices runs by

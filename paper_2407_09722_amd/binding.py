@@ -19,7 +19,7 @@ MTAD_MAX_ROWS, MTAD_MAX_BEAM = 64, 8
 EXPORTS = ["mtad_create", "mtad_destroy", "mtad_workspace_bytes", "mtad_bind_workspace", "mtad_strerror",
            "mtad_last_hip_error", "mtad_device_status", "mtad_set_persistent", "mtad_set_warp", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
            "mtad_verify_tree", "mtad_accept", "mtad_accept_spd", "mtad_accept_chain", "mtad_kv_commit",
-           "mtad_k_gemm", "mtad_k_gemm_x", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_copy"]
+           "mtad_k_gemm", "mtad_k_gemm_x", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_beam_topb_static", "mtad_k_copy"]
 
 i32, u64, f32, vp = C.c_int32, C.c_uint64, C.c_float, C.c_void_p
 
@@ -99,6 +99,7 @@ def lib():
         L.mtad_k_warp_rows.argtypes = [vp, vp, i32, i32, i32, f32, vp]
         L.mtad_k_copy.argtypes = [vp, vp, C.c_int64, vp]
         L.mtad_k_beam_topb.argtypes = [vp, vp, vp, P(mtad_beam), i32, vp, vp, i32, i32, i32, u64, vp]
+        L.mtad_k_beam_topb_static.argtypes = [vp, vp, P(mtad_beam), i32, i32, i32, i32, vp, vp, i32, i32, i32, u64, vp]
         for name in EXPORTS:
             fn = getattr(L, name)
             if name not in ("mtad_destroy", "mtad_workspace_bytes", "mtad_strerror"):
@@ -225,6 +226,16 @@ def mtad_k_row_lse(logits, lse, rows, vocab, stream=None):
 def mtad_k_beam_topb(ctx, logits, lse, hist, step, catchup_cnt, length, rows_per_seq, vocab, sample_beam=0, seed=0, stream=None):
     _check("mtad_k_beam_topb", lib().mtad_k_beam_topb(ctx, ptr(logits), ptr(lse), C.byref(hist), step, ptr(catchup_cnt), ptr(length),
                                                      rows_per_seq, vocab, int(sample_beam), u64(seed), _stream_ptr(stream)))
+
+
+MTAD_STATIC_TOPB_MAX_BATCH = 64
+
+
+def mtad_k_beam_topb_static(logits, lse, hist, batch, gamma, beam, step, catchup_cnt, length, rows_per_seq, vocab, sample_beam=0, seed=0,
+                            stream=None):
+    _check("mtad_k_beam_topb_static", lib().mtad_k_beam_topb_static(ptr(logits), ptr(lse), C.byref(hist), batch, gamma, beam, step,
+                                                                   ptr(catchup_cnt), ptr(length), rows_per_seq, vocab, int(sample_beam),
+                                                                   u64(seed), _stream_ptr(stream)))
 
 
 def mtad_k_copy(src, dst, nbytes, stream=None):

@@ -8,6 +8,7 @@
 #include "pass.h"
 
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
@@ -693,11 +694,58 @@ int mtad_k_beam_topb(mtad_ctx* c, const float* logits, const float* lse, mtad_be
                      const int32_t* len, int32_t rows_per_seq, int32_t vocab, int32_t sample_beam, uint64_t seed, void* stream) {
   if (!c || !c->ws || !logits || !lse || !hist || !hist->tok || !hist->parent || !hist->cum_logq || !catchup_cnt || !len)
     return MTAD_EINVAL;
-  if (step < 0 || step >= c->cfg.gamma || vocab < c->cfg.beam || rows_per_seq < 1) return MTAD_EINVAL;
+  if (step < 0 || step >= c->cfg.gamma || vocab < c->cfg.beam) return MTAD_EINVAL;
+  if (rows_per_seq < (step == 0 ? c->cfg.gamma + 1 : c->cfg.beam)) return MTAD_EINVAL;  // the rows the kernels may read
   const BeamView hv{hist->tok, hist->parent, hist->cum_logq};
   HIP_TRY(c, launch_topb(logits, lse, hv, catchup_cnt, len, step, c->cfg.batch, rows_per_seq, c->cfg.gamma, c->cfg.beam, vocab,
                          sample_beam ? 1 : 0, seed, c->part_key, c->part_idx, TOPB_BLOCKS, (hipStream_t)stream));
   return MTAD_OK;
+}
+
+// ---- the same selection for callers that cannot allocate --------------------------------------------------------
+// The two-stage top-b keeps its stage-1 winners in a scratch buffer; here that buffer is a file-scope device array
+// instead of a caller's workspace.  In host code the array's name is only a stand-in: its device address is looked up
+// once per device (each device holds its own copy) and only that address is handed to kernels.
+namespace {
+constexpr size_t STATIC_TOPB_ENTRIES = (size_t)MTAD_STATIC_TOPB_MAX_BATCH * TOPB_BLOCKS * 8;  // stage-1 winners, MAXB per block
+struct StaticTopbScratch {
+  float key[STATIC_TOPB_ENTRIES];
+  int idx[STATIC_TOPB_ENTRIES];
+};
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex scratch_mu;
+void* scratch_ptr[STATIC_MAX_DEVICES];  // device address of `scratch` on each device, null until first used there
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticTopbScratch)];  // 256 KiB per device, held until the process ends
+
+int mtad_k_beam_topb_static(const float* logits, const float* lse, mtad_beam* hist, int32_t batch, int32_t gamma, int32_t beam, int32_t step,
+                            const int32_t* catchup_cnt, const int32_t* len, int32_t rows_per_seq, int32_t vocab, int32_t sample_beam,
+                            uint64_t seed, void* stream) {
+  if (!logits || !lse || !hist || !hist->tok || !hist->parent || !hist->cum_logq || !catchup_cnt || !len) return MTAD_EINVAL;
+  if (batch < 1 || gamma < 1 || beam < 1 || step < 0 || step >= gamma || vocab < beam) return MTAD_EINVAL;
+  if (rows_per_seq < (step == 0 ? gamma + 1 : beam)) return MTAD_EINVAL;
+  if (beam > MTAD_MAX_BEAM || gamma > MTAD_MAX_ROWS) return MTAD_ESHAPE;
+  if (batch > MTAD_STATIC_TOPB_MAX_BATCH) return MTAD_ECAP;  // the static scratch array holds no more sequences
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return MTAD_EHIP;
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return MTAD_ECAP;
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+      void* p = nullptr;
+      if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MTAD_EHIP;
+      scratch_ptr[dev] = p;
+    }
+    base = scratch_ptr[dev];
+  }
+  StaticTopbScratch* sc = (StaticTopbScratch*)base;
+  const BeamView hv{hist->tok, hist->parent, hist->cum_logq};
+  // every entry stage 2 reads is written by stage 1 of the same call: nothing needs clearing between calls
+  return launch_topb(logits, lse, hv, catchup_cnt, len, step, batch, rows_per_seq, gamma, beam, vocab, sample_beam ? 1 : 0, seed, sc->key,
+                     sc->idx, TOPB_BLOCKS, (hipStream_t)stream) == hipSuccess
+             ? MTAD_OK
+             : MTAD_EHIP;
 }
 
 }  // extern "C"
