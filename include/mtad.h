@@ -144,11 +144,11 @@ void mtad_destroy(mtad_ctx *ctx);
  * any hot call.  The contents need no initialisation.  ECAP if too small. */
 size_t mtad_workspace_bytes(const mtad_ctx *ctx);
 int mtad_bind_workspace(mtad_ctx *ctx, void *device_buf, size_t bytes);
-/* on != 0: bf16 models with at most 32 rows in a pass run all layers of a pass in one persistent kernel (one workgroup
- * per compute unit, software grid barriers with bounded waits; a wait that gives up sets status bit 3).  Default off
- * (one kernel per product: same arithmetic, and faster on this machine); the environment variable MTAD_PERSISTENT=1
- * turns it on at context creation. */
-int mtad_set_persistent(mtad_ctx *ctx, int32_t on);
+/* bf16 passes of at most 8 rows (all sequences together) run every product and the attention of every layer as work units
+ * of ONE kernel launch, handed out in dependency order (on != 0, the default), or as one kernel per step (on == 0: same
+ * arithmetic; the form every larger pass takes).  Waits inside the one-launch pass are bounded: one that gives up sets
+ * status bit 3 and the pass runs to its end.  The environment variable MTAD_FUSED_PASS=0 turns it off at context creation. */
+int mtad_set_fused_pass(mtad_ctx *ctx, int32_t on);
 /* Warped distributions (appendix "Hyper-parameter Details"; the footnote of Section 3.2 allows approximating p~ with
  * q~): with top_k > 0 every next-token distribution of both models is warped before it is used: the top_k most likely
  * tokens keep their probabilities and are normalised; of those, in descending order, the shortest prefix whose cumulative
@@ -162,7 +162,7 @@ const char *mtad_strerror(int status);
 int mtad_last_hip_error(const mtad_ctx *ctx); /* hipError_t of the last failed HIP call, 0 if none */
 /* Copies the sticky device status word to *host_bits after synchronising `stream` (the only call that
  * synchronises).  Bit 0: KV capacity exceeded; bit 1: speculative window (64 rows) exceeded;
- * bit 2: bad catch-up count; bit 3: a grid-barrier wait of the persistent kernel gave up.  0 = clean. */
+ * bit 2: bad catch-up count; bit 3: a bounded wait inside the one-launch pass gave up.  0 = clean. */
 int mtad_device_status(mtad_ctx *ctx, uint32_t *host_bits, void *stream);
 
 /* Repacks a row-major bfloat16 matrix [N][K] (device) into the layout the matrix-core kernels stream: the 16x32

@@ -17,7 +17,7 @@ MTAD_MODE_MTAD, MTAD_MODE_MMTAD = 0, 1
 MTAD_MAX_ROWS, MTAD_MAX_BEAM = 64, 8
 
 EXPORTS = ["mtad_create", "mtad_destroy", "mtad_workspace_bytes", "mtad_bind_workspace", "mtad_strerror",
-           "mtad_last_hip_error", "mtad_device_status", "mtad_set_persistent", "mtad_set_warp", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
+           "mtad_last_hip_error", "mtad_device_status", "mtad_set_fused_pass", "mtad_set_warp", "mtad_pack_matrix", "mtad_prefill", "mtad_draft_beam_step", "mtad_build_tree",
            "mtad_verify_tree", "mtad_accept", "mtad_accept_spd", "mtad_accept_chain", "mtad_kv_commit",
            "mtad_k_gemm", "mtad_k_gemm_x", "mtad_k_rmsnorm", "mtad_k_row_lse", "mtad_k_warp_rows", "mtad_k_beam_topb", "mtad_k_beam_topb_static", "mtad_k_copy"]
 
@@ -81,7 +81,7 @@ def lib():
         L.mtad_strerror.restype = C.c_char_p
         L.mtad_last_hip_error.argtypes = [vp]
         L.mtad_device_status.argtypes = [vp, P(C.c_uint32), vp]
-        L.mtad_set_persistent.argtypes = [vp, i32]
+        L.mtad_set_fused_pass.argtypes = [vp, i32]
         L.mtad_set_warp.argtypes = [vp, i32, f32]
         L.mtad_pack_matrix.argtypes = [i32, vp, vp, i32, i32, i32, vp]
         L.mtad_prefill.argtypes = [vp, P(mtad_model), P(mtad_kv), vp, i32, vp]
@@ -152,8 +152,8 @@ def mtad_k_warp_rows(logits, lse, rows, vocab, top_k, top_p, stream=None):
     _check("mtad_k_warp_rows", lib().mtad_k_warp_rows(ptr(logits), ptr(lse), rows, vocab, int(top_k), f32(top_p), _stream_ptr(stream)))
 
 
-def mtad_set_persistent(ctx, on: bool):
-    _check("mtad_set_persistent", lib().mtad_set_persistent(ctx, int(on)))
+def mtad_set_fused_pass(ctx, on: bool):
+    _check("mtad_set_fused_pass", lib().mtad_set_fused_pass(ctx, int(on)))
 
 
 def mtad_device_status(ctx, stream=None) -> int:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmtad.so")
-SOURCES = ["kernels_gemm.hip", "kernels_gemm_tiled.hip", "kernels_misc.hip", "kernels_attn.hip", "kernels_attn_mfma.hip", "kernels_beam.hip", "kernels_pass.hip", "mtad_abi.hip"]
+SOURCES = ["kernels_gemm.hip", "kernels_gemm_tiled.hip", "kernels_misc.hip", "kernels_attn.hip", "kernels_attn_mfma.hip", "kernels_beam.hip", "kernels_flow.hip", "mtad_abi.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 

@@ -1,4 +1,4 @@
-// Device-side tree attention shared by the stand-alone kernel (kernels_attn.hip) and the persistent pass kernel.
+// Device-side tree attention of float32 models (kernels_attn.hip).
 #pragma once
 #include "common.h"
 

@@ -40,6 +40,8 @@ struct GemmArgs {
   // of 256 floats, and one zeroed counter per group (left zeroed); null = no split
   float* part;
   int* counters;
+  size_t part_floats;  // capacity of `part` in floats and of `counters` in ints: a launch that would need more does not split
+  int counters_n;
   // scratch for the many-row kernel: the pass's activations rewritten in B-operand fragment order; null = not offered
   // (such products then run on the skinny kernels)
   bf16_t* xfrag;

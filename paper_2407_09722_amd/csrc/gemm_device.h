@@ -1,5 +1,5 @@
 // Device-side pieces of the skinny bf16 matrix product shared by the stand-alone kernel (kernels_gemm.hip)
-// and the persistent pass kernel (kernels_pass.hip): fragment types and the epilogues.
+// and the one-launch pass (kernels_flow.hip): fragment types, operand loads and the epilogues.
 #pragma once
 #include "common.h"
 #include "gemm.h"
@@ -17,6 +17,60 @@ union Frag {
 };
 
 constexpr int GW = 8;  // waves per workgroup of the stand-alone product kernel
+
+// ---- operand loads shared by the product kernels ---------------------------------------------------------------
+
+template <int U>
+__device__ __forceinline__ void gemm_load_w(Frag (&w)[U], const char* strip, int KT, int kt, unsigned voff) {
+  const char* base = strip + ((size_t)kt << 10);  // tiles are 1 KiB each, k-major within the strip
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+    if (kt + u * GW < KT) w[u].n = __builtin_nontemporal_load((const uintx4*)(base + (size_t)u * (GW << 10) + voff));
+}
+
+// Activation fragments of k tiles kt + u*GW for NG row groups.  X + xoff is this lane's 16 bytes of (row group 0, k tile 0);
+// a k tile is kstride bytes further, a row group gstride bytes (plane layout: 64 and 16 K; fragment order: 1024 x the
+// pass's row groups and 1024).
+template <int NG, int U>
+__device__ __forceinline__ void gemm_load_b(Frag (&b)[U][NG], const char* X, unsigned xoff, size_t kstride, size_t gstride, int KT, int kt,
+                                            int rows_here, int c) {
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      b[u][g].u = make_uint4(0, 0, 0, 0);
+      const char* base = X + (size_t)g * gstride + (size_t)(kt + u * GW) * kstride;
+      if (kt + u * GW < KT && g * 8 + (c & 7) < rows_here) b[u][g].u = *(const uint4*)(base + xoff);
+    }
+}
+
+// (X base of the launch's first row, lane offset, k tile stride, row group stride) for either activation layout
+struct ActAddr {
+  const char* X;
+  unsigned xoff;
+  size_t kstride, gstride;
+};
+__device__ __forceinline__ ActAddr act_addr(const GemmArgs& a, int lane) {
+  const int c = lane & 15, kg = lane >> 4;
+  ActAddr r;
+  if (a.ncg == 0) {
+    r.X = (const char*)a.X + (size_t)a.row0 * a.K * 2;
+    r.xoff = (unsigned)((((size_t)(c >> 3) * a.R + (c & 7)) * a.K + kg * 8) * 2);  // plane c/8, row c%8, k group kg
+    r.kstride = 64;
+    r.gstride = (size_t)16 * a.K;
+  } else if (a.R <= ACT_COMPACT_ROWS) {  // fragments without the unused row slots (act_offset); one launch, row0 = 0
+    r.X = (const char*)a.X;
+    r.xoff = (unsigned)(((kg * 2 + (c >> 3)) * a.R + (c & 7)) * 16);  // lanes of rows past R are never loaded
+    r.kstride = (size_t)a.R * 128;
+    r.gstride = 128;  // the next 8 rows of the same (k group, plane)
+  } else {
+    r.X = (const char*)a.X + (size_t)(a.row0 >> 3) * 1024;  // launches start at multiples of 8 rows
+    r.xoff = (unsigned)lane * 16u;
+    r.kstride = (size_t)a.ncg * 1024;
+    r.gstride = 1024;
+  }
+  return r;
+}
 
 // Epilogue of one row group of one strip.  s: this lane's four sums (packed features kg*4 .. +3 of strip nt, row m;
 // hi and lo already folded), live: the lane holds a real row, inv: the row's fused-RMSNorm factor (1 if none).
@@ -54,9 +108,22 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs& a, int nt, floatx4
       float4 hn = make_float4(0.f, 0.f, 0.f, 0.f);
       if (live) {
         float4* hp = (float4*)(a.h + (int64_t)m * a.N + n);
-        const float4 p = HAVE_PRE ? pre_h : *hp;
+        float4 p;
+        if constexpr (HAVE_PRE) {
+          p = pre_h;
+        } else if constexpr (COH) {  // written by a workgroup of this kernel (an earlier step's strip owner)
+          const uint4 u = ld16<true>(hp);
+          p = make_float4(__uint_as_float(u.x), __uint_as_float(u.y), __uint_as_float(u.z), __uint_as_float(u.w));
+        } else {
+          p = *hp;
+        }
         hn = make_float4(p.x + s[0], p.y + s[1], p.z + s[2], p.w + s[3]);
-        *hp = hn;
+        if constexpr (COH) {
+          st8<true>(hp, make_uint2(__float_as_uint(hn.x), __float_as_uint(hn.y)));
+          st8<true>((float*)hp + 2, make_uint2(__float_as_uint(hn.z), __float_as_uint(hn.w)));
+        } else {
+          *hp = hn;
+        }
         const float4 gn = HAVE_PRE ? pre_gn : *(const float4*)(a.g_next + n);
         ushort4 hi, lo;
         split_bf16(hn.x * gn.x, hi.x, lo.x);

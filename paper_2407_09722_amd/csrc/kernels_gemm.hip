@@ -71,58 +71,6 @@ hipError_t launch_pack_matrix(const void* src, void* dst, int N, int K, int kind
 // tiles, the others keep the memory pipe full.
 // TAG only names the call site (0 draft pass, 1 target pass, 2 component entry point) in kernel traces.
 
-template <int U>
-__device__ __forceinline__ void gemm_load_w(Frag (&w)[U], const char* strip, int KT, int kt, unsigned voff) {
-  const char* base = strip + ((size_t)kt << 10);  // tiles are 1 KiB each, k-major within the strip
-#pragma unroll
-  for (int u = 0; u < U; ++u)
-    if (kt + u * GW < KT) w[u].n = __builtin_nontemporal_load((const uintx4*)(base + (size_t)u * (GW << 10) + voff));
-}
-
-// Activation fragments of k tiles kt + u*GW for NG row groups.  X + xoff is this lane's 16 bytes of (row group 0, k tile 0);
-// a k tile is kstride bytes further, a row group gstride bytes (plane layout: 64 and 16 K; fragment order: 1024 x the
-// pass's row groups and 1024).
-template <int NG, int U>
-__device__ __forceinline__ void gemm_load_b(Frag (&b)[U][NG], const char* X, unsigned xoff, size_t kstride, size_t gstride, int KT, int kt,
-                                            int rows_here, int c) {
-#pragma unroll
-  for (int u = 0; u < U; ++u)
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      b[u][g].u = make_uint4(0, 0, 0, 0);
-      const char* base = X + (size_t)g * gstride + (size_t)(kt + u * GW) * kstride;
-      if (kt + u * GW < KT && g * 8 + (c & 7) < rows_here) b[u][g].u = *(const uint4*)(base + xoff);
-    }
-}
-
-// (X base of the launch's first row, lane offset, k tile stride, row group stride) for either activation layout
-struct ActAddr {
-  const char* X;
-  unsigned xoff;
-  size_t kstride, gstride;
-};
-__device__ __forceinline__ ActAddr act_addr(const GemmArgs& a, int lane) {
-  const int c = lane & 15, kg = lane >> 4;
-  ActAddr r;
-  if (a.ncg == 0) {
-    r.X = (const char*)a.X + (size_t)a.row0 * a.K * 2;
-    r.xoff = (unsigned)((((size_t)(c >> 3) * a.R + (c & 7)) * a.K + kg * 8) * 2);  // plane c/8, row c%8, k group kg
-    r.kstride = 64;
-    r.gstride = (size_t)16 * a.K;
-  } else if (a.R <= ACT_COMPACT_ROWS) {  // fragments without the unused row slots (act_offset); one launch, row0 = 0
-    r.X = (const char*)a.X;
-    r.xoff = (unsigned)(((kg * 2 + (c >> 3)) * a.R + (c & 7)) * 16);  // lanes of rows past R are never loaded
-    r.kstride = (size_t)a.R * 128;
-    r.gstride = 128;  // the next 8 rows of the same (k group, plane)
-  } else {
-    r.X = (const char*)a.X + (size_t)(a.row0 >> 3) * 1024;  // launches start at multiples of 8 rows
-    r.xoff = (unsigned)lane * 16u;
-    r.kstride = (size_t)a.ncg * 1024;
-    r.gstride = 1024;
-  }
-  return r;
-}
-
 template <int NG, int EPI, int TAG>
 __global__ __launch_bounds__(GW * 64) __attribute__((amdgpu_waves_per_eu((NG <= 1 && EPI != EPI_RESID) ? 6 : 4))) void gemm_bf16_kernel(GemmArgs a) {
   constexpr int U = (NG <= 2) ? 4 : (NG <= 4 ? 2 : 1);  // weight tiles per batch and wave
@@ -523,6 +471,12 @@ static hipError_t run_epi(GemmArgs a, int tag, hipStream_t s) {
       KS = SPLIT_KS;
       if (ng <= 3) S = KS = 2;  // 9 to 24 rows: two strips and two ranges (C4 verify 4.12 -> 4.05 ms; 3 x 2, 4 x 2, 2 x 3 and 2 x 4
                                 // slower; the same cut for the o projection, 128 k tiles, slower too)
+      // the exchange must fit what the caller offers ((group, strip slot, row group, range) x 256 floats, a counter per group)
+      const int groups = (a.N / 16 + S - 1) / S;
+      if ((size_t)groups * smax * ngt * KS * 256 > a.part_floats || groups > a.counters_n) {
+        S = strips_per_group(a.N / 16, ngt);
+        KS = 1;
+      }
     }
     // 9 to 24 rows, no k split, at least two strips per compute unit: the three-strip kernel with two or three row
     // groups, whose epilogues run side by side (C3 target at 9 and 12 rows: 3.47 -> 3.39 ms per pass; C4, 17 rows:

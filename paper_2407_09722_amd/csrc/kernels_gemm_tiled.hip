@@ -23,6 +23,7 @@
 #include "gemm.h"
 #include "gemm_device.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace mtad {
@@ -365,12 +366,29 @@ int tiled_ks(int tiles, int stages) {
   return ks < 1 ? 1 : ks;
 }
 
+// LDS of one compute unit (the most a workgroup can be given); 160 KiB on gfx950 if the query fails
+size_t device_lds_bytes() {
+  static const size_t n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess) v = 0;
+    return v > 0 ? (size_t)v : (size_t)160 * 1024;
+  }();
+  return n;
+}
+
 template <int WS, int WCQ, int KP, int C, int SK, int EPI>
 hipError_t run_shape(const GemmArgs& a, hipStream_t s) {
   using Sh = TiledShape<WS, WCQ, KP, C, SK>;
+  static_assert(Sh::LDS_BYTES <= 160 * 1024, "more LDS than a gfx950 compute unit has");
   auto kern = gemm_bf16_tiled_kernel<WS, WCQ, KP, C, SK, EPI>;
-  static const hipError_t attr = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
-  if (attr != hipSuccess) return attr;
+  if ((size_t)Sh::LDS_BYTES + 1024 > device_lds_bytes()) return hipErrorInvalidValue;  // + the kernel's static arrays
+  // more than 64 KiB of dynamic LDS needs the attribute; a success is remembered, a failure is reported and tried again
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set.load(std::memory_order_acquire)) {
+    const hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Sh::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set.store(true, std::memory_order_release);
+  }
   const int NT = a.N >> 4, tiles = (NT + Sh::TN - 1) / Sh::TN;
   if (!a.ncg) {  // this launch's activations in fragment order (a pass that already holds them that way needs no copy)
     const int64_t frags = (int64_t)(a.K >> 5) * Sh::NCG;
@@ -380,6 +398,9 @@ hipError_t run_shape(const GemmArgs& a, hipStream_t s) {
   }
   int ks = 1;
   if (a.part && a.counters) ks = tiled_ks(tiles, ((a.K >> 5) + SK - 1) / SK);
+  // the exchange of a cut reduction must fit what the caller offers: (tile, range, owner wave, strip, column group) x 256 floats
+  // and one counter per tile; a product that does not fit runs uncut
+  if (ks > 1 && ((size_t)tiles * ks * Sh::OWN * 4 * C * 256 > a.part_floats || tiles > a.counters_n)) ks = 1;
   hipLaunchKernelGGL(kern, dim3(tiles, ks), dim3(TW * 64), Sh::LDS_BYTES, s, a);
   return hipGetLastError();
 }
@@ -410,15 +431,22 @@ size_t gemm_tiled_xfrag_elems(int R, int K) { (void)R; return (size_t)(K >> 5) *
 
 bool gemm_tiled_wide(int N) { return tiled_tn(N >> 4) == 8; }
 
-// floats of workspace the k split of a product with N outputs may use (0: never split)
+// floats of workspace the k split of a product with N outputs may use (0: never split): the larger of the needs of the
+// two tile widths the shapes above use (4 or 8 strips per workgroup; passes of 32 rows or fewer always take 8), each
+// with the most ranges tiled_ks can return for it and all 24 column groups
 size_t gemm_tiled_split_floats(int N) {
   const int NT = N >> 4;
   if (NT < 1) return 0;
-  const int TN = tiled_tn(NT), tiles = (NT + TN - 1) / TN;
-  int ks = device_cus() / tiles;
-  if (ks > KS_MAX) ks = KS_MAX;
-  if (ks < 2) return 0;
-  return (size_t)tiles * ks * TN * 24 * 256;  // TN strips x up to 24 column groups x 64 lanes x 4 floats per range
+  size_t need = 0;
+  for (int TN : {4, 8}) {
+    const int tiles = (NT + TN - 1) / TN;
+    int ks = device_cus() / tiles;
+    if (ks > KS_MAX) ks = KS_MAX;
+    if (ks < 2) continue;
+    const size_t n = (size_t)tiles * ks * TN * 24 * 256;  // TN strips x up to 24 column groups x 64 lanes x 4 floats per range
+    if (n > need) need = n;
+  }
+  return need;
 }
 int gemm_tiled_split_counters(int N) { return gemm_tiled_split_floats(N) ? ((N >> 4) + 3) / 4 : 0; }
 

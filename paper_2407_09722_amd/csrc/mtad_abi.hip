@@ -5,7 +5,7 @@
 #include "beam.h"
 #include "common.h"
 #include "gemm.h"
-#include "pass.h"
+#include "flow.h"
 
 #include <math.h>
 #include <mutex>
@@ -29,6 +29,7 @@ struct mtad_ctx {
   void *xn, *xg;  // xn: attention output / FFN activation; xg: h*gain planes feeding the next normalised product
   int* attn_cnt;
   float* gemm_part;  // k-split partial sums of the product kernel (products with few strips, more than 8 rows)
+  size_t gemm_part_n;  // floats
   int* gemm_cnt;
   int gemm_cnt_n;
   int pass_ncg;    // activation layout of the pass in flight (0 planes, else row groups of the fragment order): its lm_head reads it
@@ -41,24 +42,20 @@ struct mtad_ctx {
   int* part_idx;
   RowDesc rd;
   uint32_t* status;
-  unsigned long long* bar;  // grid barrier counter + abort flag of the persistent pass kernel
-  int n_cus;                // compute units of the device (workgroups of the persistent kernel)
-  int persistent;           // use the persistent pass kernel where it applies
-  // persistent pass: device copies of the step lists of (up to) two models, the host copies they were made from,
-  // and the device copy of the arguments of the pass being launched
-  PassStep* steps_dev[2];
-  PassStep steps_host[2][pass_steps(PASS_MAX_LAYERS, true)];
-  int steps_n[2];
-  int steps_evict;
+  int n_cus;                // compute units of the device
+  // one-launch pass (kernels_flow.hip) for bf16 passes of at most FLOW_MAX_ROWS rows: on by default
+  int flow_on;
+  bf16_t *flow_xg, *flow_xattn, *flow_xffn;  // per-step versions of the activation terms (see flow.h)
+  float *flow_ssq, *flow_q;
+  int* flow_sync;
+  int flow_sync_n;
+  FlowArgs* flow_args;  // device copy of the arguments of the pass in flight
+#ifdef MTAD_FLOW_PROFILE
+  unsigned long long* flow_prof;
+#endif
   // set by mtad_verify_tree around its pass: the logsumexp kernel of a bf16 pass then also gathers logp_cond
   const mtad_tree* gather_tree;
   float* gather_out;
-  PassArgs* pass_args;
-  bf16_t* pass_act;  // per-layer activation planes of the persistent pass
-  int pass_rows;     // rows those planes are sized for
-#ifdef MTAD_PASS_PROFILE
-  unsigned long long* prof;
-#endif
   int last_hip;
 };
 
@@ -67,6 +64,7 @@ namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int imax(int a, int b) { return a > b ? a : b; }
 inline int imin(int a, int b) { return a < b ? a : b; }
+inline size_t imax64(size_t a, size_t b) { return a > b ? a : b; }
 
 int shape_ok(const mtad_model* m) {
   if (m->n_layers < 1 || m->d_model < 1 || m->n_heads < 1 || m->n_kv_heads < 1 || m->d_ffn < 1 || m->vocab < 1) return 0;
@@ -130,29 +128,39 @@ void carve(mtad_ctx* c, char* base) {
         if (gemm_split_counters(N) > pc) pc = gemm_split_counters(N);
       }
     }
-    c->gemm_part = k.take<float>(pf + 64);
+    c->gemm_part_n = pf + 64;
+    c->gemm_part = k.take<float>(c->gemm_part_n);
     c->gemm_cnt_n = pc + 1;
     c->gemm_cnt = k.take<int>((size_t)c->gemm_cnt_n);
     // widest reduction dimension of any product: the model widths and FFN widths
     c->gemm_xfrag_n = gemm_tiled_xfrag_elems((int)rows, imax(imax(dmax, fmax), hhd));
     c->gemm_xfrag = k.take<bf16_t>(c->gemm_xfrag_n);
   }
-  c->bar = k.take<unsigned long long>(32);
-  for (int i = 0; i < 2; ++i) c->steps_dev[i] = k.take<PassStep>(pass_steps(PASS_MAX_LAYERS, true));
-  c->pass_args = k.take<PassArgs>(1);
-  {
-    c->pass_rows = (int)(rows < (size_t)PASS_MAX_ROWS ? rows : (size_t)PASS_MAX_ROWS);
-    size_t need = 0;
+  {  // the one-launch pass: versions of what its steps hand on, sized for FLOW_MAX_ROWS rows of the larger need of the two models
+    size_t xg = 0, ssq = 0, xa = 0, xf = 0, q = 0;
+    int items = 0;
     for (const mtad_model* m : {&t, &d}) {
-      if (m->dtype != 1 || m->n_layers > PASS_MAX_LAYERS) continue;
-      const size_t e = (size_t)m->n_layers * pass_act_elems_per_layer(m->d_model, m->n_heads * m->head_dim, m->d_ffn, c->pass_rows);
-      if (e > need) need = e;
+      if (m->dtype != 1 || m->n_layers > FLOW_MAX_LAYERS) continue;
+      const size_t L = (size_t)m->n_layers, R8 = FLOW_MAX_ROWS, hh = (size_t)m->n_heads * m->head_dim;
+      xg = imax64(xg, (2 * L + 1) * 2 * R8 * m->d_model);
+      ssq = imax64(ssq, (2 * L + 1) * R8 * (m->d_model / 16 + 1));
+      xa = imax64(xa, L * 2 * R8 * hh);
+      xf = imax64(xf, L * 2 * R8 * m->d_ffn);
+      q = imax64(q, L * R8 * hh);
+      items = imax(items, 12 * m->n_heads + 64);
     }
-    c->pass_act = k.take<bf16_t>(need);
-  }
-#ifdef MTAD_PASS_PROFILE
-  c->prof = k.take<unsigned long long>(1024 * 3 * 32);
+    c->flow_xg = k.take<bf16_t>(xg);
+    c->flow_ssq = k.take<float>(ssq);
+    c->flow_xattn = k.take<bf16_t>(xa);
+    c->flow_xffn = k.take<bf16_t>(xf);
+    c->flow_q = k.take<float>(q);
+    c->flow_sync_n = flow_sync_ints(items);
+    c->flow_sync = k.take<int>((size_t)c->flow_sync_n);
+    c->flow_args = k.take<FlowArgs>(1);
+#ifdef MTAD_FLOW_PROFILE
+    c->flow_prof = k.take<unsigned long long>((size_t)4 * 100000);
 #endif
+  }
   c->qkv = k.take<float>(rows * qkv);
   c->gu = k.take<float>(rows * 2 * fmax);
   c->dlogits = k.take<float>((size_t)c->cfg.batch * c->draft_rows * d.vocab);
@@ -246,6 +254,73 @@ int decoder_pass_f32(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R,
   return MTAD_OK;
 }
 
+// bf16 passes of at most FLOW_MAX_ROWS rows: the row inputs (embedding, rotary table), then every product and the attention
+// of every layer and the lm_head as work units of one launch (kernels_flow.hip), then the row logsumexps.  Passes whose
+// attention items hold more than 16 (query head, row) pairs (grouped-query models at several rows) run the attention of
+// each layer as its own kernels between launches that cover the steps from one attention to the next.
+int flow_pass(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R, hipStream_t s, float* logits, float* lse) {
+  const int B = c->cfg.batch, rows = B * R, L = m->n_layers;
+  const int d = m->d_model, f = m->d_ffn, H = m->n_heads, KVH = m->n_kv_heads, hd = m->head_dim;
+  const int hhd = H * hd, qkvw = (H + 2 * KVH) * hd;
+  const KvView kvv = view_of(kv, m);
+  const void* const* W = m->weights;
+  const int ncg = rows < 2 ? 0 : 1;
+  c->pass_ncg = ncg;
+  FlowArgs fa;
+  memset(&fa, 0, sizeof(fa));
+  memcpy(fa.w, W, sizeof(void*) * (size_t)(3 + 6 * L));
+  fa.n_layers = L; fa.d = d; fa.f = f; fa.H = H; fa.KVH = KVH; fa.hd = hd; fa.vocab = m->vocab;
+  fa.eps = m->rms_eps;
+  fa.rows = rows; fa.Rseq = R; fa.B = B; fa.ncg = ncg;
+  fa.kv = kvv; fa.rd = c->rd;
+  fa.h = c->h;
+  fa.xg = c->flow_xg; fa.ssq = c->flow_ssq; fa.xattn = c->flow_xattn; fa.xffn = c->flow_xffn; fa.q = c->flow_q;
+  const size_t R8 = FLOW_MAX_ROWS;
+  fa.xg_stride = 2 * R8 * d; fa.ssq_stride = R8 * (size_t)(d / 16 + 1); fa.xattn_stride = 2 * R8 * hhd; fa.xffn_stride = 2 * R8 * f;
+  fa.q_stride = R8 * hhd;
+  fa.partial = c->partial; fa.rope = c->rope;
+  fa.logits = logits; fa.lse_part = c->lse_part;
+  fa.status = c->status; fa.sync = c->flow_sync;
+#ifdef MTAD_FLOW_PROFILE
+  fa.prof = same_shape(m, &c->tshape) ? c->flow_prof : nullptr;  // the target's passes
+#endif
+  const int n_cus = c->n_cus > 0 ? c->n_cus : 256;
+  const int widths[6] = {qkvw, 0, d, 2 * f, d, m->vocab};
+  for (int k = 0; k < 6; ++k) {
+    if (k == FK_ATTN) continue;
+    const int NT = widths[k] / 16;
+    // three strips per unit share the activation fragments where the product has at least two strips per compute unit
+    fa.strips[k] = (rows >= 4 && NT >= 2 * n_cus) ? 3 : 1;
+    fa.units[k] = (NT + fa.strips[k] - 1) / fa.strips[k];
+  }
+  const int G = H / KVH;
+  const bool attn_in = G * R <= 16;  // one row group per attention item
+  fa.attn_chunks = (G * R + 15) / 16;
+  fa.n_splits = imin(32, (c->cfg.max_context + 127) / 128);
+  if (attn_in) {
+    flow_attention_plan(KVH, fa.attn_chunks, B, fa.n_splits, &fa.attn_gx, &fa.attn_want);
+    fa.units[FK_ATTN] = fa.attn_gx * KVH * fa.attn_chunks * B;
+    if (B * KVH * fa.attn_chunks > c->flow_sync_n - flow_sync_ints(0)) return MTAD_ECAP;
+  }
+  const int s_last = 5 * L + (logits ? 1 : 0);
+  HIP_TRY(c, launch_flow_setup(fa, c->flow_args, c->flow_sync, c->flow_sync_n, s));
+  HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->flow_xg, c->flow_ssq, c->rd.pos, c->rope, hd,
+                          m->rope_theta, ncg, s));
+  if (attn_in) {
+    HIP_TRY(c, launch_flow(fa, c->flow_args, 0, s_last, s));
+  } else {
+    int s0 = 0;
+    for (int l = 0; l < L; ++l) {
+      HIP_TRY(c, launch_flow(fa, c->flow_args, s0, 5 * l + 1, s));  // up to this layer's QKV product
+      HIP_TRY(c, launch_attention_mfma(c->flow_q + (size_t)l * fa.q_stride, hhd, c->rd, kvv, l, B, R, H, c->partial, fa.n_splits,
+                                       c->flow_xattn + (size_t)l * fa.xattn_stride, ncg, s));
+      s0 = 5 * l + 2;
+    }
+    HIP_TRY(c, launch_flow(fa, c->flow_args, s0, s_last, s));
+  }
+  return logits ? finish_lse(c, m, rows, logits, lse, s) : MTAD_OK;
+}
+
 // bf16 models: five kernels per layer.  Every element-wise step rides on a product's epilogue:
 //   qkv product   (rows scaled by the fused RMSNorm factor) -> rotary, q to a buffer, k/v to the cache
 //   attention     -> planes of the attention output
@@ -261,47 +336,15 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const int tag = same_shape(m, &c->tshape) ? 1 : 0;
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
-  const bool persistent = c->persistent && c->n_cus > 0 && pass_supported(rows, m->n_layers);
+  if (c->flow_on && rows <= FLOW_MAX_ROWS && m->n_layers <= FLOW_MAX_LAYERS) return flow_pass(c, m, kv, R, s, logits, lse);
   // one kernel per step, 2 rows or more: activations in operand-fragment order (act_offset), whole cache lines per
   // fragment, without the unused row slots up to 24 rows (C3 verify, 5 rows: 3.20 ms on planes, 3.14 ms with 8-row
   // fragments, 2.98 ms with 5-row fragments on the three-strip product kernel; 2 to 4 rows 1 to 3 % faster than on
-  // planes; one row, plain decoding, 1 % slower); the persistent kernel reads planes
-  const int ncg = (persistent || rows < 2) ? 0 : (rows + 7) / 8;
+  // planes; one row, plain decoding, 1 % slower)
+  const int ncg = rows < 2 ? 0 : (rows + 7) / 8;
   c->pass_ncg = ncg;
   HIP_TRY(c, launch_embed(1, W[0], c->rd.tok, c->h, rows, d, m->vocab, (const float*)W[1], c->xg, c->ssq, c->rd.pos, c->rope, hd, m->rope_theta,
                           ncg, s));
-  if (persistent) {  // every layer (and the lm_head) in one launch
-    // step list of this model: built on the host, uploaded when it differs from both cached lists
-    PassStep built[pass_steps(PASS_MAX_LAYERS, true)];
-    const int n_all = pass_steps(m->n_layers, true);
-    pass_build_steps(built, W, m->n_layers, d, f, H, m->n_kv_heads, hd, m->vocab, (const bf16_t*)c->xg, c->pass_act, c->pass_rows);
-    int slot = -1;
-    for (int i = 0; i < 2; ++i)
-      if (c->steps_n[i] == n_all && memcmp(c->steps_host[i], built, sizeof(PassStep) * n_all) == 0) slot = i;
-    if (slot < 0) {
-      slot = c->steps_evict;
-      c->steps_evict ^= 1;
-      HIP_TRY(c, hipStreamSynchronize(s));  // passes that still read the evicted list have finished
-      HIP_TRY(c, hipMemcpy(c->steps_dev[slot], built, sizeof(PassStep) * n_all, hipMemcpyHostToDevice));
-      memcpy(c->steps_host[slot], built, sizeof(PassStep) * n_all);
-      c->steps_n[slot] = n_all;
-    }
-    PassArgs p;
-    memset(&p, 0, sizeof(p));
-    p.steps = c->steps_dev[slot];
-    p.n_steps = pass_steps(m->n_layers, logits != nullptr);
-    p.d = d; p.f = f; p.H = H; p.KVH = m->n_kv_heads; p.hd = hd; p.vocab = m->vocab;
-    p.rows = rows; p.Rseq = R; p.B = B; p.n_splits = n_splits; p.eps = m->rms_eps;
-    p.kv = kvv; p.rd = c->rd; p.h = c->h; p.ssq = c->ssq; p.q = c->qkv;
-    p.rope = c->rope; p.partial = c->partial; p.attn_cnt = c->attn_cnt; p.logits = logits; p.lse_part = c->lse_part;
-    p.status = c->status; p.bar = c->bar;
-#ifdef MTAD_PASS_PROFILE
-    p.prof = c->prof;
-#endif
-    HIP_TRY(c, launch_pass(p, c->pass_args, c->n_cus, s));
-    if (logits) return finish_lse(c, m, rows, logits, lse, s);
-    return MTAD_OK;
-  }
   int np = 1;  // partial sums of squares per row currently in ctx->ssq
   for (int l = 0; l < m->n_layers; ++l) {
     const void* const* L = W + 1 + 6 * l;
@@ -312,6 +355,8 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
     a.eps = m->rms_eps;
     a.part = c->gemm_part;
     a.counters = c->gemm_cnt;
+    a.part_floats = c->gemm_part_n;
+    a.counters_n = c->gemm_cnt_n;
     a.xfrag = c->gemm_xfrag;
     a.xfrag_elems = c->gemm_xfrag_n;
     // qkv
@@ -359,7 +404,8 @@ int lm_head(mtad_ctx* c, const mtad_model* m, int rows, float* logits, float* ls
     a.ncg = c->pass_ncg;
     a.ssq = c->ssq; a.NP = m->d_model / 16; a.eps = m->rms_eps;
     a.Y = logits; a.ldy = m->vocab; a.lse_part = c->lse_part;
-    a.part = c->gemm_part; a.counters = c->gemm_cnt; a.xfrag = c->gemm_xfrag; a.xfrag_elems = c->gemm_xfrag_n;
+    a.part = c->gemm_part; a.counters = c->gemm_cnt; a.part_floats = c->gemm_part_n; a.counters_n = c->gemm_cnt_n;
+    a.xfrag = c->gemm_xfrag; a.xfrag_elems = c->gemm_xfrag_n;
     HIP_TRY(c, launch_gemm_bf16(a, EPI_STORE, same_shape(m, &c->tshape) ? 1 : 0, s));
     return finish_lse(c, m, rows, logits, lse, s);
   }
@@ -419,8 +465,8 @@ int mtad_create(mtad_ctx** out, const mtad_config* cfg, const mtad_model* target
     delete c;
     return MTAD_ESHAPE;
   }
-  c->persistent = 0;  // opt-in (mtad_set_persistent) until it is the faster path
-  if (const char* e = getenv("MTAD_PERSISTENT")) c->persistent = atoi(e) != 0;
+  c->flow_on = 1;
+  if (const char* e = getenv("MTAD_FUSED_PASS")) c->flow_on = atoi(e) != 0;
   carve(c, nullptr);
   *out = c;
   return MTAD_OK;
@@ -436,7 +482,6 @@ int mtad_bind_workspace(mtad_ctx* c, void* buf, size_t bytes) {
   if (bytes < c->ws_need) return MTAD_ECAP;
   c->ws = (char*)buf;
   carve(c, c->ws);
-  c->steps_n[0] = c->steps_n[1] = 0;  // the device copies of the step lists live in the workspace
   {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 0;
@@ -603,8 +648,8 @@ int mtad_kv_commit(mtad_ctx* c, mtad_kv* tkv, mtad_kv* dkv, const mtad_tree* tre
 
 // ---- component entry points (include/mtad_kernels.h) ------------------------------------------------------------
 
-#ifdef MTAD_PASS_PROFILE
-extern "C" void* mtad_pass_profile(mtad_ctx* c) { return c ? c->prof : nullptr; }
+#ifdef MTAD_FLOW_PROFILE
+extern "C" void* mtad_flow_profile(mtad_ctx* c) { return c ? c->flow_prof : nullptr; }
 #endif
 
 int mtad_set_warp(mtad_ctx* c, int32_t top_k, float top_p) {
@@ -620,20 +665,10 @@ int mtad_k_warp_rows(float* logits, float* lse, int32_t rows, int32_t vocab, int
   return launch_warp_rows(logits, lse, rows, vocab, top_k, top_p, (hipStream_t)stream) == hipSuccess ? MTAD_OK : MTAD_EHIP;
 }
 
-int mtad_set_persistent(mtad_ctx* c, int32_t on) {
+int mtad_set_fused_pass(mtad_ctx* c, int32_t on) {
   if (!c) return MTAD_EINVAL;
-  c->persistent = on != 0;
+  c->flow_on = on != 0;
   return MTAD_OK;
-}
-
-static size_t gemm_split_floats_cap(const mtad_ctx* c) {
-  size_t pf = 0;
-  for (const mtad_model* m : {&c->tshape, &c->dshape}) {
-    if (m->dtype != 1) continue;
-    for (int N : {(m->n_heads + 2 * m->n_kv_heads) * m->head_dim, m->d_model, 2 * m->d_ffn, m->vocab, m->n_heads * m->head_dim})
-      if (gemm_split_floats(N) > pf) pf = gemm_split_floats(N);
-  }
-  return pf;
 }
 
 int mtad_k_gemm(mtad_ctx* c, int32_t dtype, const void* W, const void* X, float* Y, int32_t R, int32_t N, int32_t K, int32_t ldy, int32_t accumulate,
@@ -655,9 +690,11 @@ int mtad_k_gemm_x(mtad_ctx* c, int32_t dtype, const void* W, const void* X, floa
   a.W = (const bf16_t*)W; a.X = (const bf16_t*)X; a.R = R; a.N = N; a.K = K;
   a.Y = Y; a.ldy = ldy; a.accumulate = accumulate != 0;
   a.ncg = x_order == MTAD_X_FRAGMENTS ? (R + 7) / 8 : 0;
-  if (c && c->ws && gemm_split_floats(N) > 0 && gemm_split_floats(N) <= gemm_split_floats_cap(c)) {  // k split needs the workspace
+  if (c && c->ws) {  // a cut of the reduction dimension needs the workspace; the launchers check that the product fits it
     a.part = c->gemm_part;
     a.counters = c->gemm_cnt;
+    a.part_floats = c->gemm_part_n;
+    a.counters_n = c->gemm_cnt_n;
   }
   if (c && c->ws && gemm_tiled_xfrag_elems(R, K) <= c->gemm_xfrag_n) {  // the many-row kernel needs its scratch
     a.xfrag = c->gemm_xfrag;

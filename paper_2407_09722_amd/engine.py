@@ -92,7 +92,7 @@ class Engine:
     """One (target, draft) pair, one batch: buffers + the per-iteration call sequence."""
 
     def __init__(self, target: DeviceModel, draft: DeviceModel, *, batch, gamma, beam, mode, max_context,
-                 prefill_rows=64, page_size=16, device="cuda:0", kv_seed=0, persistent=None, warp=None):
+                 prefill_rows=64, page_size=16, device="cuda:0", kv_seed=0, fused_pass=None, warp=None):
         self.target, self.draft = target, draft
         self.B, self.gamma, self.beam = batch, gamma, beam
         self.mode = mb.MTAD_MODE_MTAD if mode in ("mtad", 0) else mb.MTAD_MODE_MMTAD
@@ -103,8 +103,8 @@ class Engine:
         self.ctx = mb.mtad_create(cfg, target.desc, draft.desc)
         self.workspace = torch.empty(mb.mtad_workspace_bytes(self.ctx), dtype=torch.uint8, device=device)
         mb.mtad_bind_workspace(self.ctx, self.workspace)
-        if persistent is not None:
-            mb.mtad_set_persistent(self.ctx, persistent)
+        if fused_pass is not None:                          # False: one kernel per step also for passes of at most 8 rows
+            mb.mtad_set_fused_pass(self.ctx, fused_pass)
         if warp is not None:                                # (top_k, top_p): both models' distributions are warped
             mb.mtad_set_warp(self.ctx, warp[0], warp[1])
         self.tkv = DeviceKV(target.shape, batch, max_context, page_size, device, seed=kv_seed)
@@ -226,7 +226,7 @@ class Engine:
         stream).  Everything that changes from one iteration to the next (lengths, root and catch-up tokens,
         beam history, the positions that key the random numbers) lives in device memory, and the calls allocate
         nothing, synchronise nothing and record no memset, so the same graph serves every iteration.  tau, seed and
-        the two sampling switches are baked in.  Not for the persistent pass (its first launch uploads a step list)."""
+        the two sampling switches are baked in."""
         side = torch.cuda.Stream(device=self.device)
         side.wait_stream(torch.cuda.current_stream(self.device))
         graph = torch.cuda.CUDAGraph()

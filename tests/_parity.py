@@ -32,7 +32,7 @@ def close(got, want, dtype, what=""):
 
 def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, tau, sample_bonus=True,
              sample_beam=False, seed=0, max_context=None, page_size=16, prefill_rows=64, check_kv=False,
-             max_iters=None, device="cuda:0", persistent=None, warp=None, method="mtad"):
+             max_iters=None, device="cuda:0", fused_pass=None, warp=None, method="mtad"):
     """method "spd": vanilla speculative decoding (beam 1, chain, token-wise acceptance) instead of the joint rule."""
     from paper_2407_09722_amd.engine import DeviceModel, Engine
     prompt = np.asarray(prompt, np.int32)
@@ -41,7 +41,7 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
     M = 1 + (gamma if mode == "mtad" else gamma * beam)
     max_context = max_context or (n0 + new_tokens + 2 * (gamma + 1) + M + 8)
     eng = Engine(DeviceModel(tshape, wt, device), DeviceModel(dshape, wd, device), batch=B, gamma=gamma, beam=beam,
-                 mode=mode, max_context=max_context, prefill_rows=prefill_rows, page_size=page_size, device=device, persistent=persistent,
+                 mode=mode, max_context=max_context, prefill_rows=prefill_rows, page_size=page_size, device=device, fused_pass=fused_pass,
                  warp=warp)
     lm_p, lm_q = DecoderLM(tshape, wt), DecoderLM(dshape, wd)
     sp = [CachedSession(lm_p, list(prompt[s])) for s in range(B)]

@@ -42,13 +42,13 @@ def test_small_pairs_every_iteration_matches(kind, mode, tau):
         assert all(e == 4 for e in st["eta"])          # tau = 0 passes every prefix: commit / gather path
 
 
-@pytest.mark.parametrize("persistent", [True, False])
-def test_both_pass_implementations(persistent):
-    """bf16 passes run either as one persistent kernel or as one kernel per product: same results to tolerance."""
+@pytest.mark.parametrize("fused_pass", [True, False])
+def test_both_pass_implementations(fused_pass):
+    """bf16 passes of at most 8 rows run either as one launch or as one kernel per step: same results to tolerance."""
     ts, ds = SMALL["bf16_hd128"]
     wt, wd = _weights(ts, 13, "target", boost=4.0), _weights(ds, 13, "draft", boost=4.0)
     prompt = np.random.default_rng(8).integers(0, ts.vocab, (2, 41)).astype(np.int32)
-    st = run_pair(ts, ds, wt, wd, prompt, 10, gamma=3, beam=3, mode="mmtad", tau=0.0, seed=3, check_kv=True, persistent=persistent)
+    st = run_pair(ts, ds, wt, wd, prompt, 10, gamma=3, beam=3, mode="mmtad", tau=0.0, seed=3, check_kv=True, fused_pass=fused_pass)
     assert st["excused"] == 0
 
 
@@ -111,13 +111,13 @@ def test_graph_replay_matches_eager_iterations():
     n_iter = 7
     for mode, tau in (("mtad", 0.0), ("mmtad", 0.3)):
         print(f"graph replay {mode} tau={tau}", flush=True)
-        eager = Engine(tm, dm, batch=2, gamma=3, beam=3, mode=mode, max_context=128, device=DEV, persistent=False)
+        eager = Engine(tm, dm, batch=2, gamma=3, beam=3, mode=mode, max_context=128, device=DEV, fused_pass=False)
         eager.prefill(prompt)
         want = []
         for _ in range(n_iter):
             eager.iteration(tau, sample_beam=True, seed=9)
             want.append((eager.emitted(), eager.tkv.len.cpu().tolist(), eager.dkv.len.cpu().tolist()))
-        rep = Engine(tm, dm, batch=2, gamma=3, beam=3, mode=mode, max_context=128, device=DEV, persistent=False)
+        rep = Engine(tm, dm, batch=2, gamma=3, beam=3, mode=mode, max_context=128, device=DEV, fused_pass=False)
         rep.prefill(prompt)
         torch.cuda.synchronize()
         graph = rep.capture_iteration(tau, sample_beam=True, seed=9)
