@@ -144,10 +144,11 @@ void mtad_destroy(mtad_ctx *ctx);
  * any hot call.  The contents need no initialisation.  ECAP if too small. */
 size_t mtad_workspace_bytes(const mtad_ctx *ctx);
 int mtad_bind_workspace(mtad_ctx *ctx, void *device_buf, size_t bytes);
-/* bf16 passes of at most 8 rows (all sequences together) run every product and the attention of every layer as work units
- * of ONE kernel launch, handed out in dependency order (on != 0, the default), or as one kernel per step (on == 0: same
- * arithmetic; the form every larger pass takes).  Waits inside the one-launch pass are bounded: one that gives up sets
- * status bit 3 and the pass runs to its end.  The environment variable MTAD_FUSED_PASS=0 turns it off at context creation. */
+/* bf16 passes of at most 8 rows (all sequences together) can run every product and the attention of every layer as work
+ * units of ONE kernel launch, handed out in dependency order, instead of one kernel per step (same arithmetic; the form every
+ * larger pass takes).  on = 0: never; 1 (the default): for models whose layers hold at least 64 MiB of weights, where
+ * it is the faster form; 2: for every such pass.  Waits inside the one-launch pass are bounded: one that gives up sets status
+ * bit 3 and the pass runs to its end.  The environment variable MTAD_FUSED_PASS=0|1|2 sets the same at context creation. */
 int mtad_set_fused_pass(mtad_ctx *ctx, int32_t on);
 /* Warped distributions (appendix "Hyper-parameter Details"; the footnote of Section 3.2 allows approximating p~ with
  * q~): with top_k > 0 every next-token distribution of both models is warped before it is used: the top_k most likely

@@ -43,7 +43,8 @@ struct mtad_ctx {
   RowDesc rd;
   uint32_t* status;
   int n_cus;                // compute units of the device
-  // one-launch pass (kernels_flow.hip) for bf16 passes of at most FLOW_MAX_ROWS rows: on by default
+  // one-launch pass (kernels_flow.hip) for bf16 passes of at most FLOW_MAX_ROWS rows: 0 never, 1 where a layer's
+  // weights are large enough for the stream to matter (the default), 2 always
   int flow_on;
   bf16_t *flow_xg, *flow_xattn, *flow_xffn;  // per-step versions of the activation terms (see flow.h)
   float *flow_ssq, *flow_q;
@@ -336,7 +337,13 @@ int decoder_pass_bf16(mtad_ctx* c, const mtad_model* m, const mtad_kv* kv, int R
   const int tag = same_shape(m, &c->tshape) ? 1 : 0;
   const void* const* W = m->weights;
   const int tail = 1 + 6 * m->n_layers;
-  if (c->flow_on && rows <= FLOW_MAX_ROWS && m->n_layers <= FLOW_MAX_LAYERS) return flow_pass(c, m, kv, R, s, logits, lse);
+  if (c->flow_on && rows <= FLOW_MAX_ROWS && m->n_layers <= FLOW_MAX_LAYERS) {
+    // Steps hand over through counters and flags in memory, about as dear as a kernel boundary each; what the one launch
+    // gains is the weights requested across those handovers, which counts where a layer streams tens of megabytes
+    // (7B-shaped target, 405 MB per layer: pass 2.78 -> 2.61 ms) and not for small models (two 14 MB layers: 95 -> 106 us).
+    const size_t layer_bytes = 2 * ((size_t)qkvw * d + (size_t)d * H * hd + (size_t)3 * d * f);
+    if (c->flow_on >= 2 || layer_bytes >= ((size_t)64 << 20)) return flow_pass(c, m, kv, R, s, logits, lse);
+  }
   // one kernel per step, 2 rows or more: activations in operand-fragment order (act_offset), whole cache lines per
   // fragment, without the unused row slots up to 24 rows (C3 verify, 5 rows: 3.20 ms on planes, 3.14 ms with 8-row
   // fragments, 2.98 ms with 5-row fragments on the three-strip product kernel; 2 to 4 rows 1 to 3 % faster than on
@@ -466,7 +473,7 @@ int mtad_create(mtad_ctx** out, const mtad_config* cfg, const mtad_model* target
     return MTAD_ESHAPE;
   }
   c->flow_on = 1;
-  if (const char* e = getenv("MTAD_FUSED_PASS")) c->flow_on = atoi(e) != 0;
+  if (const char* e = getenv("MTAD_FUSED_PASS")) c->flow_on = atoi(e) < 0 ? 0 : (atoi(e) > 2 ? 2 : atoi(e));
   carve(c, nullptr);
   *out = c;
   return MTAD_OK;
@@ -666,8 +673,8 @@ int mtad_k_warp_rows(float* logits, float* lse, int32_t rows, int32_t vocab, int
 }
 
 int mtad_set_fused_pass(mtad_ctx* c, int32_t on) {
-  if (!c) return MTAD_EINVAL;
-  c->flow_on = on != 0;
+  if (!c || on < 0 || on > 2) return MTAD_EINVAL;
+  c->flow_on = on;
   return MTAD_OK;
 }
 

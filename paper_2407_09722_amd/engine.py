@@ -103,8 +103,8 @@ class Engine:
         self.ctx = mb.mtad_create(cfg, target.desc, draft.desc)
         self.workspace = torch.empty(mb.mtad_workspace_bytes(self.ctx), dtype=torch.uint8, device=device)
         mb.mtad_bind_workspace(self.ctx, self.workspace)
-        if fused_pass is not None:                          # False: one kernel per step also for passes of at most 8 rows
-            mb.mtad_set_fused_pass(self.ctx, fused_pass)
+        if fused_pass is not None:                          # 0 / False: one kernel per step; 1: one launch for large models; 2: always
+            mb.mtad_set_fused_pass(self.ctx, int(fused_pass))
         if warp is not None:                                # (top_k, top_p): both models' distributions are warped
             mb.mtad_set_warp(self.ctx, warp[0], warp[1])
         self.tkv = DeviceKV(target.shape, batch, max_context, page_size, device, seed=kv_seed)
