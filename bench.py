@@ -139,6 +139,130 @@ def measure_energy(eng, w, tau, prompt, tm, dm, Engine, torch, dev, seconds=3.0)
     return out
 
 
+def layer_weight_bytes(shape):
+    e = 2 if shape.dtype == "bf16" else 4
+    d, f = shape.d_model, shape.d_ffn
+    return (shape.qkv_rows * d + d * shape.n_heads * shape.head_dim + 3 * f * d) * e
+
+
+def pass_kernel_name(w, one_launch):
+    rows = w.batch * w.tree_rows
+    if w.target.dtype != "bf16":
+        return "gemm_f32_kernel (+ attention kernels): one launch per product"
+    if one_launch:
+        return f"flow_pass_kernel<{w.target.head_dim}> (one launch = the whole target pass)"
+    return ("gemm_bf16_strips_kernel / gemm_bf16_kernel" if rows <= 8 else "gemm_bf16_multi_kernel / gemm_bf16_kernel" if rows < 65 else
+            "gemm_bf16_tiled_kernel") + " (+ tree_attn_mfma_kernel): one launch per product"
+
+
+def verify_block(eng, w, K, torch, stream):
+    """One target pass over the tree rows (the verify step), timed with HIP events on the launch stream."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(3):
+        eng.verify_phase()
+    ev[0].record(stream)
+    for _ in range(K):
+        eng.verify_phase()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / K
+    n_ctx = int(eng.tkv.len[0].item())
+    nbytes = weight_bytes(w.target) + w.batch * n_ctx * kv_bytes_per_token(w.target)
+    return ms, nbytes, {"ms": round(ms, 4), "context": n_ctx, "rows": w.batch * w.tree_rows,
+                        "algorithmic_GB": round(nbytes / 1e9, 4), "GBps": round(nbytes / ms / 1e6, 1),
+                        "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)}
+
+
+def workload_block(w, K, W, threads, dev, mb, torch, DeviceModel, Engine):
+    """Compact figures of one workload on its own seeded weights: tokens/s of the whole loop and the verify step."""
+    t0 = time.time()
+    tm = DeviceModel(w.target, lambda n: si.make_tensor(w.target, w.seed, "target", n), dev, threads=threads)
+    dm = DeviceModel(w.draft, lambda n: si.make_tensor(w.draft, w.seed, "draft", n), dev, threads=threads)
+    t_weights = time.time() - t0
+    prompt = si.make_prompt(w)
+    eng = Engine(tm, dm, batch=w.batch, gamma=w.gamma, beam=w.beam, mode=w.mode,
+                 max_context=w.prompt_len + (K + W + 8) * (w.gamma + 1) + w.tree_rows + 64, device=dev)
+    stream = torch.cuda.current_stream()
+    res = {}
+    for key, tau in (("tau", w.tau), ("tau0", 0.0)):
+        eng.prefill(prompt)
+        for _ in range(W):
+            eng.iteration(tau, seed=w.seed)
+        torch.cuda.synchronize()
+        len0 = eng.tkv.len.clone()
+        t = time.perf_counter()
+        for _ in range(K):
+            eng.iteration(tau, seed=w.seed)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t
+        tokens = int((eng.tkv.len - len0).sum().item())
+        res[key] = {"tokens_per_s": round(tokens / dt, 2), "tokens_per_iteration": round(tokens / K / w.batch, 3),
+                    "ms_per_step": round(dt / K * 1e3, 4)}
+    eng.prefill(prompt)
+    eng.draft_phase(seed=w.seed)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record(stream)
+    for _ in range(K):
+        eng.draft_phase(seed=w.seed)
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    draft_ms = ev[0].elapsed_time(ev[1]) / K
+    _, _, verify = verify_block(eng, w, K, torch, stream)
+    one_launch = w.target.dtype == "bf16" and w.batch * w.tree_rows <= 8 and layer_weight_bytes(w.target) >= (64 << 20)
+    out = {"workload": f"{w.mode.upper()} gamma={w.gamma} beam={w.beam} batch={w.batch} prompt={w.prompt_len}, target "
+                       f"L{w.target.n_layers} d{w.target.d_model} {w.target.dtype}, draft L{w.draft.n_layers} d{w.draft.d_model}; seed {w.seed}",
+           "steps": K, "tau": w.tau, "value": res["tau"]["tokens_per_s"], "unit": "tokens/s",
+           "ms_per_step": res["tau"]["ms_per_step"], "tokens_per_iteration": res["tau"]["tokens_per_iteration"],
+           "iterations_per_s": round(1e3 / res["tau"]["ms_per_step"], 2), "tau0": res["tau0"],
+           "draft_phase_ms": round(draft_ms, 4), "verify": verify, "pass_kernels": pass_kernel_name(w, one_launch),
+           "weights_setup_s": round(t_weights, 1), "device_status": mb.mtad_device_status(eng.ctx)}
+    eng.close()
+    del eng, tm, dm
+    torch.cuda.empty_cache()
+    return out
+
+
+def gemm_replay_block(w, tm, eng, rows, dt_id, mb, torch, stream, dev, K):
+    """The products of one target pass launched back to back on zero activations, each by the pass's own kernel choice."""
+    per_layer, head = target_gemm_shapes(w.target)
+    esz = 2 if dt_id else 4
+    kmax = max(k for _, k in per_layer + [head])
+    nmax = max(n for n, _ in per_layer + [head])
+    x_order = mb.MTAD_X_FRAGMENTS if (dt_id and rows >= 2) else mb.MTAD_X_PLANES   # as the kernel-per-step passes keep their activations
+    X = torch.zeros(2 * ((rows + 7) // 8 * 8) * kmax, dtype=torch.int16 if dt_id else torch.float32, device=dev)
+    Y = torch.zeros(rows * nmax, dtype=torch.float32, device=dev)
+    launches = []
+    for l in range(w.target.n_layers):
+        for j, idx in enumerate((1, 2, 4, 5)):
+            n, k = per_layer[j]
+            launches.append((tm.tensors[1 + 6 * l + idx], n, k))
+    launches.append((tm.tensors[-1], head[0], head[1]))
+    gemm_bytes = sum(n * k * esz + rows * k * 4 + rows * n * 4 for _, n, k in launches)
+
+    def replay():
+        for Wt, n, k in launches:
+            mb.mtad_k_gemm(dt_id, Wt, X, Y, rows, n, k, n, False, ctx=eng.ctx, x_order=x_order)
+    replay()
+    reps = max(3, min(20, K // 3))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record(stream)
+    for _ in range(reps):
+        replay()
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    gemm_ms = ev[0].elapsed_time(ev[1]) / (reps * len(launches))
+    bpl = gemm_bytes / len(launches)
+    out = {"kernels": "gemm_f32_kernel" if not dt_id else pass_kernel_name(w, False).split(" (+")[0],
+           "launches": len(launches), "bytes_per_launch": int(bpl), "avg_launch_us": round(gemm_ms * 1e3, 3),
+           "GBps": round(bpl / gemm_ms / 1e6, 1), "frac_of_hbm_peak": round(bpl / gemm_ms / 1e6 / HBM_PEAK_GBS, 4)}
+    tfile = os.path.join(ROOT, "profiles", "c3_gemm_hbm_traffic.txt")
+    if w.name == "C3" and os.path.exists(tfile):
+        kv = dict(l.strip().split("=", 1) for l in open(tfile) if "=" in l and not l.startswith("#"))
+        out["hbm_bytes_per_launch"] = int(float(kv["fetch_bytes_per_launch"])) + int(float(kv["write_bytes_per_launch"]))
+        out["hbm_bytes_source"] = "profiles/c3_gemm_hbm_counters.md"
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -147,11 +271,13 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--tau", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-tree-verify", action="store_true", help="skip the C4-shaped verify-step measurement")
+    ap.add_argument("--others", default=None, help="comma-separated workloads that get a compact block (tokens/s and verify step) "
+                    "beside the main one; default: the other four of C1..C5 when the main workload is C3, else none")
     ap.add_argument("--no-baselines", action="store_true", help="skip plain decoding and vanilla speculative decoding")
+    ap.add_argument("--no-gemm-replay", action="store_true", help="skip the back-to-back replay of the product kernels")
     ap.add_argument("--no-energy", action="store_true", help="skip the board-power measurement (about 10 s)")
-    ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: time and energy of one target pass at each "
-                    "(Section 4's observation that a run costs about the same for any small batch); not part of the default run")
+    ap.add_argument("--batch-sweep", default="1,2,4", help="comma-separated batch sizes: time and energy of one target pass at each "
+                    "(Section 4's observation that a run costs about the same for any small batch); '' skips it")
     ap.add_argument("--gamma-beam-sweep", default="", help="'g1,g2,..xb1,b2,..': time of one iteration at each draft length gamma and beam "
                     "width (the axes of the paper's ablation, Section 5.3); not part of the default run")
     args = ap.parse_args()
@@ -242,96 +368,43 @@ def main():
     eng.prefill(prompt)
     eng.draft_phase(seed=w.seed)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    for _ in range(3):
-        eng.verify_phase()
-    ev[0].record(stream)
-    for _ in range(K):
-        eng.verify_phase()
-    ev[1].record(stream)
-    torch.cuda.synchronize()
-    verify_ms = ev[0].elapsed_time(ev[1]) / K
-    n_ctx = int(eng.tkv.len[0].item())
-    verify_bytes = weight_bytes(w.target) + w.batch * n_ctx * kv_bytes_per_token(w.target)
-    verify = {"ms": round(verify_ms, 4), "context": n_ctx, "rows": w.batch * M,
-              "algorithmic_GB": round(verify_bytes / 1e9, 4),
-              "GBps": round(verify_bytes / verify_ms / 1e6, 1),
-              "frac_of_hbm_peak": round(verify_bytes / verify_ms / 1e6 / HBM_PEAK_GBS, 4)}
+    verify_ms, verify_bytes, verify = verify_block(eng, w, K, torch, stream)
 
-    # --- dominant kernel: the skinny GEMM over the target's weight matrices, launched back to back -----------
+    # --- roofline of the dominant kernel, in the pass: for bf16 passes of at most 8 rows over layers of at least 64 MiB the
+    #     whole target pass is ONE launch (flow_pass_kernel: every product and the attention of all layers), so bytes per launch
+    #     = the verify step's algorithmic bytes and the launch's duration = the verify step's (HIP events on the launch stream;
+    #     the interval also holds the embedding and log-sum-exp kernels of the pass, a few microseconds)
     rows = w.batch * M
-    per_layer, head = target_gemm_shapes(w.target)
-    esz = 2 if w.target.dtype == "bf16" else 4
     dt_id = 1 if w.target.dtype == "bf16" else 0
-    kmax = max(k for _, k in per_layer + [head])
-    nmax = max(n for n, _ in per_layer + [head])
-    x_order = mb.MTAD_X_FRAGMENTS if (dt_id and rows >= 2) else mb.MTAD_X_PLANES   # as the kernel-per-step passes keep their activations
-    X = torch.zeros(2 * ((rows + 7) // 8 * 8) * kmax, dtype=torch.int16 if dt_id else torch.float32, device=dev)
-    Y = torch.zeros(rows * nmax, dtype=torch.float32, device=dev)
-    launches = []
-    for l in range(w.target.n_layers):
-        for j, idx in enumerate((1, 2, 4, 5)):
-            n, k = per_layer[j]
-            launches.append((tm.tensors[1 + 6 * l + idx], n, k))
-    launches.append((tm.tensors[-1], head[0], head[1]))
-    gemm_bytes = sum(n * k * esz + rows * k * (4 if dt_id else 4) + rows * n * 4 for _, n, k in launches)
-
-    def replay():
-        for Wt, n, k in launches:
-            mb.mtad_k_gemm(dt_id, Wt, X, Y, rows, n, k, n, False, ctx=eng.ctx, x_order=x_order)   # the pass's own kernel choice and layout
-    replay()
-    reps = max(3, min(20, K // 3))
-    ev[0].record(stream)
-    for _ in range(reps):
-        replay()
-    ev[1].record(stream)
-    torch.cuda.synchronize()
-    gemm_ms = ev[0].elapsed_time(ev[1]) / (reps * len(launches))
-    bytes_per_launch = gemm_bytes / len(launches)
-    achieved = bytes_per_launch / gemm_ms / 1e6
+    one_launch = bool(dt_id) and rows <= 8 and layer_weight_bytes(w.target) >= (64 << 20)
     traffic, traffic_detail = None, None
-    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "c3_gemm_hbm_traffic.txt")
-    if w.name == "C3" and os.path.exists(tfile):       # per-launch HBM bytes from the committed rocprofv3 counter runs
+    tfile = os.path.join(ROOT, "profiles", f"{w.name.lower()}_verify_hbm_traffic.txt")
+    if os.path.exists(tfile):                          # per-pass HBM bytes from the committed rocprofv3 counter runs
         kv = dict(l.strip().split("=", 1) for l in open(tfile) if "=" in l and not l.startswith("#"))
         traffic_detail = {"fetch_bytes_per_launch": int(float(kv["fetch_bytes_per_launch"])),
                           "write_bytes_per_launch": int(float(kv["write_bytes_per_launch"])),
-                          "source": "profiles/c3_gemm_hbm_counters.md (rocprofv3 FETCH_SIZE / WRITE_SIZE, scaled by the copy kernel)"}
-        traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]   # HBM bytes per launch
-    kname = "gemm_f32_kernel"
-    if dt_id:
-        kname = ("gemm_bf16_strips_kernel / gemm_bf16_kernel (the weight-streaming products of all target matrices: three strips per workgroup "
-                 "where the product has at least two strips per compute unit, else one)" if rows <= 8 else
-                 "gemm_bf16_multi_kernel / gemm_bf16_kernel (several strips per workgroup)" if rows < 65 else
-                 "gemm_bf16_tiled_kernel (operands staged through LDS)")
-    roofline = {"kernel": kname,
-                "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_detail": traffic_detail,
-                "bytes_per_launch": int(bytes_per_launch), "avg_launch_us": round(gemm_ms * 1e3, 3),
-                "launches_per_verify": len(launches)}
+                          "source": kv.get("source", "profiles/")}
+        traffic = traffic_detail["fetch_bytes_per_launch"] + traffic_detail["write_bytes_per_launch"]
+    roofline = {"kernel": pass_kernel_name(w, one_launch),
+                "bound": "hbm", "achieved": verify["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": verify["frac_of_hbm_peak"], "traffic": traffic, "traffic_detail": traffic_detail,
+                "bytes_per_launch": int(verify_bytes), "avg_launch_us": round(verify_ms * 1e3, 2),
+                "launches_per_verify": 1 if one_launch else None,
+                "scope": "in the pass: all bytes of one target pass (weights once, the KV cache of the context once) over the pass's "
+                         "duration" + ("" if one_launch else "; the pass is a sequence of kernels, the figure is their total")}
 
-    # --- the same target at the MMTAD shape of C4 (17 tree rows, context 2048): verify step only ------------------
-    verify_tree = None
-    if w.name == "C3" and not args.no_tree_verify:
-        w4 = si.WORKLOADS["C4"]
-        eng4 = Engine(tm, dm, batch=1, gamma=w4.gamma, beam=w4.beam, mode=w4.mode, max_context=w4.prompt_len + 128, device=dev)
-        eng4.prefill(si.make_prompt(w4))
-        eng4.draft_phase(seed=w4.seed)
-        for _ in range(2):
-            eng4.verify_phase()
-        k4 = max(5, K // 4)
-        ev[0].record(stream)
-        for _ in range(k4):
-            eng4.verify_phase()
-        ev[1].record(stream)
-        torch.cuda.synchronize()
-        ms4 = ev[0].elapsed_time(ev[1]) / k4
-        n4 = int(eng4.tkv.len[0].item())
-        b4 = weight_bytes(w.target) + n4 * kv_bytes_per_token(w.target)
-        status |= mb.mtad_device_status(eng4.ctx)
-        verify_tree = {"workload": "C4 shape (MMTAD, 16 nodes + root, prompt 2048) on this target's weights", "ms": round(ms4, 4),
-                       "context": n4, "rows": w4.tree_rows, "algorithmic_GB": round(b4 / 1e9, 4), "GBps": round(b4 / ms4 / 1e6, 1),
-                       "frac_of_hbm_peak": round(b4 / ms4 / 1e6 / HBM_PEAK_GBS, 4)}
-        eng4.close()
-        del eng4
+    # --- extra: the weight-streaming product kernels alone, launched back to back outside a pass (upper bound of what the pass
+    #     can reach: no dependencies between launches, activations zero) ----------------------------------------------------
+    gemm_replay = None
+    if not args.no_gemm_replay:
+        gemm_replay = gemm_replay_block(w, tm, eng, rows, dt_id, mb, torch, stream, dev, K)
+
+    # --- the other workloads: tokens/s and verify step of each, on its own weights -------------------------------------------
+    others = {}
+    names = args.others.split(",") if args.others is not None else ([n for n in si.WORKLOADS if n != w.name] if w.name == "C3" else [])
+    for name in [n for n in names if n]:
+        others[name] = workload_block(si.WORKLOADS[name], min(K, 20), min(W, 3), threads, dev, mb, torch, DeviceModel, Engine)
+        status |= others[name].pop("device_status")
 
     # --- plain copy of known size: reference for byte counters and for the bandwidth coalesced traffic reaches -----
     cbytes = 1 << 30
@@ -428,7 +501,7 @@ def main():
             for _ in range(3):
                 eb.verify_phase()
             torch.cuda.synchronize()
-            n_it = max(50, int(2.0 / (verify_ms * 1e-3)))
+            n_it = max(50, int(1.0 / (verify_ms * 1e-3)))
             with PowerSampler() as ps:
                 for _ in range(n_it):
                     eb.verify_phase()
@@ -491,7 +564,7 @@ def main():
                                "block-efficiency table): a labelled projection, not a measurement"},
         "tau0": {"tokens_per_s": round(tokens0 / dt0, 2), "tokens_per_iteration": round(tokens0 / K / w.batch, 3),
                  "ms_per_step": round(dt0 / K * 1e3, 4)},
-        "warped": warped, "baselines": baselines, "energy": energy, "batch_sweep": batch_sweep, "gamma_beam_sweep": gb_sweep, "graph_replay": graph_info, "verify": verify, "verify_tree": verify_tree, "roofline": roofline, "copy_reference": copy_ref, "cpu_baseline": cpu,
+        "warped": warped, "baselines": baselines, "energy": energy, "batch_sweep": batch_sweep, "gamma_beam_sweep": gb_sweep, "graph_replay": graph_info, "verify": verify, "roofline": roofline, "gemm_replay": gemm_replay, "workloads": others, "copy_reference": copy_ref, "cpu_baseline": cpu,
         "device_status": status, "weights_setup_s": round(t_weights, 1),
     }
     print(json.dumps(out))
