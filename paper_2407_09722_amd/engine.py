@@ -167,6 +167,18 @@ class Engine:
         self.catchup_tok.copy_(_dev(cu, self.device))
         self.catchup_cnt.copy_(_dev(np.asarray(cnt, np.int32), self.device))
 
+    def resync(self, target_len, draft_len, target_tokens, draft_tokens, root, catchup, cnt):
+        """Puts the caches and the state on a host-provided context (lock-step tests): the cache lengths are set to
+        target_len / draft_len, then target_tokens / draft_tokens ([B, n], the same n for every sequence) are appended
+        through the prefill path, then the state is set."""
+        self.tkv.len.copy_(_dev(np.asarray(target_len, np.int32), self.device))
+        self.dkv.len.copy_(_dev(np.asarray(draft_len, np.int32), self.device))
+        for model, kv, toks in ((self.target, self.tkv, target_tokens), (self.draft, self.dkv, draft_tokens)):
+            toks = np.ascontiguousarray(toks, dtype=np.int32).reshape(self.B, -1)
+            if toks.shape[1]:
+                mb.mtad_prefill(self.ctx, model.desc, kv.desc, _dev(toks, self.device), toks.shape[1], None)
+        self.set_state(root, catchup, cnt)
+
     # -- one iteration (Algorithm 1 / Section 3.3), enqueue only ---------------------------------
     def draft_phase(self, sample_beam=False, seed=0, stream=None):
         for step in range(self.gamma):

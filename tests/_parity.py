@@ -32,8 +32,13 @@ def close(got, want, dtype, what=""):
 
 def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, tau, sample_bonus=True,
              sample_beam=False, seed=0, max_context=None, page_size=16, prefill_rows=64, check_kv=False,
-             max_iters=None, device="cuda:0", fused_pass=None, warp=None, method="mtad"):
-    """method "spd": vanilla speculative decoding (beam 1, chain, token-wise acceptance) instead of the joint rule."""
+             max_iters=None, device="cuda:0", fused_pass=None, warp=None, method="mtad", lockstep=False, oracle_seqs=None):
+    """method "spd": vanilla speculative decoding (beam 1, chain, token-wise acceptance) instead of the joint rule.
+    oracle_seqs: the sequences compared with the oracle (default all).  The others must then carry the prompt of
+    oracle_seqs[0] and a deterministic run (no sampling): their trees and logits are checked against that sequence's.
+    lockstep (one sequence): where the runs part on an excused near-tie, the HIP side is put back on the oracle's context
+    (cache lengths reset to the iteration's start, the oracle's tokens appended, its state set) and the comparison goes
+    on, so every iteration of the run is compared up to the first decision that legitimately differs."""
     from paper_2407_09722_amd.engine import DeviceModel, Engine
     prompt = np.asarray(prompt, np.int32)
     B, n0 = prompt.shape
@@ -46,12 +51,29 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
     lm_p, lm_q = DecoderLM(tshape, wt), DecoderLM(dshape, wd)
     sp = [CachedSession(lm_p, list(prompt[s])) for s in range(B)]
     sq = [CachedSession(lm_q, list(prompt[s])) for s in range(B)]
+    oracle_seqs = list(range(B)) if oracle_seqs is None else list(oracle_seqs)
+    if len(oracle_seqs) < B:
+        assert not sample_beam and not sample_bonus and method == "mtad" and all(np.array_equal(prompt[s], prompt[oracle_seqs[0]]) for s in range(B))
     eng.prefill(prompt)
     stats = {"iters": 0, "excused": 0, "max_logit_err": 0.0, "eta": [], "tokens": [[] for _ in range(B)], "events": []}
     _, atol = logit_tolerance(dtype)
     margin_tol = max(atol, 1e-4) * 2
-    alive = [True] * B
+    alive = [s in oracle_seqs for s in range(B)]
+    assert not lockstep or B == 1, "lock-step appends the same number of tokens to every sequence: one sequence only"
+    stats["resyncs"] = 0
+
+    def parted(s, tr):
+        stats["excused"] += 1
+        if lockstep:
+            resync.append(s)
+            stats["tokens"][s] += tr["emitted"]
+        else:
+            alive[s] = False
+
     while min(len(t) for t in stats["tokens"]) < new_tokens and (max_iters is None or stats["iters"] < max_iters):
+        resync = []
+        t_before = [len(x.context) - 1 for x in sp]
+        d_before = [x.n_cached for x in sq]
         eng.draft_phase(sample_beam or method == "spd", seed)
         eng.verify_phase()
         if method == "spd":
@@ -67,6 +89,13 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
         post = {k: getattr(eng, k).cpu().numpy() for k in ("root_tok", "catchup_tok", "catchup_cnt")}
         tlen, dlen = eng.tkv.len.cpu().numpy(), eng.dkv.len.cpu().numpy()
         for s in range(B):
+            if s not in oracle_seqs:                   # a copy of the reference sequence: same tree, same logits, same decision
+                r0 = oracle_seqs[0]
+                for k in ("t_tok", "t_parent", "t_mask", "eta", "bonus_tok", "out_cnt"):
+                    assert np.array_equal(g[k][s], g[k][r0]), f"sequence {s} differs from its copy {r0} in {k}"
+                close(g["logits"][s], g["logits"][r0], dtype, f"logits of sequence {s} against its copy {r0}")
+                stats["tokens"][s] += [int(t) for t in g["out_tok"][s, :g["out_cnt"][s]]]
+                continue
             if not alive[s]:
                 continue
             if method == "spd":
@@ -76,19 +105,20 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
                                     sample_bonus=sample_bonus, seed=seed, seq_index=s, dt=np.float32, warp=warp)
             h = tr["hist"]
             # --- draft: beam history
+            beams_differ = False
             for i in range(gamma):
                 same = np.array_equal(g["h_tok"][s, i], h["tok"][i]) and np.array_equal(g["h_parent"][s, i], h["parent"][i])
                 if not same:
                     assert h["margin"][i] < margin_tol or _near_tie(h["score"][i], margin_tol) or h["warp_margin"][i] < margin_tol, \
                         f"seq {s} iter {stats['iters']} beam step {i}: survivors differ, margin {h['margin'][i]}"
-                    alive[s] = False
+                    beams_differ = True
                     with np.errstate(invalid="ignore"):
                         diff = np.nanmax(np.abs(np.sort(g["h_cum"][s, i].astype(np.float64)) - np.sort(h["score"][i].astype(np.float64))))
                     stats["events"].append(("beam step", stats["iters"], i, float(h["margin"][i]), float(diff)))
                     break
                 close(g["h_cum"][s, i], h["score"][i], dtype, f"cum_logq step {i}")
-            if not alive[s]:
-                stats["excused"] += 1
+            if beams_differ:
+                parted(s, tr)
                 continue
             # --- tree
             t = tr["tree"]
@@ -102,8 +132,7 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
                 # a warped support differs: only where a top-k or top-p decision sits on its threshold
                 assert v["warp_margin"] < margin_tol, f"warped supports differ with margin {v['warp_margin']}"
                 stats["events"].append(("warp support", stats["iters"], float(v["warp_margin"])))
-                alive[s] = False
-                stats["excused"] += 1
+                parted(s, tr)
                 continue
             stats["max_logit_err"] = max(stats["max_logit_err"], close(g["logits"][s], v["logits"], dtype, "target logits"))
             close(g["row_lse"][s], v["lse"], dtype, "row lse")
@@ -112,15 +141,13 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
             if g["eta"][s] != tr["eta"] or g["bonus_row"][s] != tr["node"]:
                 assert min(tr["accept_margins"]) < margin_tol * gamma, f"accept differs: {g['eta'][s]} vs {tr['eta']}"
                 stats["events"].append(("accept", stats["iters"], float(min(tr["accept_margins"]))))
-                alive[s] = False
-                stats["excused"] += 1
+                parted(s, tr)
                 continue
             assert list(g["path"][s, :tr["eta"]]) == tr["path_rows"] and np.all(g["path"][s, tr["eta"]:] == -1)
             if g["bonus_tok"][s] != tr["bonus"]:
                 assert tr["bonus_gap"] < margin_tol, f"bonus token differs with gap {tr['bonus_gap']}"
                 stats["events"].append(("bonus", stats["iters"], float(tr["bonus_gap"])))
-                alive[s] = False
-                stats["excused"] += 1
+                parted(s, tr)
                 continue
             assert g["out_cnt"][s] == tr["eta"] + 1 and list(g["out_tok"][s, :tr["eta"] + 1]) == tr["emitted"]
             # --- commit: lengths and next-iteration state
@@ -134,6 +161,11 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
             stats["eta"].append(tr["eta"])
             stats["tokens"][s] += tr["emitted"]
         stats["iters"] += 1
+        for s in resync:
+            pend = sq[s].context[sq[s].n_cached:]
+            eng.resync(t_before, d_before, [sp[s].context[t_before[s]:len(sp[s].context) - 1]], [sq[s].context[d_before[s]:sq[s].n_cached]],
+                       [sp[s].context[-1]], [pend], [len(pend)])
+            stats["resyncs"] += 1
         if not any(alive):
             break
     status = _status(eng)

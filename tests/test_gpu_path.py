@@ -91,14 +91,18 @@ def test_workload_c1_full_run():
         print(f"C1 tau={tau}: {st['iters']} iterations, mean eta {np.mean(st['eta']):.2f}, max logit err {st['max_logit_err']:.2e}")
 
 
-def test_workload_c2_shape_short_run():
-    """C2 shapes (bf16, 12-layer target, vocab 32000), prompt 128, first 24 new tokens."""
+def test_workload_c2_full_run_in_lock_step():
+    """C2 as specified (bf16, 12-layer target, vocabulary 32000, prompt 128, gamma 4, beam 4), all 256 new tokens.  Random
+    models over 32000 tokens give nearly flat distributions, so some beam or bonus decision sits inside the logit
+    tolerance every few iterations; each time the HIP side is put back on the oracle's context, so every iteration of the
+    run is compared, each up to its first decision that legitimately differs."""
     w = si.WORKLOADS["C2"]
     wt, wd = si.make_weights(w.target, w.seed, "target"), si.make_weights(w.draft, w.seed, "draft")
-    st = run_pair(w.target, w.draft, wt, wd, si.make_prompt(w), 24, gamma=w.gamma, beam=w.beam, mode=w.mode, tau=w.tau,
-                  seed=w.seed)
-    assert st["iters"] >= 5
-    print(f"C2: {st['iters']} iterations, excused {st['excused']}, max logit err {st['max_logit_err']:.2e}")
+    st = run_pair(w.target, w.draft, wt, wd, si.make_prompt(w), w.new_tokens, gamma=w.gamma, beam=w.beam, mode=w.mode, tau=w.tau,
+                  seed=w.seed, lockstep=True)
+    print(f"C2: {st['iters']} iterations, {st['excused']} excused and put back, max logit err {st['max_logit_err']:.2e}")
+    assert len(st["tokens"][0]) >= w.new_tokens and st["iters"] >= w.new_tokens // (w.gamma + 1)
+    assert st["resyncs"] == st["excused"] and st["excused"] <= st["iters"] // 16, "more than one iteration in 16 parted"
 
 
 @pytest.mark.parametrize("fused_pass", [0, 2])
