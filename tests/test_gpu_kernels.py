@@ -125,6 +125,22 @@ def test_gemm_bf16_fragment_order_input(R, N, K):
     mb.mtad_destroy(ctx)
 
 
+def test_gemm_bf16_c5_gate_up_product_at_full_size():
+    """The largest product of C5's target pass at its real size: 164 rows (4 trees of 41) x 27648 gate/up features x 5120,
+    activations in fragment order, on the kernel the pass takes for it (8 strips per workgroup, 24 column groups, 64 KiB
+    of LDS): every element against the float64 product."""
+    mb = _mb()
+    w = si.WORKLOADS["C5"]
+    desc = lambda s: mb.mtad_model(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.head_dim, s.d_ffn, s.vocab, 1, s.rms_eps, s.rope_theta, None)
+    ctx = mb.mtad_create(mb.mtad_config(w.batch, w.gamma, w.beam, 1, 32, 256), desc(w.target), desc(w.draft))
+    ws = torch.empty(mb.mtad_workspace_bytes(ctx), dtype=torch.uint8, device=DEV)
+    mb.mtad_bind_workspace(ctx, ws)
+    R, N, K = w.batch * w.tree_rows, 2 * w.target.d_ffn, w.target.d_model
+    print(f"gemm bf16 C5 gate/up R={R} N={N} K={K}", flush=True)
+    _gemm_case(mb, R, N, K, 1, seed=5, ctx=ctx, x_order=mb.MTAD_X_FRAGMENTS)
+    mb.mtad_destroy(ctx)
+
+
 def test_gemm_accumulate_and_padded_rows():
     mb = _mb()
     _gemm_case(mb, 5, 64, 96, 1, seed=1, accumulate=True)
