@@ -272,6 +272,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     return p;
   };
 
+#ifdef MTAD_FLOW_PROFILE
+  if (threadIdx.x == 0 && A->prof)  // where this workgroup runs: (XCC id, hardware id word) behind the unit stamps
+    A->prof[4 * 90000 + blockIdx.x] = ((unsigned long long)__builtin_amdgcn_s_getreg((3 << 11) | 20) << 32) | (unsigned)__builtin_amdgcn_s_getreg((31 << 11) | 4);
+#endif
   int g = g_begin + (int)blockIdx.x;
   if (g >= g_end) return;
   FlowUnit cur = decode(g);

@@ -32,10 +32,12 @@ def close(got, want, dtype, what=""):
 
 def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, tau, sample_bonus=True,
              sample_beam=False, seed=0, max_context=None, page_size=16, prefill_rows=64, check_kv=False,
-             max_iters=None, device="cuda:0", fused_pass=None, warp=None, method="mtad", lockstep=False, oracle_seqs=None):
+             max_iters=None, device="cuda:0", fused_pass=None, warp=None, method="mtad", lockstep=False, oracle_seqs=None, lms=None, device_models=None):
     """method "spd": vanilla speculative decoding (beam 1, chain, token-wise acceptance) instead of the joint rule.
     oracle_seqs: the sequences compared with the oracle (default all).  The others must then carry the prompt of
     oracle_seqs[0] and a deterministic run (no sampling): their trees and logits are checked against that sequence's.
+    lms / device_models: prebuilt (target, draft) oracle models / uploaded models, for tests that run several
+    configurations on one large pair of weight sets.
     lockstep (one sequence): where the runs part on an excused near-tie, the HIP side is put back on the oracle's context
     (cache lengths reset to the iteration's start, the oracle's tokens appended, its state set) and the comparison goes
     on, so every iteration of the run is compared up to the first decision that legitimately differs."""
@@ -45,10 +47,11 @@ def run_pair(tshape, dshape, wt, wd, prompt, new_tokens, *, gamma, beam, mode, t
     dtype = tshape.dtype
     M = 1 + (gamma if mode == "mtad" else gamma * beam)
     max_context = max_context or (n0 + new_tokens + 2 * (gamma + 1) + M + 8)
-    eng = Engine(DeviceModel(tshape, wt, device), DeviceModel(dshape, wd, device), batch=B, gamma=gamma, beam=beam,
+    tm, dm = device_models if device_models is not None else (DeviceModel(tshape, wt, device), DeviceModel(dshape, wd, device))
+    eng = Engine(tm, dm, batch=B, gamma=gamma, beam=beam,
                  mode=mode, max_context=max_context, prefill_rows=prefill_rows, page_size=page_size, device=device, fused_pass=fused_pass,
                  warp=warp)
-    lm_p, lm_q = DecoderLM(tshape, wt), DecoderLM(dshape, wd)
+    lm_p, lm_q = lms if lms is not None else (DecoderLM(tshape, wt), DecoderLM(dshape, wd))
     sp = [CachedSession(lm_p, list(prompt[s])) for s in range(B)]
     sq = [CachedSession(lm_q, list(prompt[s])) for s in range(B)]
     oracle_seqs = list(range(B)) if oracle_seqs is None else list(oracle_seqs)

@@ -1,6 +1,6 @@
 """GPU checks at the full size of the benchmark workload (C3: 32-layer 7B-shaped target, 2-layer draft, prompt 512), in the
-launch configuration bench.py times.  The float64 oracle cannot run 32 layers at this width in seconds, so these are
-properties that hold at any size, each of them able to fail on a real mistake in the path:
+launch configuration bench.py times.  The float64 oracle cannot run 32 layers at this width over a 512-token prompt in
+seconds, so most of these are properties that hold at any size, each of them able to fail on a real mistake in the path:
 
 * per-row normalisation: the fused logsumexp equals the logsumexp of the logits the pass wrote, and every conditional
   log-likelihood is the gathered logit minus its parent row's logsumexp;
@@ -9,6 +9,10 @@ properties that hold at any size, each of them able to fail on a real mistake in
 * a cache built by tree passes and commits equals a cache built by prefilling the same tokens: the next-token logits agree;
 * the MMTAD tree contains the MTAD chain (the output beam, Section 3.3), so the conditional log-likelihoods along that
   path agree between the two passes although they run different kernels (5 rows against 17 rows under a tree mask).
+
+The last test does compare with the oracle at full depth: all 32 layers at full width over a 24-token prompt (the oracle
+holds the 6.6 G weights in float64, about 53 GB of host memory, and needs a few seconds per pass), two iterations of the
+5-row chain (the one-launch pass) and two of the 17-row tree (one kernel per step), every logit within the tolerance.
 """
 import numpy as np
 import pytest
@@ -134,3 +138,55 @@ def test_full_size_tree_pass_contains_the_chain_pass(models):
     assert _status(chain) == 0 and _status(tree) == 0
     chain.close()
     tree.close()
+
+
+def test_full_depth_c3_target_matches_oracle_on_a_short_prompt(models):
+    """32 layers, d 4096, FFN 11008, vocabulary 32000 against the float64 oracle, element by element: MTAD (5 rows, the
+    one-launch pass) and MMTAD (17 rows, three row groups, one kernel per step), in lock step."""
+    from _parity import run_pair
+    from oracle.lm import DecoderLM
+    w, tm, dm = models
+    print("C3 full depth: oracle weights (float64)", flush=True)
+    wt = si.make_weights(w.target, w.seed, "target", threads=16)
+    lm_p = DecoderLM(w.target, wt)
+    del wt
+    lm_q = DecoderLM(w.draft, si.make_weights(w.draft, w.seed, "draft", threads=16))
+    prompt = si.make_prompt(w)[:, :24]
+    for mode in ("mtad", "mmtad"):
+        print(f"C3 full depth: {mode} against the oracle", flush=True)
+        st = run_pair(w.target, w.draft, None, None, prompt, 2 * (w.gamma + 1), gamma=w.gamma, beam=w.beam, mode=mode, tau=0.0, seed=w.seed,
+                      max_iters=2, lockstep=True, lms=(lm_p, lm_q), device_models=(tm, dm))
+        print(f"C3 full depth {mode}: {st['iters']} iterations, {st['excused']} put back, max logit err {st['max_logit_err']:.2e}, parted: {st['events']}",
+              flush=True)
+        assert st["iters"] == 2 and st["iters"] - st["excused"] >= 1 and st["max_logit_err"] > 0
+        assert all(ev[3] < 5e-3 for ev in st["events"] if ev[0] == "beam step") and all(ev[-1] < 5e-3 for ev in st["events"] if ev[0] != "beam step")
+
+
+def test_full_depth_c5_pair_matches_oracle_on_a_short_prompt():
+    """C5 at full depth and width against the float64 oracle, element by element: 40-layer 13B-shaped target (164 rows per
+    pass: 4 trees of 8 beams x gamma 5 + root, the LDS-staged product kernels and 48-row attention items), 22-layer
+    grouped-query draft, 4 sequences with their own 24-token prompts; one whole iteration.  The oracle holds the target in
+    float64 (about 104 GB of host memory)."""
+    from _parity import run_pair
+    from oracle.lm import DecoderLM
+    from paper_2407_09722_amd.engine import DeviceModel
+    w = si.WORKLOADS["C5"]
+    print("C5 full depth: weights", flush=True)
+    wt = si.make_weights(w.target, w.seed, "target", threads=16)
+    tm = DeviceModel(w.target, wt, DEV)
+    lm_p = DecoderLM(w.target, wt)
+    del wt
+    wd = si.make_weights(w.draft, w.seed, "draft", threads=16)
+    dm = DeviceModel(w.draft, wd, DEV)
+    lm_q = DecoderLM(w.draft, wd)
+    del wd
+    prompt = si.make_prompt(w)[:, :24]
+    print("C5 full depth: one iteration against the oracle", flush=True)
+    st = run_pair(w.target, w.draft, None, None, prompt, w.gamma + 1, gamma=w.gamma, beam=w.beam, mode=w.mode, tau=0.0, seed=w.seed,
+                  max_iters=1, prefill_rows=32, lms=(lm_p, lm_q), device_models=(tm, dm))
+    print(f"C5 full depth: {st['iters']} iteration, {st['excused']} of 4 sequences parted, max logit err {st['max_logit_err']:.2e}, parted: {st['events']}",
+          flush=True)
+    assert st["iters"] == 1 and st["excused"] <= 2 and st["max_logit_err"] > 0
+    assert all(ev[3] < 5e-3 for ev in st["events"] if ev[0] == "beam step") and all(ev[-1] < 5e-3 for ev in st["events"] if ev[0] != "beam step")
+    del tm, dm, lm_p, lm_q
+    torch.cuda.empty_cache()
