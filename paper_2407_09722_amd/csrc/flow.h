@@ -1,5 +1,5 @@
 // The one-launch decoder pass for bf16 models with few rows (kernels_flow.hip): every product and the attention of
-// every layer as work units of ONE kernel, handed out in dependency order through a ticket counter.
+// every layer as work units of ONE kernel: numbered in dependency order, workgroup b of G runs units b, b + G, ...
 #pragma once
 #include "common.h"
 

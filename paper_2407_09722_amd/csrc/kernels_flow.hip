@@ -47,7 +47,6 @@ struct FlowSmem {
     MfmaAttnSmem<HD, 1, ATTN_WAVES, HD == 128 ? 2 : 1> attn;
   };
   float inv_s[8];
-  int ticket;
   int flag;
 };
 
