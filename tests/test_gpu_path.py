@@ -55,6 +55,21 @@ def test_both_pass_implementations(fused_pass):
     assert st["excused"] == 0
 
 
+@pytest.mark.parametrize("hd,gamma", [(64, 4), (128, 4), (64, 7), (128, 1)])
+def test_one_launch_pass_with_grouped_queries(hd, gamma):
+    """Four query heads per KV head.  With 5 or 8 rows that is more than 16 (head, row) pairs per KV head: the one-launch
+    pass then runs its attention as the stand-alone kernel between launches of the pass kernel (one launch up to a layer's
+    QKV step, one from its o product on); with 2 rows the attention stays inside.  8 rows fill the row group."""
+    ts = si.ModelShape(3, 256, 8, 2, hd, 352, 1024, "bf16")
+    ds = si.ModelShape(1, 128, 4, 1, hd, 160, 1024, "bf16")
+    wt, wd = _weights(ts, 17, "target", boost=4.0), _weights(ds, 17, "draft", boost=4.0)
+    prompt = np.random.default_rng(9).integers(0, ts.vocab, (1, 45)).astype(np.int32)
+    print(f"one-launch pass, grouped queries, head dim {hd}, gamma {gamma}", flush=True)
+    st = run_pair(ts, ds, wt, wd, prompt, 3 * (gamma + 1), gamma=gamma, beam=2, mode="mtad", tau=0.0, seed=5, prefill_rows=16, check_kv=True,
+                  fused_pass=2)
+    assert st["excused"] == 0 and all(e == gamma for e in st["eta"])
+
+
 def test_identical_models_accept_everything():
     """draft == target: every joint ratio is 1, so eta = gamma in every iteration for any tau < 1."""
     ts = SMALL["fp32"][0]
